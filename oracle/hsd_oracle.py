@@ -1,0 +1,275 @@
+"""Plain CPU oracle of HSD's verification pass.  TEST INFRASTRUCTURE ONLY.
+
+This file is the slow, obviously-correct definition that the HIP kernels are compared with.  It
+shares no code with them and is never used by the product path.
+
+What it computes (paper, Section 3.2 "Verification and acceptance", Eq. 8-12, in the linear-draft
+case the related-work section describes: one candidate continuation per sequence, so the prefix
+tree is a chain and the tree-ancestry mask is the causal mask):
+
+  * the target decoder's next-token distribution at every draft position in one causal forward
+    pass over [pending token, d_1 .. d_k] on top of the already accepted context (Eq. 8);
+  * the model's own top-1 token u_hat at every position (Eq. 10);
+  * exact greedy acceptance: descend while the draft token equals u_hat (Eq. 9 and Eq. 11 in the
+    limit tau -> 1, where log p(u*) - log p(u_hat) >= 0 holds only for u* = u_hat);
+  * the accepted-sequence update  y <- y + accepted path + u_hat at the stop node (Eq. 12);
+  * alpha = number of consecutive draft tokens accepted before the first mismatch, the quantity
+    averaged by the AAL metric (Eq. 15, Section 4.2).
+
+The decoder architecture is not fixed by the paper (it runs off-the-shelf checkpoints on the
+Hugging Face Transformers stack, Section 4.3), so the oracle implements the Llama family that
+stack defines: pre-norm RMSNorm, rotary embedding with rotate-half pairing, grouped-query causal
+attention, SwiGLU feed-forward, untied LM head, no biases.  tests/test_oracle_pins.py pins this
+forward against the Transformers implementation itself.
+
+Precision: every function takes `dtype` (default float64).  The paper states no precision.
+
+Pins (tests/test_oracle_pins.py, tests/test_oracle_invariants.py): Transformers' LlamaForCausalLM
+logits and greedy generation; torch's scaled_dot_product_attention, rms_norm and silu; complex-number
+form of the rotary embedding; pure-Python brute-force attention; the lossless invariant (verification
+rounds reproduce token-by-token greedy decoding exactly); closed-form alpha from the corruption
+positions.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+__all__ = [
+    "rmsnorm", "rope_rotate_half", "causal_gqa_attention", "swiglu", "KVCache", "decoder_forward",
+    "argmax_lowest_index", "top2_margin", "accept_longest_prefix", "verify_block", "greedy_decode",
+    "prefill", "spec_decode", "RoundRecord",
+]
+
+
+# ----------------------------------------------------------------------------------------------
+# Decoder building blocks (Llama family as defined by the Transformers stack, paper Section 4.3)
+# ----------------------------------------------------------------------------------------------
+
+def rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
+    """y = x / sqrt(mean(x^2) + eps) * gain, over the last axis."""
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * gain
+
+
+def rope_rotate_half(x: np.ndarray, positions: np.ndarray, theta: float) -> np.ndarray:
+    """Rotary position embedding with rotate-half pairing.
+
+    x: [n, heads, hd]; positions: [n] absolute token positions.  Dimension i (< hd/2) is paired
+    with dimension i + hd/2; the pair is rotated by angle pos * theta^(-2i/hd)."""
+    n, _, hd = x.shape
+    half = hd // 2
+    inv_freq = theta ** (-np.arange(half, dtype=x.dtype) * 2.0 / hd)
+    ang = positions.astype(x.dtype)[:, None] * inv_freq[None, :]          # [n, half]
+    cos = np.cos(ang)[:, None, :]
+    sin = np.sin(ang)[:, None, :]
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * cos - hi * sin, hi * cos + lo * sin], axis=-1)
+
+
+def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_pos0: int) -> np.ndarray:
+    """Softmax attention of a block of queries over a key/value history.
+
+    q: [Lq, Hq, hd] queries at absolute positions q_pos0 .. q_pos0+Lq-1.
+    k, v: [n_keys, Hkv, hd] keys/values at absolute positions 0 .. n_keys-1 (n_keys >= q_pos0+Lq).
+    Query at position p attends to keys at positions <= p.  Query head h uses kv head
+    h // (Hq // Hkv).  Scores are scaled by 1/sqrt(hd).  Returns [Lq, Hq, hd]."""
+    Lq, Hq, hd = q.shape
+    n_keys, Hkv, _ = k.shape
+    group = Hq // Hkv
+    out = np.empty_like(q)
+    key_pos = np.arange(n_keys)[None, :]
+    qry_pos = (q_pos0 + np.arange(Lq))[:, None]
+    allowed = key_pos <= qry_pos                                           # [Lq, n_keys]
+    for h in range(Hq):
+        kh = k[:, h // group, :]
+        vh = v[:, h // group, :]
+        s = (q[:, h, :] @ kh.T) / np.sqrt(np.asarray(hd, dtype=q.dtype))
+        s = np.where(allowed, s, -np.inf)
+        s = s - np.max(s, axis=-1, keepdims=True)
+        p = np.exp(s)
+        p = p / np.sum(p, axis=-1, keepdims=True)
+        out[:, h, :] = p @ vh
+    return out
+
+
+def swiglu(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
+    """silu(gate) * up with silu(x) = x / (1 + exp(-x))."""
+    return gate / (1.0 + np.exp(-gate)) * up
+
+
+class KVCache:
+    """Contiguous per-layer key/value history of ONE sequence (the oracle has no paging)."""
+
+    def __init__(self, n_layers: int, n_kv_heads: int, head_dim: int, dtype=np.float64):
+        self.k = [np.zeros((0, n_kv_heads, head_dim), dtype=dtype) for _ in range(n_layers)]
+        self.v = [np.zeros((0, n_kv_heads, head_dim), dtype=dtype) for _ in range(n_layers)]
+
+    def __len__(self) -> int:
+        return self.k[0].shape[0]
+
+    def truncate(self, n: int) -> None:
+        """Rollback: forget every position >= n."""
+        self.k = [a[:n] for a in self.k]
+        self.v = [a[:n] for a in self.v]
+
+
+def _cast_weights(weights: Dict, dtype) -> Dict:
+    cache = weights.setdefault("_cast", {})
+    key = np.dtype(dtype).name
+    if key not in cache:
+        cw = {n: np.asarray(weights[n], dtype=dtype) for n in ("tok_embed", "lm_head", "final_norm")}
+        cw["layers"] = [{n: np.asarray(a, dtype=dtype) for n, a in lay.items()} for lay in weights["layers"]]
+        cache[key] = cw
+    return cache[key]
+
+
+def decoder_forward(desc, weights: Dict, x_rows: np.ndarray, cache: KVCache, dtype=np.float64,
+                    want_logits: bool = True) -> Optional[np.ndarray]:
+    """Causal forward of the decoder over a block of new rows of one sequence.
+
+    x_rows: [n, d_model] input embeddings of the new rows (token rows already looked up).  The rows
+    sit at absolute positions len(cache) .. len(cache)+n-1.  Their keys/values are appended to
+    `cache`.  Returns logits [n, vocab] (or None when want_logits is False)."""
+    w = _cast_weights(weights, dtype)
+    x = np.asarray(x_rows, dtype=dtype).copy()
+    n = x.shape[0]
+    pos0 = len(cache)
+    positions = pos0 + np.arange(n)
+    Hq, Hkv, hd = desc.n_q_heads, desc.n_kv_heads, desc.head_dim
+    for l, lay in enumerate(w["layers"]):
+        h = rmsnorm(x, lay["attn_norm"], desc.rms_eps)
+        qkv = h @ lay["wqkv"].T
+        q = qkv[:, : Hq * hd].reshape(n, Hq, hd)
+        k = qkv[:, Hq * hd: (Hq + Hkv) * hd].reshape(n, Hkv, hd)
+        v = qkv[:, (Hq + Hkv) * hd:].reshape(n, Hkv, hd)
+        q = rope_rotate_half(q, positions, desc.rope_theta)
+        k = rope_rotate_half(k, positions, desc.rope_theta)
+        cache.k[l] = np.concatenate([cache.k[l], k], axis=0)
+        cache.v[l] = np.concatenate([cache.v[l], v], axis=0)
+        a = causal_gqa_attention(q, cache.k[l], cache.v[l], pos0)
+        x = x + a.reshape(n, Hq * hd) @ lay["wo"].T
+        h = rmsnorm(x, lay["ffn_norm"], desc.rms_eps)
+        gu = h @ lay["w_gate_up"].T
+        x = x + swiglu(gu[:, : desc.d_ffn], gu[:, desc.d_ffn:]) @ lay["w_down"].T
+    if not want_logits:
+        return None
+    return rmsnorm(x, w["final_norm"], desc.rms_eps) @ w["lm_head"].T
+
+
+def embed_tokens(weights: Dict, tokens: Sequence[int], dtype=np.float64) -> np.ndarray:
+    return _cast_weights(weights, dtype)["tok_embed"][np.asarray(tokens, dtype=np.int64)]
+
+
+# ----------------------------------------------------------------------------------------------
+# Acceptance (Eq. 9-12 with one candidate per node and exact match) and AAL's alpha (Eq. 15)
+# ----------------------------------------------------------------------------------------------
+
+def argmax_lowest_index(logits: np.ndarray) -> np.ndarray:
+    """u_hat per row (Eq. 10); among equal maxima the lowest token id wins."""
+    return np.argmax(logits, axis=-1).astype(np.int32)
+
+
+def top2_margin(logits: np.ndarray) -> np.ndarray:
+    """Largest minus second-largest logit per row (used only to gate parity comparisons)."""
+    part = np.partition(logits, -2, axis=-1)
+    return part[..., -1] - part[..., -2]
+
+
+def accept_longest_prefix(u_hat: np.ndarray, draft: np.ndarray) -> Tuple[int, int]:
+    """Greedy walk down the chain.
+
+    u_hat[i] is the model's top-1 after context + d_1..d_i (row 0 = after the pending token alone),
+    i = 0..k.  draft = (d_1..d_k).  Node i+1 is entered iff d_{i+1} == u_hat[i].  Returns
+    (alpha, bonus): alpha = number of draft tokens accepted, bonus = u_hat at the stop node."""
+    k = len(draft)
+    alpha = 0
+    while alpha < k and int(draft[alpha]) == int(u_hat[alpha]):
+        alpha += 1
+    return alpha, int(u_hat[alpha])
+
+
+def verify_block(desc, weights, cache: KVCache, pending: int, draft: np.ndarray, dtype=np.float64):
+    """One verification pass for one sequence.
+
+    cache holds the accepted context except its last token `pending` (whose keys/values are not
+    cached yet).  Feeds [pending, d_1..d_k] in one causal pass (Eq. 8), takes u_hat at every row
+    (Eq. 10), walks the chain (Eq. 9, 11) and returns (alpha, bonus, u_hat[k+1], logits[k+1,V]).
+    All k+1 rows are appended to the cache; the caller commits by truncating to
+    len_before + 1 + alpha."""
+    block = np.concatenate([[pending], np.asarray(draft, dtype=np.int64)]).astype(np.int64)
+    logits = decoder_forward(desc, weights, embed_tokens(weights, block, dtype), cache, dtype)
+    u_hat = argmax_lowest_index(logits)
+    alpha, bonus = accept_longest_prefix(u_hat, draft)
+    return alpha, bonus, u_hat, logits
+
+
+def prefill(desc, weights, visual: np.ndarray, prompt: Sequence[int], dtype=np.float64):
+    """Build the cache for [visual rows, prompt tokens except the last]; the last prompt token is
+    returned as the pending token.  With an empty prompt the pending token is id 0 and all visual
+    rows are cached."""
+    cache = KVCache(desc.n_layers, desc.n_kv_heads, desc.head_dim, dtype)
+    prompt = np.asarray(prompt, dtype=np.int64)
+    if len(prompt) == 0:
+        rows, pending = np.asarray(visual, dtype=dtype), 0
+    else:
+        rows = np.concatenate([np.asarray(visual, dtype=dtype), embed_tokens(weights, prompt[:-1], dtype)], axis=0)
+        pending = int(prompt[-1])
+    if rows.shape[0]:
+        decoder_forward(desc, weights, rows, cache, dtype, want_logits=False)
+    return cache, pending
+
+
+def greedy_decode(desc, weights, cache: KVCache, pending: int, n_tokens: int, dtype=np.float64,
+                  return_margins: bool = False):
+    """Plain autoregressive decoding, one token per forward pass: the definition that verification
+    must reproduce.  Returns the n_tokens generated tokens (and each step's top-1/top-2 margin)."""
+    out, margins = [], []
+    tok = pending
+    for _ in range(n_tokens):
+        logits = decoder_forward(desc, weights, embed_tokens(weights, [tok], dtype), cache, dtype)
+        tok = int(argmax_lowest_index(logits)[0])
+        out.append(tok)
+        if return_margins:
+            margins.append(float(top2_margin(logits)[0]))
+    res = np.asarray(out, dtype=np.int32)
+    return (res, np.asarray(margins)) if return_margins else res
+
+
+@dataclass
+class RoundRecord:
+    offset: int            # index into the full draft of d_1 of this round
+    k: int                 # draft tokens scored this round
+    alpha: int
+    bonus: int
+    u_hat: np.ndarray      # [k+1]
+    margins: np.ndarray    # [k+1] top-1/top-2 margins of the rows
+
+
+def spec_decode(desc, weights, cache: KVCache, pending: int, draft: np.ndarray, n_commit: int,
+                dtype=np.float64, max_block: Optional[int] = None):
+    """SpecDecode (Eq. 1) for one sequence with a single fixed, index-aligned draft.
+
+    Repeats verification passes until n_commit tokens are committed.  The draft stays fixed (it
+    is produced once, Section 3.2); because the synthetic corruption only substitutes tokens, the
+    draft stays aligned by index: after a round that started at draft offset o and accepted alpha
+    tokens, alpha+1 tokens are committed (Eq. 12) and the next round's draft starts at
+    o + alpha + 1.  Returns (committed tokens [n_commit], list of RoundRecord)."""
+    draft = np.asarray(draft, dtype=np.int32)
+    committed: List[int] = []
+    rounds: List[RoundRecord] = []
+    while len(committed) < n_commit:
+        o = len(committed)
+        rest = draft[o:]
+        if max_block is not None:
+            rest = rest[: max_block]
+        base = len(cache)
+        alpha, bonus, u_hat, logits = verify_block(desc, weights, cache, pending, rest, dtype)
+        cache.truncate(base + 1 + alpha)                      # commit accepted rows, roll back the rest
+        committed.extend(int(t) for t in rest[:alpha])
+        committed.append(bonus)
+        rounds.append(RoundRecord(o, len(rest), alpha, bonus, u_hat, top2_margin(logits)))
+        pending = bonus
+    return np.asarray(committed[:n_commit], dtype=np.int32), rounds
