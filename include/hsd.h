@@ -1,0 +1,172 @@
+/*
+ * hsd.h -- C ABI of the HSD verification hot path for AMD MI355X (gfx950).
+ *
+ * The library runs the target decoder's *verification pass* of Hierarchical Speculative Decoding:
+ * one forward pass of the decoder over every sequence's block [pending token, d_1 .. d_k] on top of
+ * the sequence's accepted context held in a paged KV cache (paper Section 3.2, Eq. 8), the model's own
+ * top-1 token at every row (Eq. 10), greedy acceptance of the longest draft prefix that matches it
+ * (Eq. 9 and Eq. 11 taken at tau -> 1, i.e. exact match; the linear-draft case in which the prefix
+ * tree is a chain and the tree-ancestry mask is the causal mask), and the bonus token of Eq. 12.
+ * Stage 1 (many short region drafts verified together, Eq. 2) and Stage 2 (one long page draft, Eq. 4)
+ * are the same operator on different shapes, hence two entry points with one semantic definition.
+ *
+ * Conventions
+ *  - "dev" pointers are device (HBM) pointers owned by the caller; the library never allocates or
+ *    frees device memory and keeps no device state besides what the caller hands in.
+ *  - Every call that takes a stream only enqueues work on it and returns; it never synchronises.
+ *  - Return value: HSD_OK (0) or a negative hsd_status.  Argument errors are found on the host
+ *    before anything is launched.  Conditions that only the device can see (KV pool exhausted,
+ *    block table too short) set bits in hsd_batch.status and leave the affected sequence's outputs
+ *    unspecified -- but never touch memory outside the caller's buffers.
+ *  - Linear weights are row-major [out_features, in_features] (y = x W^T), in the model dtype
+ *    (bf16 or fp32).  RMSNorm gains are always fp32.
+ *  - All integer arrays are int32.
+ */
+#ifndef HSD_H_
+#define HSD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum hsd_status {
+  HSD_OK = 0,
+  HSD_EINVAL = -1,  /* null pointer, non-positive size, unsupported dimension or dtype            */
+  HSD_ENOSPC = -2,  /* workspace too small                                                       */
+  HSD_ERANGE = -3,  /* a size exceeds a documented maximum                                       */
+  HSD_EARCH = -4,   /* current device is not gfx950                                              */
+  HSD_ENODEV = -5,  /* no usable HIP device                                                      */
+  HSD_EHIP = -6     /* a HIP runtime call (launch, attribute query) failed                       */
+} hsd_status;
+
+enum { HSD_FP32 = 0, HSD_BF16 = 1 };
+
+/* bits of hsd_batch.status (device-side conditions) */
+enum {
+  HSD_STATUS_POOL_EXHAUSTED = 1, /* not enough free KV blocks for the speculative append */
+  HSD_STATUS_TABLE_OVERFLOW = 2, /* seq_len + q_len exceeds max_blocks_per_seq * 16       */
+  HSD_STATUS_BAD_SLOT = 4        /* a seq_slot entry lies outside [0, n_slots)           */
+};
+
+enum { HSD_KV_BLOCK_TOKENS = 16, HSD_HEAD_DIM = 64, HSD_MAX_SEQ = 4096 };
+
+/* Decoder dimensions (Llama family: pre-norm RMSNorm, rotate-half RoPE, GQA, SwiGLU, untied head).
+ * Requirements: head_dim == 64, kv_block_tokens == 16, n_q_heads % n_kv_heads == 0,
+ * d_model, d_ffn and vocab multiples of 128. */
+typedef struct hsd_model_desc {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  int32_t dtype; /* HSD_BF16 or HSD_FP32: storage type of weights, KV cache and GEMM operands */
+  int32_t kv_block_tokens;
+  float rms_eps, rope_theta;
+} hsd_model_desc;
+
+/* Weights.  The per-layer members are HOST arrays of n_layers device pointers (copied by hsd_create). */
+typedef struct hsd_weights {
+  const void *tok_embed;         /* dev [vocab, d_model]                                   */
+  const float *final_norm;       /* dev [d_model] fp32                                     */
+  const void *lm_head;           /* dev [vocab, d_model]                                   */
+  const float *const *attn_norm; /* [n_layers] -> dev [d_model] fp32                       */
+  const void *const *wqkv;       /* -> dev [(n_q+2 n_kv) * 64, d_model]; rows q | k | v     */
+  const void *const *wo;         /* -> dev [d_model, n_q * 64]                             */
+  const float *const *ffn_norm;  /* -> dev [d_model] fp32                                  */
+  const void *const *w_gate_up;  /* -> dev [2 * d_ffn, d_model]; rows gate | up             */
+  const void *const *w_down;     /* -> dev [d_model, d_ffn]                                */
+} hsd_weights;
+
+/* Paged KV cache.  k_pool and v_pool: dev [n_layers][n_blocks][n_kv_heads][16][64] in the model dtype.
+ * free_list is a stack of free block ids, free_count its height; both live on the device and are
+ * maintained by the library (hsd_kv_pool_init, verify, commit). */
+typedef struct hsd_kv_pool {
+  void *k_pool, *v_pool;
+  int32_t n_blocks;
+  int32_t *free_list;  /* dev [n_blocks] */
+  int32_t *free_count; /* dev [1]        */
+} hsd_kv_pool;
+
+/* One verification round over a packed, ragged batch of sequences (regions or pages).
+ * Sequence s owns rows cu_q[s] .. cu_q[s+1]-1 of the packed arrays; its block is
+ * [pending token, d_1 .. d_k], q_len = k+1 >= 1, at absolute positions L .. L+k with L = seq_len[slot(s)].
+ * The per-sequence state (seq_len, block_table) persists across rounds in rows addressed by seq_slot, so a
+ * round may verify any subset of the live sequences; the per-round outputs are indexed by s. */
+typedef struct hsd_batch {
+  int32_t n_seq;              /* 1 .. HSD_MAX_SEQ                                                     */
+  int32_t total_q;            /* cu_q[n_seq]; number of packed rows                                   */
+  int32_t max_blocks_per_seq; /* row length of block_table                                            */
+  int32_t n_slots;            /* rows of the persistent per-sequence state (seq_len, block_table)     */
+  const int32_t *cu_q;        /* dev [n_seq+1], increasing, cu_q[0] = 0                               */
+  const int32_t *seq_slot;    /* dev [n_seq]: state row used by batch sequence s (distinct entries),  */
+                              /*   or NULL for the identity (then n_slots >= n_seq)                   */
+  const int32_t *tokens;      /* dev [total_q]; a negative id means: take row r of `embeds` instead   */
+  const float *embeds;        /* dev [total_q, d_model] fp32 input rows, or NULL if no id is negative */
+  int32_t *seq_len;           /* dev [n_slots] committed KV length; read by verify, updated by commit */
+  int32_t *block_table;       /* dev [n_slots][max_blocks_per_seq]; -1 = entry owns no block          */
+  int32_t *argmax;            /* dev out [total_q] model top-1 per row (lowest id among equal maxima); */
+                              /*   NULL => skip LM head and acceptance (prefill)                      */
+  float *top2_margin;         /* dev out [total_q] top-1 minus top-2 logit, or NULL                   */
+  int32_t *accept_len;        /* dev out [n_seq] alpha in [0, k]; input of commit                     */
+  int32_t *bonus;             /* dev out [n_seq] argmax[cu_q[s] + alpha]; input of commit             */
+  int32_t *status;            /* dev [1] in/out: HSD_STATUS_* bits are OR-ed in; caller clears        */
+  float *logits_dump;         /* dev out [n_dump, vocab] fp32 logits of selected rows (debug) or NULL */
+  const int32_t *dump_rows;   /* dev [n_dump] packed row indices                                      */
+  int32_t n_dump;
+} hsd_batch;
+
+typedef struct hsd_ctx hsd_ctx; /* opaque; host memory only (descriptor + copied pointer tables) */
+
+const char *hsd_status_string(int status);
+
+/* Pure host check of a descriptor / batch / pool / workspace size; what the verify calls run first.
+ * Never dereferences a device pointer.  `pool` may be NULL to check the batch alone. */
+int hsd_validate_model(const hsd_model_desc *desc);
+int hsd_validate_batch(const hsd_model_desc *desc, const hsd_kv_pool *pool, const hsd_batch *batch,
+                       size_t ws_bytes);
+
+/* Creates a context for the current HIP device (must be gfx950).  Copies desc and the pointer tables;
+ * the weight buffers themselves stay owned by the caller and must outlive the context. */
+int hsd_create(const hsd_model_desc *desc, const hsd_weights *weights, hsd_ctx **out);
+void hsd_destroy(hsd_ctx *ctx);
+
+/* Device workspace needed by a verify/prefill call with total_q <= max_total_q, n_seq <= max_n_seq
+ * (from the descriptor alone, so it can be called before hsd_create). */
+size_t hsd_workspace_bytes(const hsd_model_desc *desc, int32_t max_total_q, int32_t max_n_seq);
+
+/* Marks every block free (free_list = all ids, free_count = n_blocks). */
+int hsd_kv_pool_init(void *stream, const hsd_kv_pool *pool);
+
+/* Region-level verification (paper Section 3.1 Stage 1, Eq. 2): many short ragged draft blocks.
+ * For every sequence: takes KV blocks from the pool for positions seq_len .. seq_len+q_len-1
+ * (writing their ids into block_table), appends the keys/values of ALL q_len rows there
+ * (speculatively), computes argmax for every row, then alpha = number of leading draft tokens with
+ * tokens[base+i] == argmax[base+i-1], and bonus = argmax[base+alpha] (Eq. 9-12, exact match).
+ * seq_len is not modified: call hsd_kv_commit_rollback afterwards. */
+int hsd_verify_region_batch(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch,
+                            void *workspace, size_t ws_bytes);
+
+/* Page-level verification (Section 3.1 Stage 2, Eq. 4): few long draft blocks.  Same semantics and
+ * outputs as hsd_verify_region_batch; the kernels are tiled for long blocks. */
+int hsd_verify_page(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch,
+                    void *workspace, size_t ws_bytes);
+
+/* KV maintenance after a verify (the "accept/reject control flow, rollbacks, KV-cache maintenance"
+ * part of the decoding loop, Section 4.2).  For each sequence with accept_len[s] = alpha >= 0:
+ * seq_len += 1 + alpha (the pending token and the accepted draft tokens become committed context);
+ * pending_out[s] = bonus[s].  With alpha < 0: pure rollback, seq_len and pending_out[s] unchanged.
+ * In both cases blocks lying wholly beyond the new length go back to the pool and their
+ * block_table slots become -1; rejected rows inside the last kept block are simply overwritten by
+ * the next round.  pending_out: dev [n_seq] or NULL. */
+int hsd_kv_commit_rollback(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch,
+                           int32_t *pending_out);
+
+/* Set-up helper (not part of the timed loop): forward pass without LM head over the given rows
+ * (batch.argmax and the acceptance outputs are ignored), then commits every row:
+ * seq_len += q_len.  Used to build the visual/prompt prefix. */
+int hsd_prefill(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch,
+                void *workspace, size_t ws_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HSD_H_ */

@@ -1,0 +1,135 @@
+// Shared device helpers for the HSD verification kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/hsd.h"
+
+namespace hsd {
+
+constexpr int kWave = 64;        // CDNA wavefront width
+constexpr int kHd = HSD_HEAD_DIM;
+constexpr int kBlk = HSD_KV_BLOCK_TOKENS;
+
+// bf16 is handled as raw 16-bit patterns; arithmetic is always fp32.
+struct bf16 {
+  uint16_t v;
+};
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+
+// round-to-nearest-even; inputs on this path are finite
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16 x) { return bf16_to_f32(x.v); }
+
+template <typename T>
+__device__ __forceinline__ T from_f32(float x);
+template <>
+__device__ __forceinline__ float from_f32<float>(float x) {
+  return x;
+}
+template <>
+__device__ __forceinline__ bf16 from_f32<bf16>(float x) {
+  bf16 r;
+  r.v = f32_to_bf16(x);
+  return r;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// Per-row top-2 record used by the LM-head arg-max: largest value m1 at index i1 (lowest index among
+// equal maxima), second largest value m2 (may equal m1 when the maximum occurs twice).
+struct Top2 {
+  float m1;
+  int i1;
+  float m2;
+};
+
+__device__ __forceinline__ Top2 top2_init() { return Top2{-INFINITY, 0x7fffffff, -INFINITY}; }
+
+__device__ __forceinline__ void top2_push(Top2 &t, float v, int idx) {
+  if (v > t.m1 || (v == t.m1 && idx < t.i1)) {
+    t.m2 = t.m1;
+    t.m1 = v;
+    t.i1 = idx;
+  } else if (v > t.m2) {
+    t.m2 = v;
+  }
+}
+
+__device__ __forceinline__ Top2 top2_merge(const Top2 &a, const Top2 &b) {
+  Top2 r;
+  bool a_first = (a.m1 > b.m1) || (a.m1 == b.m1 && a.i1 <= b.i1);
+  if (a_first) {
+    r.m1 = a.m1;
+    r.i1 = a.i1;
+    r.m2 = fmaxf(a.m2, b.m1);
+  } else {
+    r.m1 = b.m1;
+    r.i1 = b.i1;
+    r.m2 = fmaxf(b.m2, a.m1);
+  }
+  return r;
+}
+
+// State row (seq_len / block_table row) of batch sequence s; out-of-range entries are clamped so that no
+// kernel can index outside the state arrays (the reservation kernel reports them in the status word).
+__device__ __forceinline__ int slot_of(const int32_t *seq_slot, int s, int n_slots) {
+  int sl = seq_slot ? seq_slot[s] : s;
+  return sl < 0 ? 0 : (sl >= n_slots ? n_slots - 1 : sl);
+}
+
+// Per-row metadata built once per pass.
+struct RowMeta {
+  const int32_t *row_seq;  // [T] state row (slot) of the row's sequence
+  const int32_t *row_pos;  // [T] absolute position of the row in its sequence
+  const float2 *rope_cs;   // [T][32] (cos, sin) of pos * theta^(-2i/64)
+};
+
+// Everything a kernel needs to find a (sequence, position) slot in the paged pools.
+struct PagedKV {
+  void *k_pool;
+  void *v_pool;
+  const int32_t *block_table;
+  int32_t max_blocks_per_seq;
+  int32_t n_blocks;
+  int32_t n_kv_heads;
+  int32_t layer;
+};
+
+// Element offset of (layer, block, kv head, slot 0, dim 0) in a pool laid out
+// [n_layers][n_blocks][n_kv_heads][16][64].
+__device__ __forceinline__ size_t kv_block_offset(const PagedKV &kv, int block, int kvh) {
+  return ((static_cast<size_t>(kv.layer) * kv.n_blocks + block) * kv.n_kv_heads + kvh) * (kBlk * kHd);
+}
+
+// Block id holding position `pos` of sequence s, or -1 if the table has no valid block there.
+__device__ __forceinline__ int kv_lookup_block(const PagedKV &kv, int s, int pos) {
+  int bi = pos / kBlk;
+  if (bi >= kv.max_blocks_per_seq) return -1;
+  int b = kv.block_table[static_cast<size_t>(s) * kv.max_blocks_per_seq + bi];
+  return (b >= 0 && b < kv.n_blocks) ? b : -1;
+}
+
+}  // namespace hsd

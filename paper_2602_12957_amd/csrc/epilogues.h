@@ -1,0 +1,96 @@
+// GEMM epilogues of the verification forward.  Every GEMM kernel (plain fp32-FMA and bf16 MFMA) hands
+// its accumulators to one of these functors as column PAIRS (n, n+32) of the same row: a 64-aligned group
+// of output columns is exactly one attention head, so the rotate-half partner of dimension i (i + 32) is
+// always in the same thread.  For the SwiGLU GEMM the kernel accumulates the gate and the up projection
+// of the same output column side by side.
+#pragma once
+
+#include "common.h"
+
+namespace hsd {
+
+// C = A W^T for the QKV projection, then rotary embedding on q and k heads, q to the packed q buffer,
+// k and v appended to the paged cache at the row's absolute position (speculative append).
+template <typename T>
+struct EpiQKV {
+  static constexpr bool kDual = false;
+  int n_q_heads, n_kv_heads;
+  RowMeta meta;
+  PagedKV kv;
+  T *q_out;  // [T, n_q_heads*64]
+
+  __device__ __forceinline__ void pair(int m, int n, float lo, float hi) const {
+    int head = n >> 6, dim = n & 63;  // dim in [0, 32)
+    if (head < n_q_heads + n_kv_heads) {
+      float2 cs = meta.rope_cs[static_cast<size_t>(m) * 32 + dim];
+      float rlo = lo * cs.x - hi * cs.y;
+      float rhi = hi * cs.x + lo * cs.y;
+      lo = rlo;
+      hi = rhi;
+    }
+    if (head < n_q_heads) {
+      T *dst = q_out + static_cast<size_t>(m) * (n_q_heads * kHd) + head * kHd + dim;
+      dst[0] = from_f32<T>(lo);
+      dst[32] = from_f32<T>(hi);
+      return;
+    }
+    int s = meta.row_seq[m], pos = meta.row_pos[m];
+    int b = kv_lookup_block(kv, s, pos);
+    if (b < 0) return;
+    bool is_k = head < n_q_heads + n_kv_heads;
+    int kvh = is_k ? head - n_q_heads : head - n_q_heads - n_kv_heads;
+    T *pool = static_cast<T *>(is_k ? kv.k_pool : kv.v_pool);
+    T *dst = pool + kv_block_offset(kv, b, kvh) + (pos % kBlk) * kHd + dim;
+    dst[0] = from_f32<T>(lo);
+    dst[32] = from_f32<T>(hi);
+  }
+};
+
+// x += A W^T (fp32 residual stream, each element owned by one thread: deterministic).
+struct EpiResidual {
+  static constexpr bool kDual = false;
+  float *x;
+  int ld;
+  __device__ __forceinline__ void pair(int m, int n, float lo, float hi) const {
+    float *p = x + static_cast<size_t>(m) * ld + n;
+    p[0] += lo;
+    p[32] += hi;
+  }
+};
+
+// u = silu(A Wg^T) * (A Wu^T), written in the GEMM operand type.
+template <typename T>
+struct EpiSwiGLU {
+  static constexpr bool kDual = true;
+  T *u;
+  int ld;
+  __device__ __forceinline__ static float f(float g, float up) { return g / (1.0f + __expf(-g)) * up; }
+  __device__ __forceinline__ void pair2(int m, int n, float g_lo, float g_hi, float u_lo, float u_hi) const {
+    T *p = u + static_cast<size_t>(m) * ld + n;
+    p[0] = from_f32<T>(f(g_lo, u_lo));
+    p[32] = from_f32<T>(f(g_hi, u_hi));
+  }
+};
+
+// LM head: logits never reach memory.  Each thread folds its accumulators into a Top2 record; the
+// kernel reduces the records of one row within the column tile and stores one record per (row, tile).
+struct EpiLMHead {
+  static constexpr bool kDual = false;
+  Top2 *part;  // [T][n_tiles]
+  int n_tiles;
+  int vocab;
+  const int32_t *dump_slot;  // [T] or nullptr
+  float *logits_dump;        // [n_dump][vocab]
+  __device__ __forceinline__ void dump(int m, int n, float lo, float hi) const {
+    if (dump_slot != nullptr) {
+      int sl = dump_slot[m];
+      if (sl >= 0) {
+        float *p = logits_dump + static_cast<size_t>(sl) * vocab + n;
+        p[0] = lo;
+        p[32] = hi;
+      }
+    }
+  }
+};
+
+}  // namespace hsd

@@ -1,0 +1,312 @@
+// C ABI of the HSD verification hot path: argument validation, workspace carving, launch sequencing.
+// All device work is enqueued on the caller's stream; nothing here synchronises or allocates device memory.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <type_traits>
+#include <vector>
+
+#include "../../include/hsd.h"
+#include "attn_simple.h"
+#include "common.h"
+#include "epilogues.h"
+#include "gemm_simple.h"
+#include "misc_kernels.h"
+
+using namespace hsd;
+
+struct hsd_ctx {
+  hsd_model_desc desc;
+  const void *tok_embed;
+  const float *final_norm;
+  const void *lm_head;
+  std::vector<const float *> attn_norm, ffn_norm;
+  std::vector<const void *> wqkv, wo, w_gate_up, w_down;
+  int n_cu;
+  bool force_simple;
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Workspace {
+  float *x;
+  void *h, *q, *a, *u;
+  int32_t *row_seq, *row_pos, *dump_slot;
+  float2 *rope_cs;
+  Top2 *lm_part;
+  size_t total;
+};
+
+// Carves the workspace; with base == nullptr only the size is computed.
+Workspace carve(const hsd_model_desc &d, int64_t T, int64_t /*n_seq*/, void *base) {
+  const size_t es = d.dtype == HSD_BF16 ? 2 : 4;
+  const size_t qdim = static_cast<size_t>(d.n_q_heads) * d.head_dim;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += align_up(bytes);
+    return base ? static_cast<char *>(base) + o : nullptr;
+  };
+  Workspace w;
+  w.x = reinterpret_cast<float *>(take(T * d.d_model * sizeof(float)));
+  w.h = take(T * d.d_model * es);
+  w.q = take(T * qdim * es);
+  w.a = take(T * qdim * es);
+  w.u = take(T * d.d_ffn * es);
+  w.row_seq = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
+  w.row_pos = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
+  w.dump_slot = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
+  w.rope_cs = reinterpret_cast<float2 *>(take(T * 32 * sizeof(float2)));
+  w.lm_part = reinterpret_cast<Top2 *>(take(T * (d.vocab / 64) * sizeof(Top2)));
+  w.total = off;
+  return w;
+}
+
+#define HSD_LAUNCH_CHECK()                         \
+  do {                                             \
+    if (hipGetLastError() != hipSuccess) return HSD_EHIP; \
+  } while (0)
+
+template <typename T, typename Epi>
+int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int M, int N, int K, const void *A, const void *W, const Epi &epi) {
+  (void)ctx;
+  dim3 grid(N / 64, (M + 63) / 64);
+  hipLaunchKernelGGL((k_gemm_simple<T, Epi>), grid, dim3(256), 0, st, M, N, K, static_cast<const T *>(A),
+                     static_cast<const T *>(W), epi);
+  HSD_LAUNCH_CHECK();
+  return HSD_OK;
+}
+
+template <typename T>
+int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_batch *b, void *ws_base, bool page_mode,
+            bool with_head) {
+  (void)page_mode;
+  const hsd_model_desc &d = ctx->desc;
+  const int Tq = b->total_q;
+  Workspace ws = carve(d, Tq, b->n_seq, ws_base);
+  const int qdim = d.n_q_heads * d.head_dim, kvdim = d.n_kv_heads * d.head_dim;
+  int rc;
+
+  hipLaunchKernelGGL(k_row_meta, dim3((Tq * 32 + 255) / 256), dim3(256), 0, st, b->n_seq, Tq, b->cu_q, b->seq_slot,
+                     b->n_slots, b->seq_len, d.rope_theta, ws.row_seq, ws.row_pos, ws.rope_cs);
+  HSD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_kv_reserve, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, b->seq_slot, b->n_slots,
+                     b->seq_len, b->block_table, b->max_blocks_per_seq, pool->n_blocks, pool->free_list,
+                     pool->free_count, b->status);
+  HSD_LAUNCH_CHECK();
+  hipLaunchKernelGGL((k_embed<T>), dim3(Tq), dim3(256), 0, st, d.d_model, d.vocab, b->tokens, b->embeds,
+                     static_cast<const T *>(ctx->tok_embed), ws.x);
+  HSD_LAUNCH_CHECK();
+
+  RowMeta meta{ws.row_seq, ws.row_pos, ws.rope_cs};
+  for (int l = 0; l < d.n_layers; ++l) {
+    PagedKV kv{pool->k_pool, pool->v_pool, b->block_table, b->max_blocks_per_seq, pool->n_blocks, d.n_kv_heads, l};
+    hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
+                       ctx->attn_norm[l], static_cast<T *>(ws.h));
+    HSD_LAUNCH_CHECK();
+    EpiQKV<T> eq{d.n_q_heads, d.n_kv_heads, meta, kv, static_cast<T *>(ws.q)};
+    if ((rc = launch_gemm<T>(ctx, st, Tq, qdim + 2 * kvdim, d.d_model, ws.h, ctx->wqkv[l], eq))) return rc;
+    hipLaunchKernelGGL((k_attn_simple<T>), dim3(Tq, (d.n_q_heads + 3) / 4), dim3(256), 0, st, d.n_q_heads, meta, kv,
+                       static_cast<const T *>(ws.q), static_cast<T *>(ws.a));
+    HSD_LAUNCH_CHECK();
+    EpiResidual er{ws.x, d.d_model};
+    if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_model, qdim, ws.a, ctx->wo[l], er))) return rc;
+    hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
+                       ctx->ffn_norm[l], static_cast<T *>(ws.h));
+    HSD_LAUNCH_CHECK();
+    EpiSwiGLU<T> es{static_cast<T *>(ws.u), d.d_ffn};
+    if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_ffn, d.d_model, ws.h, ctx->w_gate_up[l], es))) return rc;
+    if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_model, d.d_ffn, ws.u, ctx->w_down[l], er))) return rc;
+  }
+  if (!with_head) return HSD_OK;
+
+  hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
+                     ctx->final_norm, static_cast<T *>(ws.h));
+  HSD_LAUNCH_CHECK();
+  const int32_t *dump_slot = nullptr;
+  if (b->n_dump > 0 && b->logits_dump != nullptr) {
+    hipLaunchKernelGGL(k_fill_i32, dim3((Tq + 255) / 256), dim3(256), 0, st, ws.dump_slot, Tq, -1);
+    HSD_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_dump_slots, dim3((b->n_dump + 255) / 256), dim3(256), 0, st, b->dump_rows, b->n_dump, Tq,
+                       ws.dump_slot);
+    HSD_LAUNCH_CHECK();
+    dump_slot = ws.dump_slot;
+  }
+  const int n_tiles = d.vocab / 64;
+  EpiLMHead el{ws.lm_part, n_tiles, d.vocab, dump_slot, b->logits_dump};
+  if ((rc = launch_gemm<T>(ctx, st, Tq, d.vocab, d.d_model, ws.h, ctx->lm_head, el))) return rc;
+  hipLaunchKernelGGL(k_lm_reduce, dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, n_tiles, ws.lm_part, b->argmax,
+                     b->top2_margin);
+  HSD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_accept, dim3((b->n_seq + 3) / 4), dim3(256), 0, st, b->n_seq, b->cu_q, b->tokens, b->argmax,
+                     b->accept_len, b->bonus);
+  HSD_LAUNCH_CHECK();
+  return HSD_OK;
+}
+
+int verify_common(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *b, void *ws, size_t ws_bytes,
+                  bool page_mode, bool prefill) {
+  if (ctx == nullptr || ws == nullptr) return HSD_EINVAL;
+  int rc = hsd_validate_batch(&ctx->desc, pool, b, ws_bytes);
+  if (rc != HSD_OK) return rc;
+  if (pool == nullptr) return HSD_EINVAL;
+  if (!prefill && (b->argmax == nullptr || b->accept_len == nullptr || b->bonus == nullptr)) return HSD_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool with_head = !prefill;
+  if (ctx->desc.dtype == HSD_BF16)
+    rc = forward<bf16>(ctx, st, pool, b, ws, page_mode, with_head);
+  else
+    rc = forward<float>(ctx, st, pool, b, ws, page_mode, with_head);
+  if (rc != HSD_OK) return rc;
+  if (prefill) {
+    hipLaunchKernelGGL(k_kv_commit, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, b->seq_slot, b->n_slots,
+                       b->seq_len, b->block_table, b->max_blocks_per_seq, pool->n_blocks, pool->free_list,
+                       pool->free_count, static_cast<const int32_t *>(nullptr), static_cast<const int32_t *>(nullptr),
+                       static_cast<int32_t *>(nullptr), 1);
+    HSD_LAUNCH_CHECK();
+  }
+  return HSD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *hsd_status_string(int status) {
+  switch (status) {
+    case HSD_OK: return "ok";
+    case HSD_EINVAL: return "invalid argument";
+    case HSD_ENOSPC: return "workspace too small";
+    case HSD_ERANGE: return "size out of range";
+    case HSD_EARCH: return "device is not gfx950";
+    case HSD_ENODEV: return "no HIP device";
+    case HSD_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int hsd_validate_model(const hsd_model_desc *d) {
+  if (d == nullptr) return HSD_EINVAL;
+  if (d->n_layers < 1 || d->d_model < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->d_ffn < 1 || d->vocab < 1)
+    return HSD_EINVAL;
+  if (d->head_dim != HSD_HEAD_DIM || d->kv_block_tokens != HSD_KV_BLOCK_TOKENS) return HSD_EINVAL;
+  if (d->dtype != HSD_BF16 && d->dtype != HSD_FP32) return HSD_EINVAL;
+  if (d->n_q_heads % d->n_kv_heads != 0) return HSD_EINVAL;
+  if (d->d_model % 128 != 0 || d->d_ffn % 128 != 0 || d->vocab % 128 != 0) return HSD_EINVAL;
+  if (!(d->rms_eps > 0.f) || !(d->rope_theta > 1.f)) return HSD_EINVAL;
+  if (d->n_layers > 1024 || d->n_q_heads > 1024) return HSD_ERANGE;
+  return HSD_OK;
+}
+
+size_t hsd_workspace_bytes(const hsd_model_desc *desc, int32_t max_total_q, int32_t max_n_seq) {
+  if (hsd_validate_model(desc) != HSD_OK || max_total_q < 1 || max_n_seq < 1) return 0;
+  return carve(*desc, max_total_q, max_n_seq, nullptr).total;
+}
+
+int hsd_validate_batch(const hsd_model_desc *desc, const hsd_kv_pool *pool, const hsd_batch *b, size_t ws_bytes) {
+  int rc = hsd_validate_model(desc);
+  if (rc != HSD_OK) return rc;
+  if (b == nullptr) return HSD_EINVAL;
+  if (b->n_seq < 1 || b->total_q < b->n_seq || b->max_blocks_per_seq < 1) return HSD_EINVAL;
+  if (b->n_slots < 1 || (b->seq_slot == nullptr && b->n_slots < b->n_seq)) return HSD_EINVAL;
+  if (b->n_seq > HSD_MAX_SEQ) return HSD_ERANGE;
+  if (static_cast<int64_t>(b->total_q) * desc->vocab / 64 > (int64_t{1} << 40)) return HSD_ERANGE;
+  if (b->cu_q == nullptr || b->tokens == nullptr || b->seq_len == nullptr || b->block_table == nullptr ||
+      b->status == nullptr)
+    return HSD_EINVAL;
+  if (b->n_dump < 0 || (b->n_dump > 0 && (b->logits_dump == nullptr || b->dump_rows == nullptr))) return HSD_EINVAL;
+  if (pool != nullptr) {
+    if (pool->k_pool == nullptr || pool->v_pool == nullptr || pool->free_list == nullptr ||
+        pool->free_count == nullptr || pool->n_blocks < 1)
+      return HSD_EINVAL;
+  }
+  if (ws_bytes < hsd_workspace_bytes(desc, b->total_q, b->n_seq)) return HSD_ENOSPC;
+  return HSD_OK;
+}
+
+int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) {
+  if (out == nullptr) return HSD_EINVAL;
+  *out = nullptr;
+  int rc = hsd_validate_model(desc);
+  if (rc != HSD_OK) return rc;
+  if (w == nullptr || w->tok_embed == nullptr || w->final_norm == nullptr || w->lm_head == nullptr ||
+      w->attn_norm == nullptr || w->wqkv == nullptr || w->wo == nullptr || w->ffn_norm == nullptr ||
+      w->w_gate_up == nullptr || w->w_down == nullptr)
+    return HSD_EINVAL;
+  for (int l = 0; l < desc->n_layers; ++l)
+    if (w->attn_norm[l] == nullptr || w->wqkv[l] == nullptr || w->wo[l] == nullptr || w->ffn_norm[l] == nullptr ||
+        w->w_gate_up[l] == nullptr || w->w_down[l] == nullptr)
+      return HSD_EINVAL;
+  int dev = 0, count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || count < 1) {
+    (void)hipGetLastError();
+    return HSD_ENODEV;
+  }
+  if (hipGetDevice(&dev) != hipSuccess) return HSD_ENODEV;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return HSD_EHIP;
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return HSD_EARCH;
+  hsd_ctx *c = new (std::nothrow) hsd_ctx();
+  if (c == nullptr) return HSD_EHIP;
+  c->desc = *desc;
+  c->tok_embed = w->tok_embed;
+  c->final_norm = w->final_norm;
+  c->lm_head = w->lm_head;
+  c->attn_norm.assign(w->attn_norm, w->attn_norm + desc->n_layers);
+  c->ffn_norm.assign(w->ffn_norm, w->ffn_norm + desc->n_layers);
+  c->wqkv.assign(w->wqkv, w->wqkv + desc->n_layers);
+  c->wo.assign(w->wo, w->wo + desc->n_layers);
+  c->w_gate_up.assign(w->w_gate_up, w->w_gate_up + desc->n_layers);
+  c->w_down.assign(w->w_down, w->w_down + desc->n_layers);
+  c->n_cu = prop.multiProcessorCount;
+  const char *fs = std::getenv("HSD_FORCE_SIMPLE");
+  c->force_simple = fs != nullptr && fs[0] == '1';
+  *out = c;
+  return HSD_OK;
+}
+
+void hsd_destroy(hsd_ctx *ctx) { delete ctx; }
+
+int hsd_kv_pool_init(void *stream, const hsd_kv_pool *pool) {
+  if (pool == nullptr || pool->free_list == nullptr || pool->free_count == nullptr || pool->n_blocks < 1)
+    return HSD_EINVAL;
+  hipLaunchKernelGGL(k_pool_init, dim3((pool->n_blocks + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     pool->n_blocks, pool->free_list, pool->free_count);
+  HSD_LAUNCH_CHECK();
+  return HSD_OK;
+}
+
+int hsd_verify_region_batch(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch, void *ws,
+                            size_t ws_bytes) {
+  return verify_common(ctx, stream, pool, batch, ws, ws_bytes, /*page_mode=*/false, /*prefill=*/false);
+}
+
+int hsd_verify_page(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch, void *ws,
+                    size_t ws_bytes) {
+  return verify_common(ctx, stream, pool, batch, ws, ws_bytes, /*page_mode=*/true, /*prefill=*/false);
+}
+
+int hsd_prefill(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch, void *ws,
+                size_t ws_bytes) {
+  return verify_common(ctx, stream, pool, batch, ws, ws_bytes, /*page_mode=*/true, /*prefill=*/true);
+}
+
+int hsd_kv_commit_rollback(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *b,
+                           int32_t *pending_out) {
+  if (ctx == nullptr || pool == nullptr) return HSD_EINVAL;
+  int rc = hsd_validate_batch(&ctx->desc, pool, b, static_cast<size_t>(-1));
+  if (rc != HSD_OK) return rc;
+  if (b->accept_len == nullptr || b->bonus == nullptr) return HSD_EINVAL;
+  hipLaunchKernelGGL(k_kv_commit, dim3(1), dim3(1024), 0, static_cast<hipStream_t>(stream), b->n_seq, b->cu_q,
+                     b->seq_slot, b->n_slots, b->seq_len, b->block_table, b->max_blocks_per_seq, pool->n_blocks, pool->free_list,
+                     pool->free_count, b->accept_len, b->bonus, pending_out, 0);
+  HSD_LAUNCH_CHECK();
+  return HSD_OK;
+}
+
+}  // extern "C"

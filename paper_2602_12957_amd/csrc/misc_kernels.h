@@ -1,0 +1,339 @@
+// Small kernels around the GEMMs and the attention: row metadata + rotary table, embedding gather,
+// RMSNorm, KV block reservation, LM-head arg-max reduction, acceptance scan, KV commit/rollback.
+#pragma once
+
+#include "common.h"
+
+namespace hsd {
+
+// ------------------------------------------------------------------------------------------------
+// Row metadata: sequence id, absolute position and rotary (cos, sin) table of every packed row.
+// The angle is formed in fp64 (position * theta^(-2i/64)) so that positions of many thousands lose
+// nothing before the fp32 rounding of cos/sin themselves.
+// grid: ceil(T*32 / 256) blocks of 256 threads; thread -> (row, frequency index i)
+// ------------------------------------------------------------------------------------------------
+__global__ void k_row_meta(int n_seq, int total_q, const int32_t *__restrict__ cu_q,
+                           const int32_t *__restrict__ seq_slot, int n_slots,
+                           const int32_t *__restrict__ seq_len, float rope_theta, int32_t *__restrict__ row_seq,
+                           int32_t *__restrict__ row_pos, float2 *__restrict__ rope_cs) {
+  int gid = blockIdx.x * blockDim.x + threadIdx.x;
+  int r = gid >> 5, i = gid & 31;
+  if (r >= total_q) return;
+  // binary search: largest s with cu_q[s] <= r
+  int lo = 0, hi = n_seq - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (cu_q[mid] <= r) lo = mid; else hi = mid - 1;
+  }
+  int slot = slot_of(seq_slot, lo, n_slots);
+  int pos = seq_len[slot] + (r - cu_q[lo]);
+  if (i == 0) {
+    row_seq[r] = slot;
+    row_pos[r] = pos;
+  }
+  double inv_freq = pow(static_cast<double>(rope_theta), -2.0 * i / static_cast<double>(kHd));
+  double ang = static_cast<double>(pos) * inv_freq;
+  double sn, cs;
+  sincos(ang, &sn, &cs);
+  rope_cs[static_cast<size_t>(r) * 32 + i] = make_float2(static_cast<float>(cs), static_cast<float>(sn));
+}
+
+// dump_slot[r] = index into logits_dump for row r, or -1.  Two launches: fill -1, then scatter.
+__global__ void k_fill_i32(int32_t *p, int n, int32_t v) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__global__ void k_dump_slots(const int32_t *__restrict__ dump_rows, int n_dump, int total_q,
+                             int32_t *__restrict__ dump_slot) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_dump) {
+    int r = dump_rows[i];
+    if (r >= 0 && r < total_q) dump_slot[r] = i;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Embedding gather: x[r,:] = tok_embed[tokens[r],:] (widened to fp32) or embeds[r,:] if tokens[r] < 0.
+// grid: T blocks; block 256 threads strided over d.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_embed(int d, int vocab, const int32_t *__restrict__ tokens, const float *__restrict__ embeds,
+                        const T *__restrict__ table, float *__restrict__ x) {
+  int r = blockIdx.x;
+  int t = tokens[r];
+  float *xr = x + static_cast<size_t>(r) * d;
+  if (t >= 0) {
+    if (t >= vocab) t = vocab - 1;  // ids are validated by the caller; clamp keeps the read in bounds
+    const T *src = table + static_cast<size_t>(t) * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) xr[c] = to_f32(src[c]);
+  } else if (embeds != nullptr) {
+    const float *src = embeds + static_cast<size_t>(r) * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) xr[c] = src[c];
+  } else {
+    for (int c = threadIdx.x; c < d; c += blockDim.x) xr[c] = 0.f;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// RMSNorm: h[r,:] = x[r,:] * rsqrt(mean(x^2) + eps) * gain, fp32 math, output in the GEMM operand type.
+// One wave per row, 4 rows per 256-thread block; d is a multiple of 128 so every lane reads float4s.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_rmsnorm(int n_rows, int d, float eps, const float *__restrict__ x, const float *__restrict__ gain,
+                          T *__restrict__ h) {
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int r = blockIdx.x * 4 + wave;
+  if (r >= n_rows) return;
+  const float4 *xr = reinterpret_cast<const float4 *>(x + static_cast<size_t>(r) * d);
+  const float4 *g4 = reinterpret_cast<const float4 *>(gain);
+  int n4 = d >> 2;
+  float ss = 0.f;
+  for (int c = lane; c < n4; c += kWave) {
+    float4 v = xr[c];
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = wave_sum(ss);
+  float rstd = 1.0f / sqrtf(ss / static_cast<float>(d) + eps);
+  T *hr = h + static_cast<size_t>(r) * d;
+  for (int c = lane; c < n4; c += kWave) {
+    float4 v = xr[c];
+    float4 g = g4[c];
+    hr[4 * c + 0] = from_f32<T>(v.x * rstd * g.x);
+    hr[4 * c + 1] = from_f32<T>(v.y * rstd * g.y);
+    hr[4 * c + 2] = from_f32<T>(v.z * rstd * g.z);
+    hr[4 * c + 3] = from_f32<T>(v.w * rstd * g.w);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Block-wide exclusive scan of up to HSD_MAX_SEQ ints held in LDS (1024 threads, 4 items each).
+// On return s_val[i] holds the exclusive prefix and the function returns the grand total.
+// ------------------------------------------------------------------------------------------------
+__device__ inline int block_exclusive_scan_4096(int *s_val, int n, int *s_part /*[1024]*/) {
+  int t = threadIdx.x;
+  int base = t * 4;
+  int v[4], sum = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    v[j] = (base + j < n) ? s_val[base + j] : 0;
+    sum += v[j];
+  }
+  s_part[t] = sum;
+  __syncthreads();
+  // Hillis-Steele inclusive scan over the 1024 partial sums
+  for (int off = 1; off < 1024; off <<= 1) {
+    int add = (t >= off) ? s_part[t - off] : 0;
+    __syncthreads();
+    s_part[t] += add;
+    __syncthreads();
+  }
+  int total = s_part[1023];
+  int run = s_part[t] - sum;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (base + j < n) s_val[base + j] = run;
+    run += v[j];
+  }
+  __syncthreads();
+  return total;
+}
+
+// ------------------------------------------------------------------------------------------------
+// KV block reservation for the speculative append.  For every sequence, every block-table slot that
+// covers positions seq_len .. seq_len+q_len-1 and holds no block gets one popped from the free stack.
+// Deterministic: sequence s takes its blocks after all sequences < s, slots in increasing order.
+// One block of 1024 threads (16 waves; waves stride over sequences, lanes over slots).
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024) k_kv_reserve(int n_seq, const int32_t *__restrict__ cu_q,
+                                                     const int32_t *__restrict__ seq_slot, int n_slots,
+                                                     const int32_t *__restrict__ seq_len,
+                                                     int32_t *__restrict__ block_table, int maxb, int n_blocks,
+                                                     int32_t *__restrict__ free_list, int32_t *__restrict__ free_count,
+                                                     int32_t *__restrict__ status) {
+  __shared__ int s_cnt[HSD_MAX_SEQ];
+  __shared__ int s_part[1024];
+  __shared__ int s_flags;
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (threadIdx.x == 0) s_flags = 0;
+  __syncthreads();
+  for (int s = wave; s < n_seq; s += 16) {
+    int sl = slot_of(seq_slot, s, n_slots);
+    if (lane == 0 && seq_slot != nullptr && seq_slot[s] != sl) atomicOr(&s_flags, HSD_STATUS_BAD_SLOT);
+    int S = seq_len[sl], Lq = cu_q[s + 1] - cu_q[s];
+    int lo = S / kBlk, hi = (S + Lq + kBlk - 1) / kBlk;
+    if (hi > maxb) {
+      if (lane == 0) atomicOr(&s_flags, HSD_STATUS_TABLE_OVERFLOW);
+      hi = maxb;
+    }
+    int cnt = 0;
+    for (int i = lo + lane; i < hi; i += kWave) cnt += (block_table[static_cast<size_t>(sl) * maxb + i] < 0);
+    cnt = wave_sum_i(cnt);
+    if (lane == 0) s_cnt[s] = cnt;
+  }
+  __syncthreads();
+  int total = block_exclusive_scan_4096(s_cnt, n_seq, s_part);
+  int avail = *free_count;
+  if (avail > n_blocks) avail = n_blocks;
+  if (total > avail) {
+    if (threadIdx.x == 0) atomicOr(status, s_flags | HSD_STATUS_POOL_EXHAUSTED);
+    return;  // nothing is taken; slots stay -1 and every later kernel skips them
+  }
+  for (int s = wave; s < n_seq; s += 16) {
+    int sl = slot_of(seq_slot, s, n_slots);
+    int S = seq_len[sl], Lq = cu_q[s + 1] - cu_q[s];
+    int lo = S / kBlk, hi = (S + Lq + kBlk - 1) / kBlk;
+    if (hi > maxb) hi = maxb;
+    int taken = s_cnt[s];  // exclusive prefix = blocks taken by earlier sequences
+    for (int i0 = lo; i0 < hi; i0 += kWave) {
+      int i = i0 + lane;
+      bool need = (i < hi) && (block_table[static_cast<size_t>(sl) * maxb + i] < 0);
+      unsigned long long m = __ballot(need);
+      int rank = __popcll(m & ((1ull << lane) - 1ull));
+      if (need) block_table[static_cast<size_t>(sl) * maxb + i] = free_list[avail - 1 - (taken + rank)];
+      taken += __popcll(m);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    *free_count = avail - total;
+    if (s_flags) atomicOr(status, s_flags);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// KV commit / rollback.  seq_len += 1 + alpha (alpha >= 0), or += q_len when commit_all (prefill);
+// slots wholly beyond the new length are pushed back on the free stack in (sequence, slot) order.
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024) k_kv_commit(int n_seq, const int32_t *__restrict__ cu_q,
+                                                    const int32_t *__restrict__ seq_slot, int n_slots,
+                                                    int32_t *__restrict__ seq_len, int32_t *__restrict__ block_table,
+                                                    int maxb, int n_blocks, int32_t *__restrict__ free_list,
+                                                    int32_t *__restrict__ free_count,
+                                                    const int32_t *__restrict__ accept_len,
+                                                    const int32_t *__restrict__ bonus, int32_t *__restrict__ pending_out,
+                                                    int commit_all) {
+  __shared__ int s_cnt[HSD_MAX_SEQ];
+  __shared__ int s_new[HSD_MAX_SEQ];
+  __shared__ int s_part[1024];
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int s = wave; s < n_seq; s += 16) {
+    int sl = slot_of(seq_slot, s, n_slots);
+    int S = seq_len[sl], Lq = cu_q[s + 1] - cu_q[s];
+    int new_len = S;
+    if (commit_all) {
+      new_len = S + Lq;
+    } else {
+      int a = accept_len[s];
+      if (a > Lq - 1) a = Lq - 1;
+      if (a >= 0) new_len = S + 1 + a;
+    }
+    int keep = (new_len + kBlk - 1) / kBlk, hi = (S + Lq + kBlk - 1) / kBlk;
+    if (hi > maxb) hi = maxb;
+    int cnt = 0;
+    for (int i = keep + lane; i < hi; i += kWave) {
+      int b = block_table[static_cast<size_t>(sl) * maxb + i];
+      cnt += (b >= 0 && b < n_blocks);
+    }
+    cnt = wave_sum_i(cnt);
+    if (lane == 0) {
+      s_cnt[s] = cnt;
+      s_new[s] = new_len;
+    }
+  }
+  __syncthreads();
+  int total = block_exclusive_scan_4096(s_cnt, n_seq, s_part);
+  int height = *free_count;
+  if (height < 0) height = 0;
+  if (height + total > n_blocks) total = 0, height = -1;  // corrupted accounting: free nothing
+  for (int s = wave; s < n_seq; s += 16) {
+    int sl = slot_of(seq_slot, s, n_slots);
+    int S = seq_len[sl], Lq = cu_q[s + 1] - cu_q[s];
+    int new_len = s_new[s];
+    int keep = (new_len + kBlk - 1) / kBlk, hi = (S + Lq + kBlk - 1) / kBlk;
+    if (hi > maxb) hi = maxb;
+    int pushed = s_cnt[s];
+    if (height >= 0) {
+      for (int i0 = keep; i0 < hi; i0 += kWave) {
+        int i = i0 + lane;
+        int b = (i < hi) ? block_table[static_cast<size_t>(sl) * maxb + i] : -1;
+        bool has = (b >= 0 && b < n_blocks);
+        unsigned long long m = __ballot(has);
+        int rank = __popcll(m & ((1ull << lane) - 1ull));
+        if (has) {
+          free_list[height + pushed + rank] = b;
+          block_table[static_cast<size_t>(sl) * maxb + i] = -1;
+        }
+        pushed += __popcll(m);
+      }
+    }
+  }
+  __syncthreads();
+  for (int s = threadIdx.x; s < n_seq; s += blockDim.x) {
+    bool advanced = commit_all || accept_len[s] >= 0;
+    seq_len[slot_of(seq_slot, s, n_slots)] = s_new[s];
+    if (!commit_all && advanced && pending_out != nullptr) pending_out[s] = bonus[s];
+  }
+  if (threadIdx.x == 0 && height >= 0) *free_count = height + total;
+}
+
+__global__ void k_pool_init(int n_blocks, int32_t *__restrict__ free_list, int32_t *__restrict__ free_count) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_blocks) free_list[i] = n_blocks - 1 - i;  // popping from the top hands out 0, 1, 2, ...
+  if (i == 0) *free_count = n_blocks;
+}
+
+// ------------------------------------------------------------------------------------------------
+// LM-head arg-max, second stage: merge the per-(row, column tile) Top2 partials of the LM-head GEMM.
+// One wave per row.  Output u_hat (Eq. 10: arg-max over the vocabulary; arg-max of logits equals
+// arg-max of probabilities) and the top-1/top-2 logit margin.
+// ------------------------------------------------------------------------------------------------
+__global__ void k_lm_reduce(int n_rows, int n_tiles, const Top2 *__restrict__ part, int32_t *__restrict__ argmax,
+                            float *__restrict__ margin) {
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int r = blockIdx.x * 4 + wave;
+  if (r >= n_rows) return;
+  Top2 t = top2_init();
+  for (int c = lane; c < n_tiles; c += kWave) t = top2_merge(t, part[static_cast<size_t>(r) * n_tiles + c]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    Top2 u;
+    u.m1 = __shfl_xor(t.m1, o, kWave);
+    u.i1 = __shfl_xor(t.i1, o, kWave);
+    u.m2 = __shfl_xor(t.m2, o, kWave);
+    t = top2_merge(t, u);
+  }
+  if (lane == 0) {
+    argmax[r] = t.i1;
+    if (margin != nullptr) margin[r] = t.m1 - t.m2;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Draft compare + longest-prefix acceptance (Eq. 9, 11 at exact match; Eq. 12 bonus; alpha of Eq. 15).
+// One wave per sequence: lanes compare 64 draft positions at a time, a ballot finds the first
+// mismatch.  match_i = (tokens[base+i] == argmax[base+i-1]) for i = 1..k.
+// ------------------------------------------------------------------------------------------------
+__global__ void k_accept(int n_seq, const int32_t *__restrict__ cu_q, const int32_t *__restrict__ tokens,
+                         const int32_t *__restrict__ argmax, int32_t *__restrict__ accept_len,
+                         int32_t *__restrict__ bonus) {
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int s = blockIdx.x * 4 + wave;
+  if (s >= n_seq) return;
+  int base = cu_q[s], k = cu_q[s + 1] - base - 1;
+  int alpha = k;
+  for (int i0 = 1; i0 <= k; i0 += kWave) {
+    int i = i0 + lane;
+    bool mismatch = (i <= k) && (tokens[base + i] != argmax[base + i - 1]);
+    unsigned long long m = __ballot(mismatch);
+    if (m != 0ull) {
+      alpha = i0 + (__ffsll(static_cast<long long>(m)) - 1) - 1;  // accepted = index of first mismatch - 1
+      break;
+    }
+  }
+  if (lane == 0) {
+    accept_len[s] = alpha;
+    bonus[s] = argmax[base + alpha];
+  }
+}
+
+}  // namespace hsd
