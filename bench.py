@@ -1,0 +1,173 @@
+"""Benchmark of the HSD verification hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: the round-1 verification of the
+region-level workload (16 regions, 1024 visual + 32 prompt tokens of prefix each, draft lengths U[16,256],
+5 % of the draft tokens corrupted): batch metadata already in HBM -> verify (KV reservation, 24-layer decoder
+forward over every draft row with KV append, LM-head arg-max, acceptance scan) -> KV commit/rollback -> read
+back (alpha, bonus).  Prefix prefill, weight upload and the generation of the greedy target sequence the
+drafts derive from are outside the timed region (the paper's T_decode excludes prefill, Section 4.2).
+
+Prints ONE JSON line.  `value` = verified draft tokens per second (draft rows scored / time).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+
+
+def build_workload(cfg_index, seed):
+    import workloads as W
+    specs = W.draw_sequences(cfg_index, seed)
+    desc = W.CONFIGS[cfg_index].model
+    weights = W.make_weights(desc, seed)
+    return W, desc, weights, specs
+
+
+def prefix_inputs(W, desc, seed, sp):
+    vis, prompt = W.make_prefix(desc, seed, sp.seq_id, sp.n_visual, sp.n_prompt)
+    if sp.n_prompt == 0:
+        return np.full(sp.n_visual, -1, np.int32), vis, 0
+    tok = np.concatenate([np.full(sp.n_visual, -1, np.int32), prompt[:-1]]).astype(np.int32)
+    emb = np.concatenate([vis, np.zeros((sp.n_prompt - 1, desc.d_model), np.float32)], axis=0)
+    return tok, emb, int(prompt[-1])
+
+
+def cpu_baseline(W, desc, weights, seed, specs, drafts, pendings, n_sample):
+    """The oracle as it stands, timed on this machine's host cores on round 1 of the first n_sample sequences
+    (prefill of their prefixes is done first and not timed, as on the GPU side)."""
+    import oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    caches = []
+    for sp in specs[:n_sample]:
+        vis, prompt = W.make_prefix(desc, seed, sp.seq_id, sp.n_visual, sp.n_prompt)
+        caches.append(O.prefill(desc, weights, vis, prompt)[0])
+    t0 = time.perf_counter()
+    rows = 0
+    for i in range(n_sample):
+        O.verify_block(desc, weights, caches[i], pendings[i], drafts[i])
+        rows += len(drafts[i])
+    dt = time.perf_counter() - t0
+    return {"value": rows / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"round-1 verification of the first {n_sample} of {len(specs)} regions "
+                      f"({rows} draft tokens, fp64 numpy, {dt:.1f} s; prefix prefill not timed)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--cpu-sample", type=int, default=4, help="sequences of the workload the oracle is timed on (0 = skip)")
+    ap.add_argument("--profile-kernel", type=str, default="gate_up",
+                    choices=["gate_up", "qkv", "attention", "o", "down", "lm_head", "rmsnorm", "none"])
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_12957_amd.runtime import Engine
+    import paper_2602_12957_amd.binding as B
+
+    cfg_index = 1
+    W, desc, weights, specs = build_workload(cfg_index, args.seed or 20260212)
+    seed = args.seed or W.SEED_BASE
+    n = len(specs)
+    k_max = max(sp.draft_len for sp in specs)
+    maxb = max((sp.n_visual + sp.n_prompt + sp.draft_len + 1 + 15) // 16 + 1 for sp in specs)
+    n_blocks = sum((sp.n_visual + sp.n_prompt + sp.draft_len + 1 + 15) // 16 + 1 for sp in specs) + 8
+    total_q = sum(sp.draft_len + 1 for sp in specs)
+    eng = Engine(desc, weights, n_blocks, n, maxb, max(total_q, 4096))
+    slots = list(range(n))
+
+    toks, embs, pend = [], [], []
+    for sp in specs:
+        t, e, p = prefix_inputs(W, desc, seed, sp)
+        toks.append(t), embs.append(e), pend.append(p)
+
+    # --- set-up (untimed): prefix prefill, greedy target generation on the GPU path itself, prefill again
+    eng.prefill(slots, toks, embs)
+    target = eng.greedy_decode(slots, pend, k_max)
+    eng.reset()
+    eng.prefill(slots, toks, embs)
+    torch.cuda.synchronize()
+    drafts = [W.corrupt_draft(target[i][:sp.draft_len], sp.corrupt_p, desc.vocab, seed, f"cfg{cfg_index}.{sp.seq_id}")[0]
+              for i, sp in enumerate(specs)]
+    blocks = [np.concatenate([[pend[i]], drafts[i]]).astype(np.int32) for i in range(n)]
+    batch = eng.prepare(slots, blocks)
+    eng.snapshot()
+    torch.cuda.synchronize()
+
+    def step():
+        eng.restore()                       # bookkeeping back to "prefix cached" (one small device copy)
+        eng.verify_prepared(batch, "region")
+        eng.commit()
+        return eng.read_acceptance(n)       # synchronises: the host needs alpha to slice the next round
+
+    for _ in range(args.warmup):
+        alpha, bonus, status = step()
+    prof_map = {"gate_up": B.HSD_PROF_GEMM_GATE_UP, "qkv": B.HSD_PROF_GEMM_QKV, "attention": B.HSD_PROF_ATTENTION,
+                "o": B.HSD_PROF_GEMM_O, "down": B.HSD_PROF_GEMM_DOWN, "lm_head": B.HSD_PROF_GEMM_LM_HEAD,
+                "rmsnorm": B.HSD_PROF_RMSNORM, "none": B.HSD_PROF_NONE}
+    which = prof_map[args.profile_kernel]
+    eng.profile(which, 2 * desc.n_layers * args.steps + 8)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        alpha, bonus, status = step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_launch, kern_ms = eng.profile_read()
+    eng.profile(B.HSD_PROF_NONE, 0)
+    assert status == 0, f"device status {status}"
+
+    verified = sum(sp.draft_len for sp in specs)
+    accepted = int(alpha.sum())
+    ms_step = dt / args.steps * 1e3
+    d, F, V = desc.d_model, desc.d_ffn, desc.vocab
+    qd, kvd = desc.q_dim, desc.kv_dim
+    flops_per_launch = {"gate_up": 2.0 * total_q * d * 2 * F, "qkv": 2.0 * total_q * d * (qd + 2 * kvd),
+                        "o": 2.0 * total_q * qd * d, "down": 2.0 * total_q * F * d, "lm_head": 2.0 * total_q * d * V}
+    roofline = None
+    if n_launch > 0 and args.profile_kernel in flops_per_launch:
+        avg_ms = kern_ms / n_launch
+        ach = flops_per_launch[args.profile_kernel] / (avg_ms * 1e-3) / 1e12
+        roofline = {"kernel": f"k_gemm_mfma ({args.profile_kernel})", "bound": "mfma", "achieved": round(ach, 1),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                    "traffic": None, "avg_launch_ms": round(avg_ms, 5), "launches_timed": n_launch,
+                    "flops_per_launch": flops_per_launch[args.profile_kernel]}
+    gemm_flops_step = 2.0 * desc.gemm_params * total_q
+    out = {
+        "metric": "verified_draft_tokens_per_s", "value": round(verified / (ms_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1] region-level verify, round 1: 16 regions x (1055 cached + pending + draft "
+                               "U[16,256]), 24-layer d1024 16q/4kv x64 FFN4096 vocab 32768, paged KV 16-token blocks",
+                   "n_seq": n, "rows_per_step": total_q, "draft_tokens_per_step": verified, "corruption_p": 0.05},
+        "accepted_tokens_per_s": round(accepted / (ms_step * 1e-3), 1),
+        "committed_tokens_per_s": round((accepted + n) / (ms_step * 1e-3), 1),
+        "aal": round(accepted / n, 3),
+        "gemm_tflops_whole_step": round(gemm_flops_step / (ms_step * 1e-3) / 1e12, 1),
+        "roofline": roofline,
+    }
+    if args.cpu_sample > 0:
+        out["cpu_baseline"] = cpu_baseline(W, desc, weights, seed, specs, drafts, pend, min(args.cpu_sample, n))
+    eng.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

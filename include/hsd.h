@@ -166,6 +166,25 @@ int hsd_kv_commit_rollback(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, 
 int hsd_prefill(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch,
                 void *workspace, size_t ws_bytes);
 
+/* Measurement aid (for callers that report a per-kernel roofline; not a step of the method).
+ * After hsd_profile_enable(ctx, which, max_launches) every launch of the kernel class `which` made by a
+ * verify call is bracketed by a pair of HIP events recorded on the caller's stream (at most max_launches
+ * pairs; later launches are not timed).  hsd_profile_read waits for the recorded events, returns the number
+ * of timed launches and the sum of their durations in milliseconds, and clears the record.
+ * hsd_profile_enable(ctx, HSD_PROF_NONE, 0) switches timing off and releases the events. */
+enum {
+  HSD_PROF_NONE = 0,
+  HSD_PROF_GEMM_QKV = 1,
+  HSD_PROF_ATTENTION = 2,
+  HSD_PROF_GEMM_O = 3,
+  HSD_PROF_GEMM_GATE_UP = 4,
+  HSD_PROF_GEMM_DOWN = 5,
+  HSD_PROF_GEMM_LM_HEAD = 6,
+  HSD_PROF_RMSNORM = 7
+};
+int hsd_profile_enable(hsd_ctx *ctx, int which, int32_t max_launches);
+int hsd_profile_read(hsd_ctx *ctx, int32_t *n_launches, float *total_ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -60,7 +60,12 @@ for _n in ("hsd_verify_region_batch", "hsd_verify_page", "hsd_prefill"):
     getattr(lib, _n).argtypes = [vp, vp, _P(hsd_kv_pool), _P(hsd_batch), vp, C.c_size_t]
 lib.hsd_kv_commit_rollback.argtypes = [vp, vp, _P(hsd_kv_pool), _P(hsd_batch), vp]
 
-EXPORTS = ["hsd_status_string", "hsd_validate_model", "hsd_validate_batch", "hsd_create", "hsd_destroy",
+lib.hsd_profile_enable.argtypes = [vp, C.c_int, i32]
+lib.hsd_profile_read.argtypes = [vp, _P(i32), _P(f32)]
+(HSD_PROF_NONE, HSD_PROF_GEMM_QKV, HSD_PROF_ATTENTION, HSD_PROF_GEMM_O, HSD_PROF_GEMM_GATE_UP, HSD_PROF_GEMM_DOWN,
+ HSD_PROF_GEMM_LM_HEAD, HSD_PROF_RMSNORM) = range(8)
+
+EXPORTS = ["hsd_profile_enable", "hsd_profile_read", "hsd_status_string", "hsd_validate_model", "hsd_validate_batch", "hsd_create", "hsd_destroy",
            "hsd_workspace_bytes", "hsd_kv_pool_init", "hsd_verify_region_batch", "hsd_verify_page",
            "hsd_kv_commit_rollback", "hsd_prefill"]
 
@@ -95,3 +100,10 @@ def hsd_prefill(ctx, stream, pool, batch, ws, ws_bytes):
     check("hsd_prefill", lib.hsd_prefill(ctx, stream, C.byref(pool), C.byref(batch), ws, ws_bytes))
 def hsd_kv_commit_rollback(ctx, stream, pool, batch, pending_out):
     check("hsd_kv_commit_rollback", lib.hsd_kv_commit_rollback(ctx, stream, C.byref(pool), C.byref(batch), pending_out))
+
+def hsd_profile_enable(ctx, which, max_launches):
+    check("hsd_profile_enable", lib.hsd_profile_enable(ctx, which, max_launches))
+def hsd_profile_read(ctx):
+    n, ms = i32(), f32()
+    check("hsd_profile_read", lib.hsd_profile_read(ctx, C.byref(n), C.byref(ms)))
+    return n.value, ms.value

@@ -64,7 +64,10 @@ struct EpiSwiGLU {
   static constexpr bool kDual = true;
   T *u;
   int ld;
-  __device__ __forceinline__ static float f(float g, float up) { return g / (1.0f + __expf(-g)) * up; }
+  __device__ __forceinline__ static float f(float g, float up) { return g / (1.0f + expf(-g)) * up; }
+  __device__ __forceinline__ void one2(int m, int n, float g, float up) const {
+    u[static_cast<size_t>(m) * ld + n] = from_f32<T>(f(g, up));
+  }
   __device__ __forceinline__ void pair2(int m, int n, float g_lo, float g_hi, float u_lo, float u_hi) const {
     T *p = u + static_cast<size_t>(m) * ld + n;
     p[0] = from_f32<T>(f(g_lo, u_lo));

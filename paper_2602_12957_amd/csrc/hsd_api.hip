@@ -12,6 +12,7 @@
 #include "attn_simple.h"
 #include "common.h"
 #include "epilogues.h"
+#include "gemm_mfma.h"
 #include "gemm_simple.h"
 #include "misc_kernels.h"
 
@@ -25,7 +26,12 @@ struct hsd_ctx {
   std::vector<const float *> attn_norm, ffn_norm;
   std::vector<const void *> wqkv, wo, w_gate_up, w_down;
   int n_cu;
-  bool force_simple;
+  bool force_simple;  // HSD_FORCE_SIMPLE=1: run the plain kernels also for bf16 (cross-check of the MFMA path)
+  int gemm_bk;        // HSD_GEMM_BK=32|64: K slice of the MFMA GEMM
+  // per-kernel timing (hsd_profile_*)
+  int prof_which = HSD_PROF_NONE;
+  int prof_used = 0;
+  std::vector<hipEvent_t> prof_events;  // 2 per timed launch
 };
 
 namespace {
@@ -72,9 +78,58 @@ Workspace carve(const hsd_model_desc &d, int64_t T, int64_t /*n_seq*/, void *bas
     if (hipGetLastError() != hipSuccess) return HSD_EHIP; \
   } while (0)
 
+// Brackets one launch with events when its class is being timed.
+struct ProfScope {
+  hsd_ctx *ctx;
+  hipStream_t st;
+  bool on;
+  ProfScope(hsd_ctx *c, hipStream_t s, int which) : ctx(c), st(s) {
+    on = c->prof_which == which && which != HSD_PROF_NONE &&
+         static_cast<size_t>(2 * c->prof_used + 1) < c->prof_events.size();
+    if (on) (void)hipEventRecord(c->prof_events[2 * c->prof_used], st);
+  }
+  ~ProfScope() {
+    if (on) {
+      (void)hipEventRecord(ctx->prof_events[2 * ctx->prof_used + 1], st);
+      ctx->prof_used++;
+    }
+  }
+};
+
+template <typename Epi>
+struct GemmModeOf {
+  static constexpr int value = Epi::kDual ? kModeDual : (std::is_same<Epi, EpiLMHead>::value ? kModeSwapLM : kModeNormal);
+};
+
+template <int BK, typename Epi>
+int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const void *W, const Epi &epi) {
+  constexpr int MODE = GemmModeOf<Epi>::value;
+  auto kern = k_gemm_mfma<BK, MODE, Epi>;
+  constexpr int smem = GemmSmem<BK>::kBytes;
+  static bool attr_done = false;  // per instantiation; the attribute is per function, setting it twice is harmless
+  if (!attr_done) {
+    if (smem > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
+            hipSuccess)
+      return HSD_EHIP;
+    attr_done = true;
+  }
+  const int tiles_m = (M + kGemmBM - 1) / kGemmBM;
+  const int tiles_n = (MODE == kModeDual) ? N / 64 : (N + kGemmBN - 1) / kGemmBN;
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, st, M, N, K, static_cast<const bf16 *>(A),
+                     static_cast<const bf16 *>(W), epi);
+  HSD_LAUNCH_CHECK();
+  return HSD_OK;
+}
+
 template <typename T, typename Epi>
 int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int M, int N, int K, const void *A, const void *W, const Epi &epi) {
-  (void)ctx;
+  if constexpr (std::is_same<T, bf16>::value) {
+    if (!ctx->force_simple && K % 64 == 0) {
+      if (ctx->gemm_bk == 32) return launch_gemm_mfma<32>(st, M, N, K, A, W, epi);
+      return launch_gemm_mfma<64>(st, M, N, K, A, W, epi);
+    }
+  }
   dim3 grid(N / 64, (M + 63) / 64);
   hipLaunchKernelGGL((k_gemm_simple<T, Epi>), grid, dim3(256), 0, st, M, N, K, static_cast<const T *>(A),
                      static_cast<const T *>(W), epi);
@@ -106,22 +161,40 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
   RowMeta meta{ws.row_seq, ws.row_pos, ws.rope_cs};
   for (int l = 0; l < d.n_layers; ++l) {
     PagedKV kv{pool->k_pool, pool->v_pool, b->block_table, b->max_blocks_per_seq, pool->n_blocks, d.n_kv_heads, l};
-    hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
-                       ctx->attn_norm[l], static_cast<T *>(ws.h));
-    HSD_LAUNCH_CHECK();
+    {
+      ProfScope ps(ctx, st, HSD_PROF_RMSNORM);
+      hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
+                         ctx->attn_norm[l], static_cast<T *>(ws.h));
+      HSD_LAUNCH_CHECK();
+    }
     EpiQKV<T> eq{d.n_q_heads, d.n_kv_heads, meta, kv, static_cast<T *>(ws.q)};
-    if ((rc = launch_gemm<T>(ctx, st, Tq, qdim + 2 * kvdim, d.d_model, ws.h, ctx->wqkv[l], eq))) return rc;
-    hipLaunchKernelGGL((k_attn_simple<T>), dim3(Tq, (d.n_q_heads + 3) / 4), dim3(256), 0, st, d.n_q_heads, meta, kv,
-                       static_cast<const T *>(ws.q), static_cast<T *>(ws.a));
-    HSD_LAUNCH_CHECK();
+    {
+      ProfScope ps(ctx, st, HSD_PROF_GEMM_QKV);
+      if ((rc = launch_gemm<T>(ctx, st, Tq, qdim + 2 * kvdim, d.d_model, ws.h, ctx->wqkv[l], eq))) return rc;
+    }
+    {
+      ProfScope ps(ctx, st, HSD_PROF_ATTENTION);
+      hipLaunchKernelGGL((k_attn_simple<T>), dim3(Tq, (d.n_q_heads + 3) / 4), dim3(256), 0, st, d.n_q_heads, meta,
+                         kv, static_cast<const T *>(ws.q), static_cast<T *>(ws.a));
+      HSD_LAUNCH_CHECK();
+    }
     EpiResidual er{ws.x, d.d_model};
-    if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_model, qdim, ws.a, ctx->wo[l], er))) return rc;
+    {
+      ProfScope ps(ctx, st, HSD_PROF_GEMM_O);
+      if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_model, qdim, ws.a, ctx->wo[l], er))) return rc;
+    }
     hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
                        ctx->ffn_norm[l], static_cast<T *>(ws.h));
     HSD_LAUNCH_CHECK();
     EpiSwiGLU<T> es{static_cast<T *>(ws.u), d.d_ffn};
-    if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_ffn, d.d_model, ws.h, ctx->w_gate_up[l], es))) return rc;
-    if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_model, d.d_ffn, ws.u, ctx->w_down[l], er))) return rc;
+    {
+      ProfScope ps(ctx, st, HSD_PROF_GEMM_GATE_UP);
+      if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_ffn, d.d_model, ws.h, ctx->w_gate_up[l], es))) return rc;
+    }
+    {
+      ProfScope ps(ctx, st, HSD_PROF_GEMM_DOWN);
+      if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_model, d.d_ffn, ws.u, ctx->w_down[l], er))) return rc;
+    }
   }
   if (!with_head) return HSD_OK;
 
@@ -139,7 +212,10 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
   }
   const int n_tiles = d.vocab / 64;
   EpiLMHead el{ws.lm_part, n_tiles, d.vocab, dump_slot, b->logits_dump};
-  if ((rc = launch_gemm<T>(ctx, st, Tq, d.vocab, d.d_model, ws.h, ctx->lm_head, el))) return rc;
+  {
+    ProfScope ps(ctx, st, HSD_PROF_GEMM_LM_HEAD);
+    if ((rc = launch_gemm<T>(ctx, st, Tq, d.vocab, d.d_model, ws.h, ctx->lm_head, el))) return rc;
+  }
   hipLaunchKernelGGL(k_lm_reduce, dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, n_tiles, ws.lm_part, b->argmax,
                      b->top2_margin);
   HSD_LAUNCH_CHECK();
@@ -266,11 +342,49 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   c->n_cu = prop.multiProcessorCount;
   const char *fs = std::getenv("HSD_FORCE_SIMPLE");
   c->force_simple = fs != nullptr && fs[0] == '1';
+  const char *bk = std::getenv("HSD_GEMM_BK");
+  c->gemm_bk = (bk != nullptr && std::atoi(bk) == 32) ? 32 : 64;
   *out = c;
   return HSD_OK;
 }
 
-void hsd_destroy(hsd_ctx *ctx) { delete ctx; }
+void hsd_destroy(hsd_ctx *ctx) {
+  if (ctx == nullptr) return;
+  for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
+  delete ctx;
+}
+
+int hsd_profile_enable(hsd_ctx *ctx, int which, int32_t max_launches) {
+  if (ctx == nullptr || which < HSD_PROF_NONE || which > HSD_PROF_RMSNORM || max_launches < 0) return HSD_EINVAL;
+  if (max_launches > (1 << 20)) return HSD_ERANGE;
+  for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
+  ctx->prof_events.clear();
+  ctx->prof_used = 0;
+  ctx->prof_which = which;
+  if (which == HSD_PROF_NONE) return HSD_OK;
+  ctx->prof_events.resize(2 * static_cast<size_t>(max_launches));
+  for (size_t i = 0; i < ctx->prof_events.size(); ++i)
+    if (hipEventCreate(&ctx->prof_events[i]) != hipSuccess) {
+      ctx->prof_events.resize(i);
+      return HSD_EHIP;
+    }
+  return HSD_OK;
+}
+
+int hsd_profile_read(hsd_ctx *ctx, int32_t *n_launches, float *total_ms) {
+  if (ctx == nullptr || n_launches == nullptr || total_ms == nullptr) return HSD_EINVAL;
+  float sum = 0.f;
+  for (int i = 0; i < ctx->prof_used; ++i) {
+    float ms = 0.f;
+    if (hipEventSynchronize(ctx->prof_events[2 * i + 1]) != hipSuccess) return HSD_EHIP;
+    if (hipEventElapsedTime(&ms, ctx->prof_events[2 * i], ctx->prof_events[2 * i + 1]) != hipSuccess) return HSD_EHIP;
+    sum += ms;
+  }
+  *n_launches = ctx->prof_used;
+  *total_ms = sum;
+  ctx->prof_used = 0;
+  return HSD_OK;
+}
 
 int hsd_kv_pool_init(void *stream, const hsd_kv_pool *pool) {
   if (pool == nullptr || pool->free_list == nullptr || pool->free_count == nullptr || pool->n_blocks < 1)

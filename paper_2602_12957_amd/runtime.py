@@ -82,11 +82,17 @@ class Engine:
         pool_elems = L * n_blocks * desc.n_kv_heads * B.HSD_KV_BLOCK_TOKENS * B.HSD_HEAD_DIM
         self.k_pool = torch.zeros(pool_elems, dtype=es, device=self.dev)
         self.v_pool = torch.zeros(pool_elems, dtype=es, device=self.dev)
-        self.free_list = torch.zeros(n_blocks, dtype=torch.int32, device=self.dev)
-        self.free_count = torch.zeros(1, dtype=torch.int32, device=self.dev)
-        self.seq_len = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
-        self.block_table = torch.full((n_slots, max_blocks_per_seq), -1, dtype=torch.int32, device=self.dev)
-        self.status = torch.zeros(1, dtype=torch.int32, device=self.dev)
+        # all KV bookkeeping lives in one int32 buffer so that a snapshot/restore is a single device copy
+        n_state = n_blocks + 1 + n_slots + n_slots * max_blocks_per_seq + 1
+        self._state = torch.zeros(n_state, dtype=torch.int32, device=self.dev)
+        o = 0
+        self.free_list = self._state[o:o + n_blocks]; o += n_blocks
+        self.free_count = self._state[o:o + 1]; o += 1
+        self.seq_len = self._state[o:o + n_slots]; o += n_slots
+        self.block_table = self._state[o:o + n_slots * max_blocks_per_seq].view(n_slots, max_blocks_per_seq)
+        o += n_slots * max_blocks_per_seq
+        self.status = self._state[o:o + 1]
+        self._snapshot = torch.zeros_like(self._state)
         self.cpool = B.hsd_kv_pool(_ptr(self.k_pool), _ptr(self.v_pool), n_blocks, _ptr(self.free_list),
                                    _ptr(self.free_count))
 
@@ -143,6 +149,20 @@ class Engine:
         self.block_table.fill_(-1)
         self.status.zero_()
         B.hsd_kv_pool_init(self.stream, self.cpool)
+
+    def snapshot(self):
+        """Remembers the KV bookkeeping (free stack, lengths, block tables); cached K/V data is not copied."""
+        self._snapshot.copy_(self._state)
+
+    def restore(self):
+        """Returns the bookkeeping to the last snapshot (one small device copy on the current stream)."""
+        self._state.copy_(self._snapshot)
+
+    def profile(self, which: int, max_launches: int):
+        B.hsd_profile_enable(self.ctx, which, max_launches)
+
+    def profile_read(self):
+        return B.hsd_profile_read(self.ctx)
 
     def _make_batch(self, slots: Sequence[int], blocks: Sequence[np.ndarray], dump_rows=None,
                     with_outputs: bool = True, embeds: Optional[torch.Tensor] = None) -> B.hsd_batch:
@@ -224,6 +244,17 @@ class Engine:
         n, T = b.n_seq, b.total_q
         return VerifyOutput(n, T, self._cu.copy(), self.argmax[:T], self.margin[:T], self.accept_len[:n],
                             self.bonus[:n], self.logits_dump[:b.n_dump] if b.n_dump else None)
+
+    def prepare(self, slots: Sequence[int], blocks: Sequence[np.ndarray]) -> B.hsd_batch:
+        """Uploads a batch description once; verify_prepared/commit can then be replayed on it."""
+        b = self._make_batch(slots, blocks)
+        self._batch = b
+        return b
+
+    def verify_prepared(self, b: B.hsd_batch, mode: str = "region"):
+        fn = B.hsd_verify_region_batch if mode == "region" else B.hsd_verify_page
+        fn(self.ctx, self.stream, self.cpool, b, _ptr(self.ws), self.ws_bytes)
+        self._batch = b
 
     def override_acceptance(self, accept_len: np.ndarray, bonus: np.ndarray):
         """Test hook: replaces the device-side alpha/bonus of the last verify before commit."""
