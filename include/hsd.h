@@ -76,7 +76,10 @@ typedef struct hsd_weights {
   const void *const *w_down;     /* -> dev [d_model, d_ffn]                                */
 } hsd_weights;
 
-/* Paged KV cache.  k_pool and v_pool: dev [n_layers][n_blocks][n_kv_heads][16][64] in the model dtype.
+/* Paged KV cache.  k_pool and v_pool: dev [n_layers][n_blocks][n_kv_heads][1024] in the model dtype.  A K page
+ * is [16 tokens][64 dims]; a V page is stored transposed, [64 dims][16 token slots], token t in slot
+ * 8*((t>>2)&1) + 4*(t>>3) + (t&3) (the order the attention kernel's matrix-core operands want).  The contents
+ * are written and read only by the library.
  * free_list is a stack of free block ids, free_count its height; both live on the device and are
  * maintained by the library (hsd_kv_pool_init, verify, commit). */
 typedef struct hsd_kv_pool {

@@ -57,8 +57,8 @@ __global__ void __launch_bounds__(256) k_attn_simple(int n_q_heads, RowMeta meta
       float pb = __shfl(pj, jj, kWave);
       int bb = __shfl(blk, jj, kWave);
       if (bb >= 0) {
-        const T *vp = vpool + kv_block_offset(kv, bb, kvh) + ((j0 + jj) % kBlk) * kHd;
-        acc = fmaf(pb, to_f32(vp[lane]), acc);
+        const T *vp = vpool + kv_block_offset(kv, bb, kvh) + kv_v_elem((j0 + jj) % kBlk, lane);
+        acc = fmaf(pb, to_f32(vp[0]), acc);
       }
     }
     m = m_new;

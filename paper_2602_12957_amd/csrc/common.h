@@ -118,11 +118,18 @@ struct PagedKV {
   int32_t layer;
 };
 
-// Element offset of (layer, block, kv head, slot 0, dim 0) in a pool laid out
-// [n_layers][n_blocks][n_kv_heads][16][64].
+// Element offset of the (layer, block, kv head) page in a pool laid out [n_layers][n_blocks][n_kv_heads][1024].
+// A K page is [16 tokens][64 dims]; a V page is [64 dims][16 token slots] (see kv_v_slot).
 __device__ __forceinline__ size_t kv_block_offset(const PagedKV &kv, int block, int kvh) {
   return ((static_cast<size_t>(kv.layer) * kv.n_blocks + block) * kv.n_kv_heads + kvh) * (kBlk * kHd);
 }
+
+// The V pages are stored transposed, [dim][16 token slots], with the tokens of a page in the order
+// 0-3, 8-11, 4-7, 12-15: the order in which one lane half of a 32x32 MFMA result holds 16 consecutive keys,
+// so that the attention kernel can feed probabilities and V^T to the second product without any shuffle.
+__device__ __forceinline__ int kv_v_slot(int tok) { return ((tok >> 2) & 1) * 8 + (tok >> 3) * 4 + (tok & 3); }
+// element offset of V(token, dim) inside a (block, kv head) page
+__device__ __forceinline__ int kv_v_elem(int tok, int dim) { return dim * kBlk + kv_v_slot(tok); }
 
 // Block id holding position `pos` of sequence s, or -1 if the table has no valid block there.
 __device__ __forceinline__ int kv_lookup_block(const PagedKV &kv, int s, int pos) {

@@ -39,10 +39,15 @@ struct EpiQKV {
     if (b < 0) return;
     bool is_k = head < n_q_heads + n_kv_heads;
     int kvh = is_k ? head - n_q_heads : head - n_q_heads - n_kv_heads;
-    T *pool = static_cast<T *>(is_k ? kv.k_pool : kv.v_pool);
-    T *dst = pool + kv_block_offset(kv, b, kvh) + (pos % kBlk) * kHd + dim;
-    dst[0] = from_f32<T>(lo);
-    dst[32] = from_f32<T>(hi);
+    if (is_k) {
+      T *dst = static_cast<T *>(kv.k_pool) + kv_block_offset(kv, b, kvh) + (pos % kBlk) * kHd + dim;
+      dst[0] = from_f32<T>(lo);
+      dst[32] = from_f32<T>(hi);
+    } else {
+      T *dst = static_cast<T *>(kv.v_pool) + kv_block_offset(kv, b, kvh) + kv_v_elem(pos % kBlk, dim);
+      dst[0] = from_f32<T>(lo);
+      dst[32 * kBlk] = from_f32<T>(hi);
+    }
   }
 };
 

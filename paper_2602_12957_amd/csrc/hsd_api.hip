@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "../../include/hsd.h"
+#include "attn_mfma.h"
 #include "attn_simple.h"
 #include "common.h"
 #include "epilogues.h"
@@ -42,14 +43,14 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Workspace {
   float *x;
   void *h, *q, *a, *u;
-  int32_t *row_seq, *row_pos, *dump_slot;
+  int32_t *row_seq, *row_pos, *dump_slot, *tile_cu;
   float2 *rope_cs;
   Top2 *lm_part;
   size_t total;
 };
 
 // Carves the workspace; with base == nullptr only the size is computed.
-Workspace carve(const hsd_model_desc &d, int64_t T, int64_t /*n_seq*/, void *base) {
+Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
   const size_t es = d.dtype == HSD_BF16 ? 2 : 4;
   const size_t qdim = static_cast<size_t>(d.n_q_heads) * d.head_dim;
   size_t off = 0;
@@ -67,6 +68,7 @@ Workspace carve(const hsd_model_desc &d, int64_t T, int64_t /*n_seq*/, void *bas
   w.row_seq = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.row_pos = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.dump_slot = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
+  w.tile_cu = reinterpret_cast<int32_t *>(take((n_seq + 1) * sizeof(int32_t)));
   w.rope_cs = reinterpret_cast<float2 *>(take(T * 32 * sizeof(float2)));
   w.lm_part = reinterpret_cast<Top2 *>(take(T * (d.vocab / 64) * sizeof(Top2)));
   w.total = off;
@@ -137,6 +139,44 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int M, int N, int K, const v
   return HSD_OK;
 }
 
+// Verification attention: bf16 goes to the MFMA kernel when the GQA group size fits its wave mapping.
+template <typename T>
+int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, const RowMeta &meta, const PagedKV &kv,
+                     const Workspace &ws) {
+  const hsd_model_desc &d = ctx->desc;
+  const int group = d.n_q_heads / d.n_kv_heads;
+  if constexpr (std::is_same<T, bf16>::value) {
+    if (!ctx->force_simple && (group == 1 || group == 2 || group % 4 == 0)) {
+      const int g4 = group >= 4 ? 4 : group;
+      const int q_tile = 32 * (4 / g4);
+      const int max_tiles = b->total_q / q_tile + b->n_seq;
+      const dim3 grid(max_tiles, d.n_kv_heads * ((group + g4 - 1) / g4));
+      const size_t smem = 2 * kAttnStage * sizeof(uint16_t);
+      const bf16 *q = static_cast<const bf16 *>(ws.q);
+      bf16 *o = static_cast<bf16 *>(ws.a);
+      if (kv.layer == 0) {  // the tile map depends on the batch only: built once per pass
+        hipLaunchKernelGGL(k_attn_tiles, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, q_tile, ws.tile_cu);
+        HSD_LAUNCH_CHECK();
+      }
+      if (g4 == 4)
+        hipLaunchKernelGGL((k_attn_mfma<4>), grid, dim3(256), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
+                           b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);
+      else if (g4 == 2)
+        hipLaunchKernelGGL((k_attn_mfma<2>), grid, dim3(256), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
+                           b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);
+      else
+        hipLaunchKernelGGL((k_attn_mfma<1>), grid, dim3(256), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
+                           b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);
+      HSD_LAUNCH_CHECK();
+      return HSD_OK;
+    }
+  }
+  hipLaunchKernelGGL((k_attn_simple<T>), dim3(b->total_q, (d.n_q_heads + 3) / 4), dim3(256), 0, st, d.n_q_heads, meta,
+                     kv, static_cast<const T *>(ws.q), static_cast<T *>(ws.a));
+  HSD_LAUNCH_CHECK();
+  return HSD_OK;
+}
+
 template <typename T>
 int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_batch *b, void *ws_base, bool page_mode,
             bool with_head) {
@@ -174,9 +214,7 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
     }
     {
       ProfScope ps(ctx, st, HSD_PROF_ATTENTION);
-      hipLaunchKernelGGL((k_attn_simple<T>), dim3(Tq, (d.n_q_heads + 3) / 4), dim3(256), 0, st, d.n_q_heads, meta,
-                         kv, static_cast<const T *>(ws.q), static_cast<T *>(ws.a));
-      HSD_LAUNCH_CHECK();
+      if ((rc = launch_attention<T>(ctx, st, b, meta, kv, ws))) return rc;
     }
     EpiResidual er{ws.x, d.d_model};
     {

@@ -209,14 +209,19 @@ def test_metamorphic_paging_batching_rollback(desc):
     sl = eng.seq_len.cpu().numpy()
     owned = set(int(b) for b in bt.ravel() if b >= 0)
     poison = float("nan") if desc.dtype == "fp32" else 0x7FC0     # bf16 NaN bit pattern held in the int16 view
-    for pool in (eng.k_pool, eng.v_pool):
-        p = pool.view(desc.n_layers, eng.n_blocks, desc.n_kv_heads, 16, 64)
+    v_slot = lambda t: ((t >> 2) & 1) * 8 + (t >> 3) * 4 + (t & 3)      # token order inside a transposed V page
+    for pool, is_v in ((eng.k_pool, False), (eng.v_pool, True)):
+        p = pool.view(desc.n_layers, eng.n_blocks, desc.n_kv_heads, 64, 16) if is_v else \
+            pool.view(desc.n_layers, eng.n_blocks, desc.n_kv_heads, 16, 64)
         for b in range(eng.n_blocks):
             if b not in owned:
                 p[:, b] = poison
         for s in range(3):
-            if sl[s] % 16:
-                p[:, int(bt[s, sl[s] // 16]), :, sl[s] % 16:, :] = poison
+            for tok in range(sl[s] % 16, 16 if sl[s] % 16 else 0):
+                if is_v:
+                    p[:, int(bt[s, sl[s] // 16]), :, :, v_slot(tok)] = poison
+                else:
+                    p[:, int(bt[s, sl[s] // 16]), :, tok, :] = poison
     again = _one_round(eng, [0, 1, 2], blocks)
     np.testing.assert_array_equal(again[0], ref[0])
     np.testing.assert_array_equal(again[1], ref[1])
