@@ -73,6 +73,11 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=4, help="sequences of the workload the oracle is timed on (0 = skip)")
     ap.add_argument("--profile-kernel", type=str, default="gate_up",
                     choices=["gate_up", "qkv", "attention", "o", "down", "lm_head", "rmsnorm", "none"])
+    ap.add_argument("--random-target", action="store_true",
+                    help="profiling aid: skip the greedy target generation and corrupt a random token sequence instead "
+                         "(same shapes and kernels; acceptance lengths are then meaningless)")
+    ap.add_argument("--breakdown", action="store_true",
+                    help="after the timed region, time every kernel class in turn (extra steps) and report avg us per launch")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -100,9 +105,12 @@ def main():
 
     # --- set-up (untimed): prefix prefill, greedy target generation on the GPU path itself, prefill again
     eng.prefill(slots, toks, embs)
-    target = eng.greedy_decode(slots, pend, k_max)
-    eng.reset()
-    eng.prefill(slots, toks, embs)
+    if args.random_target:
+        target = np.random.default_rng(seed).integers(0, desc.vocab, size=(n, k_max)).astype(np.int32)
+    else:
+        target = eng.greedy_decode(slots, pend, k_max)
+        eng.reset()
+        eng.prefill(slots, toks, embs)
     torch.cuda.synchronize()
     drafts = [W.corrupt_draft(target[i][:sp.draft_len], sp.corrupt_p, desc.vocab, seed, f"cfg{cfg_index}.{sp.seq_id}")[0]
               for i, sp in enumerate(specs)]
@@ -163,6 +171,19 @@ def main():
         "gemm_tflops_whole_step": round(gemm_flops_step / (ms_step * 1e-3) / 1e12, 1),
         "roofline": roofline,
     }
+    if args.breakdown:
+        bd = {}
+        for name, cls in prof_map.items():
+            if cls == B.HSD_PROF_NONE:
+                continue
+            eng.profile(cls, 4 * desc.n_layers * 3 + 8)
+            for _ in range(3):
+                step()
+            cnt, ms = eng.profile_read()
+            bd[name] = {"launches_per_step": cnt // 3, "avg_us": round(ms / max(cnt, 1) * 1e3, 2),
+                        "us_per_step": round(ms / 3 * 1e3, 1)}
+        eng.profile(B.HSD_PROF_NONE, 0)
+        out["breakdown"] = bd
     if args.cpu_sample > 0:
         out["cpu_baseline"] = cpu_baseline(W, desc, weights, seed, specs, drafts, pend, min(args.cpu_sample, n))
     eng.close()

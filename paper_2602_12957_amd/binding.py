@@ -8,6 +8,8 @@ import torch  # noqa: F401
 
 from .build import LIB_PATH
 
+LIB_PATH = os.environ.get("HSD_LIB_PATH", LIB_PATH)   # experiments: load an alternative build of the library
+
 if not os.path.exists(LIB_PATH):
     raise ImportError(
         f"{LIB_PATH} is missing: build it first (python -m paper_2602_12957_amd.build, or "

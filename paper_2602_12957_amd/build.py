@@ -13,16 +13,16 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, defines=(), out_path: str = LIB_PATH) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, os.path.join(CSRC, "hsd_api.hip"), "-o", LIB_PATH + ".tmp"]
+    cmd = [hipcc, *HIPCC_FLAGS, *[f"-D{d}" for d in defines], os.path.join(CSRC, "hsd_api.hip"), "-o", out_path + ".tmp"]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
-    os.replace(LIB_PATH + ".tmp", LIB_PATH)
+    os.replace(out_path + ".tmp", out_path)
     if verbose:
-        print("built", LIB_PATH)
-    return LIB_PATH
+        print("built", out_path)
+    return out_path
 
 
 if __name__ == "__main__":

@@ -2,22 +2,22 @@
 //
 // Both operands are K-contiguous (activations [M,K], weights [N,K]), which is what the MFMA operand
 // layout wants: lane l of v_mfma_f32_32x32x16_bf16 supplies 8 consecutive k of row (l % 32), k-group
-// (l / 32).  A 256-thread workgroup (4 waves, 2x2) computes a 128x128 tile; each wave a 64x64 tile as
-// 2x2 MFMA tiles of 32x32, accumulators 64 fp32 registers per lane.  K is consumed in slices of BK
-// staged through LDS (rows padded by 16 bytes so that the 128-bit operand reads of 8 consecutive lanes
-// cover all banks), double buffered: global loads of slice k+1 are issued before the MFMAs of slice k.
+// (l / 32).  A workgroup of WM x WN waves computes a BP x BQ tile; each wave a (BP/WM) x (BQ/WN) tile made
+// of 32x32 MFMA tiles.  K is consumed in slices of BK staged through LDS (rows padded by 16 bytes so that
+// the 128-bit operand reads of 8 consecutive lanes cover all banks), double buffered: the global loads of
+// slice k+1 are issued before the MFMAs of slice k and written to the other LDS stage after them.
 //
 // The kernel is written on two K-contiguous matrices P (MFMA "i" side) and Q ("j" side).  In the 32x32
 // result tile, lane l holds column j = l % 32 and rows i = 8*(v/4) + 4*(l/32) + v%4 for register v.
-//  - normal mode  (P = activations, Q = weights): a lane owns one output column and many rows; the two
+//  - normal mode  (P = activations, Q = weights): a lane owns one output column and many rows; two adjacent
 //    N sub-tiles of a wave are columns n and n+32 of the same head -> rotary pairs stay in one lane.
 //  - swapped mode (P = weights, Q = activations): a lane owns one token and many vocabulary entries, so
 //    the LM-head arg-max folds in registers with no cross-lane traffic.
-//  - dual mode: the Q tile interleaves 32 gate rows and 32 up rows per wave, so gate and up of the same
-//    output element sit in the same lane and register (SwiGLU in place).
+//  - dual mode: the Q tile alternates 32 gate rows and 32 up rows, so gate and up of the same output
+//    element sit in the same lane and register index of adjacent sub-tiles (SwiGLU in place).
 //
 // Workgroups are numbered so that the 8 XCDs (round-robin over workgroup ids) each walk a contiguous
-// range of tiles, M-tile fastest: consecutive tiles on one XCD share the weight tile in that XCD's L2.
+// range of tiles, activation tile fastest: consecutive tiles on one XCD share the weight tile in its L2.
 #pragma once
 
 #include "common.h"
@@ -27,14 +27,22 @@ namespace hsd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // 16-byte staging register (native vector: stays in VGPRs)
 
-constexpr int kGemmBM = 128, kGemmBN = 128;
+enum GemmMode { kModeNormal = 0, kModeDual = 1, kModeSwapLM = 2 };
 
-template <int BK>
-struct GemmSmem {
-  static constexpr int kStride = BK + 8;  // bf16 elements per LDS row
-  static constexpr int kTile = 128 * kStride;
-  static constexpr int kBytes = 2 /*stages*/ * 2 /*P,Q*/ * kTile * 2;
+template <int BP_, int BQ_, int BK_, int WM_, int WN_>
+struct GemmCfg {
+  static constexpr int BP = BP_, BQ = BQ_, BK = BK_, WM = WM_, WN = WN_;
+  static constexpr int kThreads = 64 * WM * WN;
+  static constexpr int TM = BP / WM / 32, TN = BQ / WN / 32;  // 32x32 MFMA tiles per wave
+  static constexpr int kStride = BK + 8;                      // bf16 elements per LDS row
+  static constexpr int kStage = (BP + BQ) * kStride;          // bf16 elements per stage
+  static constexpr int kSmemBytes = 2 * kStage * 2;
+  static constexpr int kChunks = BK / 8;                      // 16-byte chunks per tile row
+  static constexpr int kLoadsP = BP * kChunks / kThreads, kLoadsQ = BQ * kChunks / kThreads;
+  static_assert(BP % (WM * 32) == 0 && BQ % (WN * 64) == 0, "wave tile must be made of 32-row / 64-col groups");
+  static_assert(BP * kChunks % kThreads == 0 && BQ * kChunks % kThreads == 0, "tile loads must divide evenly");
 };
 
 __device__ __forceinline__ void xcd_tile(int pid, int tiles_fast, int n_tiles, int &t_fast, int &t_slow) {
@@ -45,127 +53,190 @@ __device__ __forceinline__ void xcd_tile(int pid, int tiles_fast, int n_tiles, i
   t_slow = p / tiles_fast;
 }
 
-enum GemmMode { kModeNormal = 0, kModeDual = 1, kModeSwapLM = 2 };
+// Tile counts for (M, N) in a mode: activation tiles first, weight tiles second.
+template <typename Cfg, int MODE>
+__host__ __device__ inline void gemm_tiles(int M, int N, int &tiles_act, int &tiles_w) {
+  if (MODE == kModeSwapLM) {
+    tiles_act = (M + Cfg::BQ - 1) / Cfg::BQ;
+    tiles_w = (N + Cfg::BP - 1) / Cfg::BP;
+  } else if (MODE == kModeDual) {
+    tiles_act = (M + Cfg::BP - 1) / Cfg::BP;
+    tiles_w = (2 * N + Cfg::BQ - 1) / Cfg::BQ;
+  } else {
+    tiles_act = (M + Cfg::BP - 1) / Cfg::BP;
+    tiles_w = (N + Cfg::BQ - 1) / Cfg::BQ;
+  }
+}
 
-// grid: 1-D, ceil(M/128) * (N_tiles) workgroups; N_tiles = N/128 (normal, swapped; N padded up) or
-// N/64 (dual, N = number of output columns).
-template <int BK, int MODE, typename Epi>
-__global__ void __launch_bounds__(256) k_gemm_mfma(int M, int N, int K, const bf16 *__restrict__ A,
-                                                   const bf16 *__restrict__ W, Epi epi) {
-  using S = GemmSmem<BK>;
+// grid: 1-D, tiles_act * tiles_w workgroups of Cfg::kThreads threads, Cfg::kSmemBytes dynamic LDS.
+// N is the number of output columns (for dual mode the weight matrix has 2N rows: gate | up).
+template <typename Cfg, int MODE, typename Epi>
+__global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K, const bf16 *__restrict__ A,
+                                                             const bf16 *__restrict__ W, Epi epi) {
+  constexpr int BP = Cfg::BP, BQ = Cfg::BQ, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN, LS = Cfg::kStride;
+  constexpr int NT = Cfg::kThreads, CH = Cfg::kChunks;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   uint16_t *smem = reinterpret_cast<uint16_t *>(smem_raw);
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int tiles_m = (M + kGemmBM - 1) / kGemmBM;
-  const int tiles_n = (MODE == kModeDual) ? N / 64 : (N + kGemmBN - 1) / kGemmBN;
-  int tm, tn;
-  xcd_tile(blockIdx.x, tiles_m, tiles_m * tiles_n, tm, tn);
-  const int m0 = tm * kGemmBM;
-  const int n0 = tn * ((MODE == kModeDual) ? 64 : kGemmBN);
+  const int wi = wave / Cfg::WN, wj = wave % Cfg::WN;
+  int tiles_act, tiles_w, ta, tw;
+  gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
+  xcd_tile(blockIdx.x, tiles_act, tiles_act * tiles_w, ta, tw);
+  // first activation row / first output column of this tile
+  const int m0 = ta * ((MODE == kModeSwapLM) ? BQ : BP);
+  const int n0 = tw * ((MODE == kModeSwapLM) ? BP : ((MODE == kModeDual) ? BQ / 2 : BQ));
 
-  // ---- which global row feeds tile row r of P and of Q
-  auto act_row = [&](int r) { return min(m0 + r, M - 1); };
-  auto w_row = [&](int r) {
-    if (MODE == kModeDual) {
-      int wn = r >> 6, sub = (r >> 5) & 1, j = r & 31;
-      return (sub ? N : 0) + n0 + wn * 32 + j;
-    }
-    return min(n0 + r, N - 1);
-  };
-
-  constexpr int kChunks = BK / 8;                 // 16-byte chunks per tile row
-  constexpr int kLoads = 128 * kChunks / 256;     // per thread per matrix
-  const bf16 *srcP[kLoads], *srcQ[kLoads];
-  int dst[kLoads];
+  // ---- global source of every 16-byte chunk this thread stages (fixed over the K loop)
+  const bf16 *srcP[Cfg::kLoadsP];
+  const bf16 *srcQ[Cfg::kLoadsQ];
 #pragma unroll
-  for (int i = 0; i < kLoads; ++i) {
-    int c = t + 256 * i, r = c / kChunks, kc = c % kChunks;
-    int ra = act_row(r), rw = w_row(r);
-    const bf16 *pa = A + static_cast<size_t>(ra) * K + kc * 8;
-    const bf16 *pw = W + static_cast<size_t>(rw) * K + kc * 8;
-    srcP[i] = (MODE == kModeSwapLM) ? pw : pa;
-    srcQ[i] = (MODE == kModeSwapLM) ? pa : pw;
-    dst[i] = r * S::kStride + kc * 8;
+  for (int i = 0; i < Cfg::kLoadsP; ++i) {
+    int c = t + NT * i, r = c / CH, kc = c % CH;
+    int row = (MODE == kModeSwapLM) ? min(n0 + r, N - 1) : min(m0 + r, M - 1);
+    srcP[i] = ((MODE == kModeSwapLM) ? W : A) + static_cast<size_t>(row) * K + kc * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < Cfg::kLoadsQ; ++i) {
+    int c = t + NT * i, r = c / CH, kc = c % CH;
+    int row;
+    if (MODE == kModeSwapLM) {
+      row = min(m0 + r, M - 1);
+    } else if (MODE == kModeDual) {
+      constexpr int WNC = BQ / Cfg::WN;  // Q rows per wave column
+      int wq = r / WNC, tn = (r % WNC) >> 5, j = r & 31;
+      row = min(((tn & 1) ? N : 0) + n0 + wq * (WNC / 2) + (tn >> 1) * 32 + j, 2 * N - 1);
+    } else {
+      row = min(n0 + r, N - 1);
+    }
+    srcQ[i] = ((MODE == kModeSwapLM) ? A : W) + static_cast<size_t>(row) * K + kc * 8;
   }
 
-  uint4 regP[kLoads], regQ[kLoads];
-  auto load_global = [&](int k0) {
+  floatx16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < kLoads; ++i) {
-      regP[i] = *reinterpret_cast<const uint4 *>(srcP[i] + k0);
-      regQ[i] = *reinterpret_cast<const uint4 *>(srcQ[i] + k0);
-    }
-  };
-  auto store_lds = [&](int stage) {
-    uint16_t *ps = smem + stage * 2 * S::kTile, *qs = ps + S::kTile;
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int i = 0; i < kLoads; ++i) {
-      *reinterpret_cast<uint4 *>(ps + dst[i]) = regP[i];
-      *reinterpret_cast<uint4 *>(qs + dst[i]) = regQ[i];
-    }
-  };
-
-  floatx16 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int wi = wave >> 1, wj = wave & 1;
-  const int frag_off_p = (wi * 64 + (lane & 31)) * S::kStride + (lane >> 5) * 8;
-  const int frag_off_q = (wj * 64 + (lane & 31)) * S::kStride + (lane >> 5) * 8;
+  const int frag_p = (wi * (BP / Cfg::WM) + (lane & 31)) * LS + (lane >> 5) * 8;
+  const int frag_q = BP * LS + (wj * (BQ / Cfg::WN) + (lane & 31)) * LS + (lane >> 5) * 8;
 
+  u32x4 regP[Cfg::kLoadsP], regQ[Cfg::kLoadsQ];
   const int nk = K / BK;
-  load_global(0);
-  store_lds(0);
+
+#define HSD_GEMM_LOAD(k0)                                                              \
+  _Pragma("unroll") for (int i = 0; i < Cfg::kLoadsP; ++i) regP[i] =                   \
+      *reinterpret_cast<const u32x4 *>(srcP[i] + (k0));                                \
+  _Pragma("unroll") for (int i = 0; i < Cfg::kLoadsQ; ++i) regQ[i] =                   \
+      *reinterpret_cast<const u32x4 *>(srcQ[i] + (k0));
+#define HSD_GEMM_STORE(stage)                                                          \
+  {                                                                                    \
+    uint16_t *sp = smem + (stage) * Cfg::kStage;                                       \
+    _Pragma("unroll") for (int i = 0; i < Cfg::kLoadsP; ++i) {                         \
+      int c = t + NT * i;                                                              \
+      *reinterpret_cast<u32x4 *>(sp + (c / CH) * LS + (c % CH) * 8) = regP[i];         \
+    }                                                                                  \
+    _Pragma("unroll") for (int i = 0; i < Cfg::kLoadsQ; ++i) {                         \
+      int c = t + NT * i;                                                              \
+      *reinterpret_cast<u32x4 *>(sp + BP * LS + (c / CH) * LS + (c % CH) * 8) = regQ[i]; \
+    }                                                                                  \
+  }
+
+  HSD_GEMM_LOAD(0)
+  HSD_GEMM_STORE(0)
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) load_global((kt + 1) * BK);
-    const uint16_t *ps = smem + (kt & 1) * 2 * S::kTile, *qs = ps + S::kTile;
+    if (kt + 1 < nk) {
+      HSD_GEMM_LOAD((kt + 1) * BK)
+    }
+    const uint16_t *sp = smem + (kt & 1) * Cfg::kStage;
+#ifndef HSD_GEMM_VARIANT
+#define HSD_GEMM_VARIANT 1
+#endif
+#if HSD_GEMM_VARIANT == 2
+    // all operand fragments of the slice are read up front, then the MFMAs run from registers
+    bf16x8 a[BK / 16][TM], b[BK / 16][TN];
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 a[2], b[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        a[i] = *reinterpret_cast<const bf16x8 *>(ps + frag_off_p + i * 32 * S::kStride + kk * 16);
-        b[i] = *reinterpret_cast<const bf16x8 *>(qs + frag_off_q + i * 32 * S::kStride + kk * 16);
-      }
+      for (int i = 0; i < TM; ++i) a[kk][i] = *reinterpret_cast<const bf16x8 *>(sp + frag_p + i * 32 * LS + kk * 16);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < TN; ++j) b[kk][j] = *reinterpret_cast<const bf16x8 *>(sp + frag_q + j * 32 * LS + kk * 16);
     }
-    if (kt + 1 < nk) store_lds((kt + 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][i], b[kk][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+#else
+    // operand fragments are double buffered in registers: the LDS reads of k-step kk+1 are issued before the
+    // MFMAs of k-step kk, into registers that no MFMA still in flight reads
+    bf16x8 a[2][TM], b[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a[0][i] = *reinterpret_cast<const bf16x8 *>(sp + frag_p + i * 32 * LS);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[0][j] = *reinterpret_cast<const bf16x8 *>(sp + frag_q + j * 32 * LS);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk + 1 < BK / 16) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          a[nxt][i] = *reinterpret_cast<const bf16x8 *>(sp + frag_p + i * 32 * LS + (kk + 1) * 16);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          b[nxt][j] = *reinterpret_cast<const bf16x8 *>(sp + frag_q + j * 32 * LS + (kk + 1) * 16);
+      }
+#if HSD_GEMM_VARIANT == 1
+      __builtin_amdgcn_sched_barrier(0);
+#endif
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+#if HSD_GEMM_VARIANT == 1
+      __builtin_amdgcn_sched_barrier(0);
+#endif
+    }
+#endif
+    if (kt + 1 < nk) {
+      HSD_GEMM_STORE((kt + 1) & 1)
+    }
     __syncthreads();
   }
+#undef HSD_GEMM_LOAD
+#undef HSD_GEMM_STORE
 
   // ---- epilogue
   const int col = lane & 31, half = lane >> 5;
   if constexpr (MODE == kModeSwapLM) {
-    // i side = vocabulary rows, j side = tokens: fold the lane's 2x16 values per token, merge the two lane halves
+    // i side = vocabulary rows, j side = tokens: fold the lane's TM*16 values per token, merge the lane halves
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      int m = m0 + wj * 64 + j * 32 + col;
+    for (int j = 0; j < TN; ++j) {
+      const int m = m0 + wj * (BQ / Cfg::WN) + j * 32 + col;
       Top2 tp = top2_init();
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          int n = n0 + wi * 64 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+          int n = n0 + wi * (BP / Cfg::WM) + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
           top2_push(tp, acc[i][j][v], n);
         }
       if (epi.dump_slot != nullptr && m < M) {
         int sl = epi.dump_slot[m];
         if (sl >= 0) {
 #pragma unroll
-          for (int i = 0; i < 2; ++i)
+          for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-              int n = n0 + wi * 64 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+              int n = n0 + wi * (BP / Cfg::WM) + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
               epi.logits_dump[static_cast<size_t>(sl) * epi.vocab + n] = acc[i][j][v];
             }
         }
@@ -175,20 +246,23 @@ __global__ void __launch_bounds__(256) k_gemm_mfma(int M, int N, int K, const bf
       other.i1 = __shfl_xor(tp.i1, 32, kWave);
       other.m2 = __shfl_xor(tp.m2, 32, kWave);
       tp = top2_merge(tp, other);
-      if (half == 0 && m < M) epi.part[static_cast<size_t>(m) * epi.n_tiles + tn * 2 + wi] = tp;
+      if (half == 0 && m < M) epi.part[static_cast<size_t>(m) * epi.n_tiles + tw * Cfg::WM + wi] = tp;
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        int m = m0 + wi * 64 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+        const int m = m0 + wi * (BP / Cfg::WM) + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
         if (m >= M) continue;
-        if constexpr (MODE == kModeDual) {
-          epi.one2(m, n0 + wj * 32 + col, acc[i][0][v], acc[i][1][v]);
-        } else {
-          int n = n0 + wj * 64 + col;
-          if (n < N) epi.pair(m, n, acc[i][0][v], acc[i][1][v]);
+#pragma unroll
+        for (int j = 0; j < TN; j += 2) {
+          if constexpr (MODE == kModeDual) {
+            epi.one2(m, n0 + wj * (BQ / Cfg::WN / 2) + (j >> 1) * 32 + col, acc[i][j][v], acc[i][j + 1][v]);
+          } else {
+            int n = n0 + wj * (BQ / Cfg::WN) + j * 32 + col;
+            if (n < N) epi.pair(m, n, acc[i][j][v], acc[i][j + 1][v]);
+          }
         }
       }
   }

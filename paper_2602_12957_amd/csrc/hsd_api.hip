@@ -28,7 +28,7 @@ struct hsd_ctx {
   std::vector<const void *> wqkv, wo, w_gate_up, w_down;
   int n_cu;
   bool force_simple;  // HSD_FORCE_SIMPLE=1: run the plain kernels also for bf16 (cross-check of the MFMA path)
-  int gemm_bk;        // HSD_GEMM_BK=32|64: K slice of the MFMA GEMM
+  int gemm_cfg;       // HSD_GEMM_CFG=0..4: tile configuration of the MFMA GEMM (experiments)
   // per-kernel timing (hsd_profile_*)
   int prof_which = HSD_PROF_NONE;
   int prof_used = 0;
@@ -103,11 +103,11 @@ struct GemmModeOf {
   static constexpr int value = Epi::kDual ? kModeDual : (std::is_same<Epi, EpiLMHead>::value ? kModeSwapLM : kModeNormal);
 };
 
-template <int BK, typename Epi>
-int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const void *W, const Epi &epi) {
+template <typename Cfg, typename Epi>
+int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi) {
   constexpr int MODE = GemmModeOf<Epi>::value;
-  auto kern = k_gemm_mfma<BK, MODE, Epi>;
-  constexpr int smem = GemmSmem<BK>::kBytes;
+  auto kern = k_gemm_mfma<Cfg, MODE, Epi>;
+  constexpr int smem = Cfg::kSmemBytes;
   static bool attr_done = false;  // per instantiation; the attribute is per function, setting it twice is harmless
   if (!attr_done) {
     if (smem > 48 * 1024 &&
@@ -116,20 +116,35 @@ int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const v
       return HSD_EHIP;
     attr_done = true;
   }
-  const int tiles_m = (M + kGemmBM - 1) / kGemmBM;
-  const int tiles_n = (MODE == kModeDual) ? N / 64 : (N + kGemmBN - 1) / kGemmBN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, st, M, N, K, static_cast<const bf16 *>(A),
-                     static_cast<const bf16 *>(W), epi);
+  if constexpr (MODE == kModeSwapLM) epi.n_tiles = (N / Cfg::BP) * Cfg::WM;
+  int tiles_act, tiles_w;
+  gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
+  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(Cfg::kThreads), smem, st, M, N, K,
+                     static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), epi);
   HSD_LAUNCH_CHECK();
   return HSD_OK;
 }
 
+// Tile configurations of the MFMA GEMM (HSD_GEMM_CFG selects one for experiments; default per call site).
+using GemmCfg0 = GemmCfg<128, 128, 64, 2, 2>;
+using GemmCfg1 = GemmCfg<256, 128, 64, 2, 2>;
+using GemmCfg2 = GemmCfg<256, 256, 64, 2, 2>;
+using GemmCfg3 = GemmCfg<256, 256, 32, 2, 2>;
+using GemmCfg4 = GemmCfg<128, 256, 64, 2, 2>;
+
 template <typename T, typename Epi>
-int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int M, int N, int K, const void *A, const void *W, const Epi &epi) {
+int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int M, int N, int K, const void *A, const void *W, const Epi &epi,
+                int n_tiles_simple = 0) {
+  (void)n_tiles_simple;
   if constexpr (std::is_same<T, bf16>::value) {
     if (!ctx->force_simple && K % 64 == 0) {
-      if (ctx->gemm_bk == 32) return launch_gemm_mfma<32>(st, M, N, K, A, W, epi);
-      return launch_gemm_mfma<64>(st, M, N, K, A, W, epi);
+      switch (ctx->gemm_cfg) {
+        case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi);
+        case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi);
+        case 3: return launch_gemm_mfma<GemmCfg3>(st, M, N, K, A, W, epi);
+        case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi);
+        default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi);
+      }
     }
   }
   dim3 grid(N / 64, (M + 63) / 64);
@@ -137,6 +152,22 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int M, int N, int K, const v
                      static_cast<const T *>(W), epi);
   HSD_LAUNCH_CHECK();
   return HSD_OK;
+}
+
+// Number of (row, column-tile) partial records the LM-head GEMM writes per row.
+template <typename T>
+int lm_head_tiles(const hsd_ctx *ctx) {
+  const int V = ctx->desc.vocab;
+  if (std::is_same<T, bf16>::value && !ctx->force_simple && ctx->desc.d_model % 64 == 0) {
+    switch (ctx->gemm_cfg) {
+      case 1: return V / GemmCfg1::BP * GemmCfg1::WM;
+      case 2: return V / GemmCfg2::BP * GemmCfg2::WM;
+      case 3: return V / GemmCfg3::BP * GemmCfg3::WM;
+      case 4: return V / GemmCfg4::BP * GemmCfg4::WM;
+      default: return V / GemmCfg0::BP * GemmCfg0::WM;
+    }
+  }
+  return V / 64;
 }
 
 // Verification attention: bf16 goes to the MFMA kernel when the GQA group size fits its wave mapping.
@@ -248,7 +279,7 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
     HSD_LAUNCH_CHECK();
     dump_slot = ws.dump_slot;
   }
-  const int n_tiles = d.vocab / 64;
+  const int n_tiles = lm_head_tiles<T>(ctx);
   EpiLMHead el{ws.lm_part, n_tiles, d.vocab, dump_slot, b->logits_dump};
   {
     ProfScope ps(ctx, st, HSD_PROF_GEMM_LM_HEAD);
@@ -380,8 +411,8 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   c->n_cu = prop.multiProcessorCount;
   const char *fs = std::getenv("HSD_FORCE_SIMPLE");
   c->force_simple = fs != nullptr && fs[0] == '1';
-  const char *bk = std::getenv("HSD_GEMM_BK");
-  c->gemm_bk = (bk != nullptr && std::atoi(bk) == 32) ? 32 : 64;
+  const char *gc = std::getenv("HSD_GEMM_CFG");
+  c->gemm_cfg = gc != nullptr ? std::atoi(gc) : 0;
   *out = c;
   return HSD_OK;
 }
