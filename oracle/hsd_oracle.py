@@ -101,19 +101,46 @@ def swiglu(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
 
 
 class KVCache:
-    """Contiguous per-layer key/value history of ONE sequence (the oracle has no paging)."""
+    """Contiguous per-layer key/value history of ONE sequence (the oracle has no paging).
+
+    Storage grows geometrically so that token-by-token decoding does not copy the history every step;
+    `k[l]` / `v[l]` are views of the first len(self) positions."""
 
     def __init__(self, n_layers: int, n_kv_heads: int, head_dim: int, dtype=np.float64):
-        self.k = [np.zeros((0, n_kv_heads, head_dim), dtype=dtype) for _ in range(n_layers)]
-        self.v = [np.zeros((0, n_kv_heads, head_dim), dtype=dtype) for _ in range(n_layers)]
+        self._n = 0
+        self._shape = (n_kv_heads, head_dim)
+        self._dtype = dtype
+        self._kbuf = [np.zeros((0,) + self._shape, dtype=dtype) for _ in range(n_layers)]
+        self._vbuf = [np.zeros((0,) + self._shape, dtype=dtype) for _ in range(n_layers)]
 
     def __len__(self) -> int:
-        return self.k[0].shape[0]
+        return self._n
+
+    def keys(self, layer: int, n: int) -> np.ndarray:
+        return self._kbuf[layer][:n]
+
+    def values(self, layer: int, n: int) -> np.ndarray:
+        return self._vbuf[layer][:n]
+
+    def write(self, layer: int, pos0: int, k: np.ndarray, v: np.ndarray) -> None:
+        """Stores keys/values of positions pos0 .. pos0+len(k)-1 of one layer."""
+        need = pos0 + k.shape[0]
+        if need > self._kbuf[layer].shape[0]:
+            cap = max(need, 2 * self._kbuf[layer].shape[0], 64)
+            for buf in (self._kbuf, self._vbuf):
+                grown = np.zeros((cap,) + self._shape, dtype=self._dtype)
+                grown[: self._n] = buf[layer][: self._n]
+                buf[layer] = grown
+        self._kbuf[layer][pos0:need] = k
+        self._vbuf[layer][pos0:need] = v
+
+    def advance(self, n_new: int) -> None:
+        self._n += n_new
 
     def truncate(self, n: int) -> None:
         """Rollback: forget every position >= n."""
-        self.k = [a[:n] for a in self.k]
-        self.v = [a[:n] for a in self.v]
+        assert n <= self._n
+        self._n = n
 
 
 def _cast_weights(weights: Dict, dtype) -> Dict:
@@ -147,13 +174,13 @@ def decoder_forward(desc, weights: Dict, x_rows: np.ndarray, cache: KVCache, dty
         v = qkv[:, (Hq + Hkv) * hd:].reshape(n, Hkv, hd)
         q = rope_rotate_half(q, positions, desc.rope_theta)
         k = rope_rotate_half(k, positions, desc.rope_theta)
-        cache.k[l] = np.concatenate([cache.k[l], k], axis=0)
-        cache.v[l] = np.concatenate([cache.v[l], v], axis=0)
-        a = causal_gqa_attention(q, cache.k[l], cache.v[l], pos0)
+        cache.write(l, pos0, k, v)
+        a = causal_gqa_attention(q, cache.keys(l, pos0 + n), cache.values(l, pos0 + n), pos0)
         x = x + a.reshape(n, Hq * hd) @ lay["wo"].T
         h = rmsnorm(x, lay["ffn_norm"], desc.rms_eps)
         gu = h @ lay["w_gate_up"].T
         x = x + swiglu(gu[:, : desc.d_ffn], gu[:, desc.d_ffn:]) @ lay["w_down"].T
+    cache.advance(n)
     if not want_logits:
         return None
     return rmsnorm(x, w["final_norm"], desc.rms_eps) @ w["lm_head"].T

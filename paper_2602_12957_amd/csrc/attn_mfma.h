@@ -46,11 +46,17 @@ union Frag8 {
   bf16x8 v;
   uint16_t h[8];
 };
+typedef float floatx8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 // G4 = query heads of one kv head handled per workgroup (1, 2 or 4); 4/G4 row sub-tiles of 32 queries.
-// grid: (upper bound of query tiles, n_kv_heads * ceil(group / G4)), block 256, dynamic LDS 2 * kAttnStage * 2 B.
+// The workgroup has 8 waves: waves w and w+4 own the same 32 queries and split every 64-key tile between them
+// (keys 0-31 / 32-63), which doubles the waves in flight per query tile; their partial (max, sum, O^T) are merged
+// through LDS at the end, always in the same order, so results do not depend on timing.
+// grid: (upper bound of query tiles, n_kv_heads * ceil(group / G4)), block 512, dynamic LDS 2 * kAttnStage * 2 B.
 template <int G4>
-__global__ void __launch_bounds__(256) k_attn_mfma(int n_seq, int n_q_heads, const int32_t *__restrict__ cu_q,
+__global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, const int32_t *__restrict__ cu_q,
                                                    const int32_t *__restrict__ seq_slot, int n_slots,
                                                    const int32_t *__restrict__ seq_len,
                                                    const int32_t *__restrict__ tile_cu, PagedKV kv,
@@ -73,8 +79,9 @@ __global__ void __launch_bounds__(256) k_attn_mfma(int n_seq, int n_q_heads, con
   const int group = n_q_heads / kv.n_kv_heads, hb = (group + G4 - 1) / G4;
   const int kvh = blockIdx.y / hb, hgrp = blockIdx.y % hb;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5, qj = lane & 31;
-  const int head = kvh * group + hgrp * G4 + (wave % G4);
-  const int row0 = tile_in_seq * QT + (wave / G4) * 32;          // first query row (within the block) of this wave
+  const int wq = wave & 3, kh = wave >> 2;                         // query-set index, key half of each tile
+  const int head = kvh * group + hgrp * G4 + (wq % G4);
+  const int row0 = tile_in_seq * QT + (wq / G4) * 32;              // first query row (within the block) of this wave
   const bool wave_active = row0 < Lq;
   const int my_row = min(row0 + qj, Lq - 1);
   const int pos_j = S + my_row;                                    // absolute position of the lane's query
@@ -94,46 +101,41 @@ __global__ void __launch_bounds__(256) k_attn_mfma(int n_seq, int n_q_heads, con
 
   const bf16 *kpool = static_cast<const bf16 *>(kv.k_pool);
   const bf16 *vpool = static_cast<const bf16 *>(kv.v_pool);
-  uint4 rk[2], rv[2];
+  // Staging: thread t moves one 16-byte piece of K (key t/8, piece t%8) and one of V^T (page t/128, dim
+  // (t%128)/2, half row t%2) per tile; both lie in page t/128 of the tile.  Page ids are fetched one tile ahead
+  // of the data they address, so the K/V loads of the next tile never wait behind a dependent block-table read.
+  const int key = t >> 3, ch = t & 7, pg = t >> 7, vd = (t & 127) >> 1, hf = t & 1;
+  uint4 rk, rv;
+  int bid;
+  auto fetch_id = [&](int kt) {
+    const int p0 = kt * kAttnKeys + pg * kBlk;
+    bid = (p0 < n_valid) ? kv_lookup_block(kv, slot, p0) : -1;
+  };
   auto prefetch = [&](int kt) {
     const int kb = kt * kAttnKeys;
+    rk = make_uint4(0, 0, 0, 0);
+    Frag8 f;
+    f.u = make_uint4(0, 0, 0, 0);
+    if (bid >= 0) {
+      const size_t off = kv_block_offset(kv, bid, kvh);
+      rk = *reinterpret_cast<const uint4 *>(kpool + off + (key & 15) * kHd + ch * 8);
+      f.u = *reinterpret_cast<const uint4 *>(vpool + off + vd * kBlk + hf * 8);
+      if (kb + pg * kBlk + kBlk > n_valid) {
+        // last, partly filled page: slots of positions that hold no data of this sequence must read as 0
+        // (their probability is 0, but 0 * stale-NaN would poison the product)
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      // K: chunk c -> key c/8, 16-byte piece c%8
-      int c = t + 256 * i, key = c >> 3, ch = c & 7;
-      int blk = (kb + key < n_valid) ? kv_lookup_block(kv, slot, kb + key) : -1;
-      rk[i] = make_uint4(0, 0, 0, 0);
-      if (blk >= 0)
-        rk[i] = *reinterpret_cast<const uint4 *>(kpool + kv_block_offset(kv, blk, kvh) + (key & 15) * kHd + ch * 8);
-      // V^T: chunk c -> page c/128, dim (c%128)/2, half row c%2
-      int pg = c >> 7, cc = c & 127, d = cc >> 1, hf = cc & 1;
-      int vblk = (kb + pg * kBlk < n_valid) ? kv_lookup_block(kv, slot, kb + pg * kBlk) : -1;
-      Frag8 f;
-      f.u = make_uint4(0, 0, 0, 0);
-      if (vblk >= 0) {
-        f.u = *reinterpret_cast<const uint4 *>(vpool + kv_block_offset(kv, vblk, kvh) + d * kBlk + hf * 8);
-        if (kb + pg * kBlk + kBlk > n_valid) {
-          // last, partly filled page: slots of positions that hold no data of this sequence must read as 0
-          // (their probability is 0, but 0 * stale-NaN would poison the product)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            int tok = (e < 4) ? 4 * hf + e : 8 + 4 * hf + (e - 4);
-            if (kb + pg * kBlk + tok >= n_valid) f.h[e] = 0;
-          }
+        for (int e = 0; e < 8; ++e) {
+          int tok = (e < 4) ? 4 * hf + e : 8 + 4 * hf + (e - 4);
+          if (kb + pg * kBlk + tok >= n_valid) f.h[e] = 0;
         }
       }
-      rv[i] = f.u;
     }
+    rv = f.u;
   };
   auto store_lds = [&](int stage) {
     uint16_t *ks = smem + stage * kAttnStage, *vt = ks + kAttnKeys * kKsStride;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      int c = t + 256 * i, key = c >> 3, ch = c & 7;
-      *reinterpret_cast<uint4 *>(ks + key * kKsStride + ch * 8) = rk[i];
-      int pg = c >> 7, cc = c & 127, d = cc >> 1, hf = cc & 1;
-      *reinterpret_cast<uint4 *>(vt + (pg * kHd + d) * kVtStride + hf * 8) = rv[i];
-    }
+    *reinterpret_cast<uint4 *>(ks + key * kKsStride + ch * 8) = rk;
+    *reinterpret_cast<uint4 *>(vt + (pg * kHd + vd) * kVtStride + hf * 8) = rv;
   };
 
   floatx16 o[2];
@@ -144,85 +146,106 @@ __global__ void __launch_bounds__(256) k_attn_mfma(int n_seq, int n_q_heads, con
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = 0.125f * 1.4426950408889634f;  // 1/sqrt(64) * log2(e): softmax in base 2
 
+  fetch_id(0);
   prefetch(0);
+  if (n_tiles > 1) fetch_id(1);
   store_lds(0);
   __syncthreads();
   for (int kt = 0; kt < n_tiles; ++kt) {
-    if (kt + 1 < n_tiles) prefetch(kt + 1);
-    const int kb = kt * kAttnKeys;
+    if (kt + 1 < n_tiles) {
+      prefetch(kt + 1);
+      if (kt + 2 < n_tiles) fetch_id(kt + 2);
+    }
+    const int kb = kt * kAttnKeys + kh * 32;   // first key of this wave's half tile
     if (wave_active && kb < wave_keys) {
       const uint16_t *ks = smem + (kt & 1) * kAttnStage, *vt = ks + kAttnKeys * kKsStride;
-      floatx16 st[2];
+      floatx16 st;
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
+      for (int v = 0; v < 16; ++v) st[v] = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) st[tt][v] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          bf16x8 a = *reinterpret_cast<const bf16x8 *>(ks + (tt * 32 + qj) * kKsStride + kk * 16 + half * 8);
-          st[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk].v, st[tt], 0, 0, 0);
-        }
+      for (int kk = 0; kk < 4; ++kk) {
+        bf16x8 a = *reinterpret_cast<const bf16x8 *>(ks + (kh * 32 + qj) * kKsStride + kk * 16 + half * 8);
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk].v, st, 0, 0, 0);
       }
-      const bool need_mask = kb + kAttnKeys - 1 > S + row0;
-      float mx = -INFINITY;
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
+      // scores stay unscaled; the softmax scale rides in the exponent's fused multiply-add
+      if (kb + 31 > S + row0) {  // half tile reaches past the wave's first query: causal mask (wave-uniform)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          float sv = st[tt][v] * sc;
-          if (need_mask) {
-            int key = kb + tt * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-            if (key > pos_j) sv = -INFINITY;
-          }
-          st[tt][v] = sv;
-          mx = fmaxf(mx, sv);
+          const int kpos = kb + 8 * (v >> 2) + 4 * half + (v & 3);
+          if (kpos > pos_j) st[v] = -INFINITY;
         }
+      }
+      float mx = st[0];
+#pragma unroll
+      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, st[v]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      const float m_new = fmaxf(m_run, mx);   // finite: key 0 is visible to every query
-      const float corr = exp2f(m_run - m_new);
+      const float m_new = fmaxf(m_run, mx);
+      // a query that has seen no visible key yet (its first keys lie in the other half tile) keeps max = -inf;
+      // the reference point 0 then yields p = 0 and corr = 0 without producing inf - inf
+      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+      const float corr = exp2f((m_run - m_ref) * sc);
+      const float msc = m_ref * sc;
       l_run *= corr;
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[i][v] *= corr;
-      Frag8 pf[2][2];
+      bf16x8 pf[2];
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
+      for (int kk = 0; kk < 2; ++kk) {
+        floatx8 pv;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float p = exp2f(st[tt][v] - m_new);
+        for (int e = 0; e < 8; ++e) {
+          const float p = exp2f(fmaf(st[8 * kk + e], sc, -msc));
           l_run += p;
-          pf[tt][v >> 3].h[v & 7] = f32_to_bf16(p);
+          pv[e] = p;
         }
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-          const int pg = 2 * tt + kk;
-#pragma unroll
-          for (int i = 0; i < 2; ++i) {
-            bf16x8 a = *reinterpret_cast<const bf16x8 *>(vt + (pg * kHd + i * 32 + qj) * kVtStride + half * 8);
-            o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[tt][kk].v, o[i], 0, 0, 0);
-          }
-        }
+        pf[kk] = __builtin_convertvector(pv, bf16x8);
+      }
       m_run = m_new;
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const int pgk = 2 * kh + kk;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          bf16x8 a = *reinterpret_cast<const bf16x8 *>(vt + (pgk * kHd + i * 32 + qj) * kVtStride + half * 8);
+          o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kk], o[i], 0, 0, 0);
+        }
+      }
     }
     if (kt + 1 < n_tiles) store_lds((kt + 1) & 1);
     __syncthreads();
   }
 
-  const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
-  if (wave_active && row0 + qj < Lq) {
-    const float inv = 1.0f / l_tot;
+  // ---- merge the two key halves of each query set through LDS (stage memory is free after the last barrier)
+  float *mrg = reinterpret_cast<float *>(smem_raw);   // [4 query sets][34][64 lanes]
+  l_run += __shfl_xor(l_run, 32, kWave);
+  if (kh == 1) {
+    float *dst = mrg + wq * 34 * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) dst[(i * 16 + v) * 64] = o[i][v];
+    dst[32 * 64] = m_run;
+    dst[33 * 64] = l_run;
+  }
+  __syncthreads();
+  if (kh == 0 && wave_active && row0 + qj < Lq) {
+    const float *src = mrg + wq * 34 * 64 + lane;
+    const float m_b = src[32 * 64], l_b = src[33 * 64];
+    const float m_tot = fmaxf(m_run, m_b);            // finite: key 0 belongs to half 0 of the first tile
+    const float ca = exp2f((m_run - m_tot) * sc);
+    const float cb = (m_b > -INFINITY) ? exp2f((m_b - m_tot) * sc) : 0.f;
+    const float inv = 1.0f / (l_run * ca + l_b * cb);
     bf16 *op = out + static_cast<size_t>(base + row0 + qj) * qdim + head * kHd;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        uint2 pk;
-        pk.x = f32_to_bf16(o[i][4 * g] * inv) | (static_cast<uint32_t>(f32_to_bf16(o[i][4 * g + 1] * inv)) << 16);
-        pk.y = f32_to_bf16(o[i][4 * g + 2] * inv) | (static_cast<uint32_t>(f32_to_bf16(o[i][4 * g + 3] * inv)) << 16);
-        *reinterpret_cast<uint2 *>(op + i * 32 + 8 * g + 4 * half) = pk;
+        floatx4 ov;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ov[e] = (o[i][4 * g + e] * ca + src[(i * 16 + 4 * g + e) * 64] * cb) * inv;
+        *reinterpret_cast<bf16x4 *>(op + i * 32 + 8 * g + 4 * half) = __builtin_convertvector(ov, bf16x4);
       }
   }
 }

@@ -190,13 +190,13 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
         HSD_LAUNCH_CHECK();
       }
       if (g4 == 4)
-        hipLaunchKernelGGL((k_attn_mfma<4>), grid, dim3(256), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
+        hipLaunchKernelGGL((k_attn_mfma<4>), grid, dim3(512), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
                            b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);
       else if (g4 == 2)
-        hipLaunchKernelGGL((k_attn_mfma<2>), grid, dim3(256), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
+        hipLaunchKernelGGL((k_attn_mfma<2>), grid, dim3(512), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
                            b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);
       else
-        hipLaunchKernelGGL((k_attn_mfma<1>), grid, dim3(256), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
+        hipLaunchKernelGGL((k_attn_mfma<1>), grid, dim3(512), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
                            b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);
       HSD_LAUNCH_CHECK();
       return HSD_OK;

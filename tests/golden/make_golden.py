@@ -1,0 +1,127 @@
+"""Writes the stored expected values under tests/golden/ for the full-size workload configurations.
+
+Calls ONLY oracle/ (the CPU oracle) and workloads/ (seeded inputs); nothing here touches the HIP path.
+For every sequence of a configuration it stores, as JSON:
+  * the oracle's token-by-token greedy output ("target") and each step's top-1/top-2 margin: the sequence
+    the synthetic drafts are derived from;
+  * for each verification round of SpecDecode over the seeded corrupted draft (paper Section 3.2, Eq. 8-12):
+    draft offset, k, alpha, bonus, the model's top-1 token at every row, and every row's top-1/top-2 margin;
+  * for a few rows of round 1, the logits at a seeded sample of vocabulary columns plus each row's top-8
+    (value, index) pairs, for the element-wise logit comparison.
+
+Usage:  python tests/golden/make_golden.py --config 1 [--procs 4] [--max-rounds N]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+
+import oracle as O          # noqa: E402
+import workloads as W       # noqa: E402
+
+N_SAMPLE_ROWS = 4
+N_SAMPLE_COLS = 256
+
+
+def draft_for(cfg_index, desc, seed, sp, target):
+    fn = W.corrupt_draft_forced if sp.forced_different else W.corrupt_draft
+    return fn(target, sp.corrupt_p, desc.vocab, seed, f"cfg{cfg_index}.{sp.seq_id}")[0]
+
+
+def sample_positions(seed, cfg_index, seq_id, n_rows, vocab):
+    g = np.random.default_rng([seed, cfg_index, seq_id])
+    rows = np.unique(np.concatenate([[0, n_rows - 1], g.integers(0, n_rows, size=N_SAMPLE_ROWS - 2)]))
+    cols = np.sort(g.choice(vocab, size=N_SAMPLE_COLS, replace=False))
+    return rows, cols
+
+
+def one_sequence(args):
+    cfg_index, seed, sp, max_rounds, threads = args
+    try:
+        from threadpoolctl import threadpool_limits
+        threadpool_limits(threads)
+    except Exception:
+        pass
+    t0 = time.time()
+    desc = W.CONFIGS[cfg_index].model
+    weights = _WEIGHTS
+    vis, prompt = W.make_prefix(desc, seed, sp.seq_id, sp.n_visual, sp.n_prompt)
+    cache, pending = O.prefill(desc, weights, vis, prompt)
+    base_len = len(cache)
+    target, tmargin = O.greedy_decode(desc, weights, cache, pending, sp.draft_len, return_margins=True)
+    t1 = time.time()
+    cache.truncate(base_len)
+    draft = draft_for(cfg_index, desc, seed, sp, target)
+    rounds, committed = [], 0
+    pend = pending
+    samples = None
+    while committed < sp.draft_len and (max_rounds is None or len(rounds) < max_rounds):
+        rest = draft[committed:]
+        base = len(cache)
+        alpha, bonus, u_hat, logits = O.verify_block(desc, weights, cache, pend, rest)
+        cache.truncate(base + 1 + alpha)
+        margin = O.top2_margin(logits)
+        if not rounds:
+            rows, cols = sample_positions(seed, cfg_index, sp.seq_id, logits.shape[0], desc.vocab)
+            top_idx = np.argsort(-logits[rows], axis=1)[:, :8]
+            samples = {"rows": rows.tolist(), "cols": cols.tolist(),
+                       "values": [[float(f"{x:.9g}") for x in logits[r, cols]] for r in rows],
+                       "top8_idx": top_idx.tolist(),
+                       "top8_val": [[float(f"{logits[r, j]:.9g}") for j in top_idx[i]] for i, r in enumerate(rows)]}
+        rounds.append({"offset": committed, "k": int(len(rest)), "alpha": int(alpha), "bonus": int(bonus),
+                       "u_hat": u_hat.tolist(), "margin": [float(f"{m:.6g}") for m in margin]})
+        committed += alpha + 1
+        pend = bonus
+    print(f"  cfg{cfg_index} seq {sp.seq_id}: S={base_len} k={sp.draft_len} greedy {t1 - t0:.0f}s rounds {len(rounds)} "
+          f"total {time.time() - t0:.0f}s", flush=True)
+    return {"seq_id": sp.seq_id, "n_visual": sp.n_visual, "n_prompt": sp.n_prompt, "draft_len": sp.draft_len,
+            "cached_len": base_len, "pending": int(pending), "target": target.tolist(),
+            "target_margin": [float(f"{m:.6g}") for m in tmargin], "rounds": rounds,
+            "complete": committed >= sp.draft_len, "logit_samples": samples}
+
+
+_WEIGHTS = None
+
+
+def main():
+    global _WEIGHTS
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, required=True)
+    ap.add_argument("--procs", type=int, default=1)
+    ap.add_argument("--max-rounds", type=int, default=None)
+    ap.add_argument("--seqs", type=str, default=None, help="a:b slice of the configuration's sequences")
+    ap.add_argument("--out", type=str, default=None)
+    args = ap.parse_args()
+    seed = W.SEED_BASE
+    desc = W.CONFIGS[args.config].model
+    specs = W.draw_sequences(args.config, seed)
+    if args.seqs:
+        a, b = args.seqs.split(":")
+        specs = specs[int(a):int(b)]
+    _WEIGHTS = W.make_weights(desc, seed)
+    O.hsd_oracle._cast_weights(_WEIGHTS, np.float64)     # cast once, before forking
+    threads = max(1, (os.cpu_count() or 8) // args.procs)
+    jobs = [(args.config, seed, sp, args.max_rounds, threads) for sp in specs]
+    t0 = time.time()
+    if args.procs > 1:
+        import multiprocessing as mp
+        with mp.get_context("fork").Pool(args.procs) as pool:
+            seqs = pool.map(one_sequence, jobs, chunksize=1)
+    else:
+        seqs = [one_sequence(j) for j in jobs]
+    out = {"config": args.config, "seed": seed, "oracle_dtype": "float64", "generator": "tests/golden/make_golden.py",
+           "sequences": seqs}
+    path = args.out or os.path.join(os.path.dirname(os.path.abspath(__file__)), f"cfg{args.config}.json")
+    with open(path, "w") as f:
+        json.dump(out, f, separators=(",", ":"))
+    print(f"wrote {path} ({os.path.getsize(path) / 1e6:.2f} MB) in {time.time() - t0:.0f}s")
+
+
+if __name__ == "__main__":
+    main()
