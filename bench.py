@@ -92,8 +92,9 @@ def main():
     seed = args.seed or W.SEED_BASE
     n = len(specs)
     k_max = max(sp.draft_len for sp in specs)
-    maxb = max((sp.n_visual + sp.n_prompt + sp.draft_len + 1 + 15) // 16 + 1 for sp in specs)
-    n_blocks = sum((sp.n_visual + sp.n_prompt + sp.draft_len + 1 + 15) // 16 + 1 for sp in specs) + 8
+    # room for every sequence to grow by the longest draft: the untimed greedy generation advances all in lock step
+    maxb = max((sp.n_visual + sp.n_prompt + k_max + 1 + 15) // 16 + 1 for sp in specs)
+    n_blocks = sum((sp.n_visual + sp.n_prompt + k_max + 1 + 15) // 16 + 1 for sp in specs) + 8
     total_q = sum(sp.draft_len + 1 for sp in specs)
     eng = Engine(desc, weights, n_blocks, n, maxb, max(total_q, 4096))
     slots = list(range(n))

@@ -22,7 +22,13 @@ stack defines: pre-norm RMSNorm, rotary embedding with rotate-half pairing, grou
 attention, SwiGLU feed-forward, untied LM head, no biases.  tests/test_oracle_pins.py pins this
 forward against the Transformers implementation itself.
 
-Precision: every function takes `dtype` (default float64).  The paper states no precision.
+Precision: every function takes `dtype` (default float64).  The paper states no precision.  A decoder whose
+configuration says "bf16" stores its activations in bf16 between operators; `act_dtype="bf16"` makes the
+oracle round to the nearest bf16 value (ties to even) at exactly those storage points -- the normalised
+hidden state fed to each projection, q/k after the rotary embedding, v, the un-normalised attention
+probabilities entering the weighted sum of values, the attention output, the SwiGLU output -- while every
+sum is still formed in `dtype`.  With act_dtype=None nothing is rounded.  Decisions that floating point
+feeds (arg-max, acceptance) are compared with the HIP path at the HIP path's storage precision.
 
 Pins (tests/test_oracle_pins.py, tests/test_oracle_invariants.py): Transformers' LlamaForCausalLM
 logits and greedy generation; torch's scaled_dot_product_attention, rms_norm and silu; complex-number
@@ -38,7 +44,7 @@ from typing import Dict, List, Optional, Sequence, Tuple
 import numpy as np
 
 __all__ = [
-    "rmsnorm", "rope_rotate_half", "causal_gqa_attention", "swiglu", "KVCache", "decoder_forward",
+    "round_bf16", "rmsnorm", "rope_rotate_half", "causal_gqa_attention", "swiglu", "KVCache", "decoder_forward",
     "argmax_lowest_index", "top2_margin", "accept_longest_prefix", "verify_block", "greedy_decode",
     "prefill", "spec_decode", "RoundRecord",
 ]
@@ -47,6 +53,22 @@ __all__ = [
 # ----------------------------------------------------------------------------------------------
 # Decoder building blocks (Llama family as defined by the Transformers stack, paper Section 4.3)
 # ----------------------------------------------------------------------------------------------
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest bf16-representable value, ties to even (via the fp32 bit pattern); dtype of x is kept."""
+    f = np.ascontiguousarray(x, dtype=np.float32)
+    u = f.view(np.uint32)
+    r = ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)).view(np.float32)
+    return r.astype(np.asarray(x).dtype)
+
+
+def _act_round(act_dtype):
+    if act_dtype is None:
+        return lambda a: a
+    if act_dtype == "bf16":
+        return round_bf16
+    raise ValueError(f"unknown act_dtype {act_dtype!r}")
+
 
 def rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
     """y = x / sqrt(mean(x^2) + eps) * gain, over the last axis."""
@@ -69,13 +91,19 @@ def rope_rotate_half(x: np.ndarray, positions: np.ndarray, theta: float) -> np.n
     return np.concatenate([lo * cos - hi * sin, hi * cos + lo * sin], axis=-1)
 
 
-def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_pos0: int) -> np.ndarray:
+def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_pos0: int, act_dtype=None) -> np.ndarray:
     """Softmax attention of a block of queries over a key/value history.
 
     q: [Lq, Hq, hd] queries at absolute positions q_pos0 .. q_pos0+Lq-1.
     k, v: [n_keys, Hkv, hd] keys/values at absolute positions 0 .. n_keys-1 (n_keys >= q_pos0+Lq).
     Query at position p attends to keys at positions <= p.  Query head h uses kv head
-    h // (Hq // Hkv).  Scores are scaled by 1/sqrt(hd).  Returns [Lq, Hq, hd]."""
+    h // (Hq // Hkv).  Scores are scaled by 1/sqrt(hd).  Returns [Lq, Hq, hd].
+    With act_dtype set, the un-normalised probabilities are rounded before they weight the values and the
+    normaliser is the sum of the unrounded ones.  Softmax is invariant to the reference point c in
+    2^(t - c) / sum 2^(t - c)  (t = score * log2 e); for the rounded form c is the smallest integer >= max t, so
+    that the stored value is the probability's own floating-point rounding whatever order the keys are visited in
+    (rounding commutes with powers of two)."""
+    rnd = _act_round(act_dtype)
     Lq, Hq, hd = q.shape
     n_keys, Hkv, _ = k.shape
     group = Hq // Hkv
@@ -88,10 +116,12 @@ def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_pos0: in
         vh = v[:, h // group, :]
         s = (q[:, h, :] @ kh.T) / np.sqrt(np.asarray(hd, dtype=q.dtype))
         s = np.where(allowed, s, -np.inf)
-        s = s - np.max(s, axis=-1, keepdims=True)
-        p = np.exp(s)
-        p = p / np.sum(p, axis=-1, keepdims=True)
-        out[:, h, :] = p @ vh
+        if act_dtype is None:
+            p = np.exp(s - np.max(s, axis=-1, keepdims=True))
+        else:
+            t = s * np.log2(np.e)
+            p = np.exp2(t - np.ceil(np.max(t, axis=-1, keepdims=True)))
+        out[:, h, :] = (rnd(p) @ vh) / np.sum(p, axis=-1, keepdims=True)
     return out
 
 
@@ -154,36 +184,37 @@ def _cast_weights(weights: Dict, dtype) -> Dict:
 
 
 def decoder_forward(desc, weights: Dict, x_rows: np.ndarray, cache: KVCache, dtype=np.float64,
-                    want_logits: bool = True) -> Optional[np.ndarray]:
+                    want_logits: bool = True, act_dtype=None) -> Optional[np.ndarray]:
     """Causal forward of the decoder over a block of new rows of one sequence.
 
     x_rows: [n, d_model] input embeddings of the new rows (token rows already looked up).  The rows
     sit at absolute positions len(cache) .. len(cache)+n-1.  Their keys/values are appended to
     `cache`.  Returns logits [n, vocab] (or None when want_logits is False)."""
     w = _cast_weights(weights, dtype)
+    rnd = _act_round(act_dtype)
     x = np.asarray(x_rows, dtype=dtype).copy()
     n = x.shape[0]
     pos0 = len(cache)
     positions = pos0 + np.arange(n)
     Hq, Hkv, hd = desc.n_q_heads, desc.n_kv_heads, desc.head_dim
     for l, lay in enumerate(w["layers"]):
-        h = rmsnorm(x, lay["attn_norm"], desc.rms_eps)
+        h = rnd(rmsnorm(x, lay["attn_norm"], desc.rms_eps))
         qkv = h @ lay["wqkv"].T
         q = qkv[:, : Hq * hd].reshape(n, Hq, hd)
         k = qkv[:, Hq * hd: (Hq + Hkv) * hd].reshape(n, Hkv, hd)
         v = qkv[:, (Hq + Hkv) * hd:].reshape(n, Hkv, hd)
-        q = rope_rotate_half(q, positions, desc.rope_theta)
-        k = rope_rotate_half(k, positions, desc.rope_theta)
-        cache.write(l, pos0, k, v)
-        a = causal_gqa_attention(q, cache.keys(l, pos0 + n), cache.values(l, pos0 + n), pos0)
+        q = rnd(rope_rotate_half(q, positions, desc.rope_theta))
+        k = rnd(rope_rotate_half(k, positions, desc.rope_theta))
+        cache.write(l, pos0, k, rnd(v))
+        a = rnd(causal_gqa_attention(q, cache.keys(l, pos0 + n), cache.values(l, pos0 + n), pos0, act_dtype))
         x = x + a.reshape(n, Hq * hd) @ lay["wo"].T
-        h = rmsnorm(x, lay["ffn_norm"], desc.rms_eps)
+        h = rnd(rmsnorm(x, lay["ffn_norm"], desc.rms_eps))
         gu = h @ lay["w_gate_up"].T
-        x = x + swiglu(gu[:, : desc.d_ffn], gu[:, desc.d_ffn:]) @ lay["w_down"].T
+        x = x + rnd(swiglu(gu[:, : desc.d_ffn], gu[:, desc.d_ffn:])) @ lay["w_down"].T
     cache.advance(n)
     if not want_logits:
         return None
-    return rmsnorm(x, w["final_norm"], desc.rms_eps) @ w["lm_head"].T
+    return rnd(rmsnorm(x, w["final_norm"], desc.rms_eps)) @ w["lm_head"].T
 
 
 def embed_tokens(weights: Dict, tokens: Sequence[int], dtype=np.float64) -> np.ndarray:
@@ -218,7 +249,7 @@ def accept_longest_prefix(u_hat: np.ndarray, draft: np.ndarray) -> Tuple[int, in
     return alpha, int(u_hat[alpha])
 
 
-def verify_block(desc, weights, cache: KVCache, pending: int, draft: np.ndarray, dtype=np.float64):
+def verify_block(desc, weights, cache: KVCache, pending: int, draft: np.ndarray, dtype=np.float64, act_dtype=None):
     """One verification pass for one sequence.
 
     cache holds the accepted context except its last token `pending` (whose keys/values are not
@@ -227,13 +258,13 @@ def verify_block(desc, weights, cache: KVCache, pending: int, draft: np.ndarray,
     All k+1 rows are appended to the cache; the caller commits by truncating to
     len_before + 1 + alpha."""
     block = np.concatenate([[pending], np.asarray(draft, dtype=np.int64)]).astype(np.int64)
-    logits = decoder_forward(desc, weights, embed_tokens(weights, block, dtype), cache, dtype)
+    logits = decoder_forward(desc, weights, embed_tokens(weights, block, dtype), cache, dtype, act_dtype=act_dtype)
     u_hat = argmax_lowest_index(logits)
     alpha, bonus = accept_longest_prefix(u_hat, draft)
     return alpha, bonus, u_hat, logits
 
 
-def prefill(desc, weights, visual: np.ndarray, prompt: Sequence[int], dtype=np.float64):
+def prefill(desc, weights, visual: np.ndarray, prompt: Sequence[int], dtype=np.float64, act_dtype=None):
     """Build the cache for [visual rows, prompt tokens except the last]; the last prompt token is
     returned as the pending token.  With an empty prompt the pending token is id 0 and all visual
     rows are cached."""
@@ -245,18 +276,18 @@ def prefill(desc, weights, visual: np.ndarray, prompt: Sequence[int], dtype=np.f
         rows = np.concatenate([np.asarray(visual, dtype=dtype), embed_tokens(weights, prompt[:-1], dtype)], axis=0)
         pending = int(prompt[-1])
     if rows.shape[0]:
-        decoder_forward(desc, weights, rows, cache, dtype, want_logits=False)
+        decoder_forward(desc, weights, rows, cache, dtype, want_logits=False, act_dtype=act_dtype)
     return cache, pending
 
 
 def greedy_decode(desc, weights, cache: KVCache, pending: int, n_tokens: int, dtype=np.float64,
-                  return_margins: bool = False):
+                  return_margins: bool = False, act_dtype=None):
     """Plain autoregressive decoding, one token per forward pass: the definition that verification
     must reproduce.  Returns the n_tokens generated tokens (and each step's top-1/top-2 margin)."""
     out, margins = [], []
     tok = pending
     for _ in range(n_tokens):
-        logits = decoder_forward(desc, weights, embed_tokens(weights, [tok], dtype), cache, dtype)
+        logits = decoder_forward(desc, weights, embed_tokens(weights, [tok], dtype), cache, dtype, act_dtype=act_dtype)
         tok = int(argmax_lowest_index(logits)[0])
         out.append(tok)
         if return_margins:
@@ -276,7 +307,7 @@ class RoundRecord:
 
 
 def spec_decode(desc, weights, cache: KVCache, pending: int, draft: np.ndarray, n_commit: int,
-                dtype=np.float64, max_block: Optional[int] = None):
+                dtype=np.float64, max_block: Optional[int] = None, act_dtype=None):
     """SpecDecode (Eq. 1) for one sequence with a single fixed, index-aligned draft.
 
     Repeats verification passes until n_commit tokens are committed.  The draft stays fixed (it
@@ -293,7 +324,7 @@ def spec_decode(desc, weights, cache: KVCache, pending: int, draft: np.ndarray, 
         if max_block is not None:
             rest = rest[: max_block]
         base = len(cache)
-        alpha, bonus, u_hat, logits = verify_block(desc, weights, cache, pending, rest, dtype)
+        alpha, bonus, u_hat, logits = verify_block(desc, weights, cache, pending, rest, dtype, act_dtype)
         cache.truncate(base + 1 + alpha)                      # commit accepted rows, roll back the rest
         committed.extend(int(t) for t in rest[:alpha])
         committed.append(bonus)

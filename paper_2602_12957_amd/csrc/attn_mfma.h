@@ -179,12 +179,15 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
 #pragma unroll
       for (int v = 1; v < 16; ++v) mx = fmaxf(mx, st[v]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      const float m_new = fmaxf(m_run, mx);
-      // a query that has seen no visible key yet (its first keys lie in the other half tile) keeps max = -inf;
+      // The running reference point is kept as an INTEGER in the base-2 exponent domain (the smallest integer
+      // >= max score * scale seen so far).  Every correction factor is then an exact power of two, and the bf16
+      // rounding of a probability no longer depends on which tile (or key half) it was computed in: rounding
+      // commutes with powers of two.  Probabilities lie in (0, 1].
+      const float m_new = fmaxf(m_run, ceilf(mx * sc));
+      // a query that has seen no visible key yet (its first keys lie in the other half tile) keeps -inf;
       // the reference point 0 then yields p = 0 and corr = 0 without producing inf - inf
-      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-      const float corr = exp2f((m_run - m_ref) * sc);
-      const float msc = m_ref * sc;
+      const float msc = (m_new == -INFINITY) ? 0.f : m_new;
+      const float corr = (m_run == -INFINITY) ? 0.f : ldexpf(1.0f, static_cast<int>(m_run - msc));
       l_run *= corr;
 #pragma unroll
       for (int i = 0; i < 2; ++i)
@@ -234,8 +237,8 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
     const float *src = mrg + wq * 34 * 64 + lane;
     const float m_b = src[32 * 64], l_b = src[33 * 64];
     const float m_tot = fmaxf(m_run, m_b);            // finite: key 0 belongs to half 0 of the first tile
-    const float ca = exp2f((m_run - m_tot) * sc);
-    const float cb = (m_b > -INFINITY) ? exp2f((m_b - m_tot) * sc) : 0.f;
+    const float ca = ldexpf(1.0f, static_cast<int>(m_run - m_tot));   // integer exponents: exact powers of two
+    const float cb = (m_b > -INFINITY) ? ldexpf(1.0f, static_cast<int>(m_b - m_tot)) : 0.f;
     const float inv = 1.0f / (l_run * ca + l_b * cb);
     bf16 *op = out + static_cast<size_t>(base + row0 + qj) * qdim + head * kHd;
 #pragma unroll

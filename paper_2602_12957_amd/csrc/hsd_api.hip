@@ -2,6 +2,7 @@
 // All device work is enqueued on the caller's stream; nothing here synchronises or allocates device memory.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -28,7 +29,7 @@ struct hsd_ctx {
   std::vector<const void *> wqkv, wo, w_gate_up, w_down;
   int n_cu;
   bool force_simple;  // HSD_FORCE_SIMPLE=1: run the plain kernels also for bf16 (cross-check of the MFMA path)
-  int gemm_cfg;       // HSD_GEMM_CFG=0..4: tile configuration of the MFMA GEMM (experiments)
+  int gemm_cfg[5];    // tile configuration of the MFMA GEMM per call site (qkv, o, gate_up, down, lm_head)
   // per-kernel timing (hsd_profile_*)
   int prof_which = HSD_PROF_NONE;
   int prof_used = 0;
@@ -98,6 +99,8 @@ struct ProfScope {
   }
 };
 
+enum { kSiteQKV = 0, kSiteO = 1, kSiteGateUp = 2, kSiteDown = 3, kSiteLM = 4 };
+
 template <typename Epi>
 struct GemmModeOf {
   static constexpr int value = Epi::kDual ? kModeDual : (std::is_same<Epi, EpiLMHead>::value ? kModeSwapLM : kModeNormal);
@@ -131,18 +134,23 @@ using GemmCfg1 = GemmCfg<256, 128, 64, 2, 2>;
 using GemmCfg2 = GemmCfg<256, 256, 64, 2, 2>;
 using GemmCfg3 = GemmCfg<256, 256, 32, 2, 2>;
 using GemmCfg4 = GemmCfg<128, 256, 64, 2, 2>;
+using GemmCfg5 = GemmCfg<256, 256, 64, 2, 4>;   // 8 waves, wave tile 128x64
+using GemmCfg6 = GemmCfg<256, 128, 64, 4, 2>;   // 8 waves, wave tile 64x64
+using GemmCfg7 = GemmCfg<128, 256, 64, 2, 4>;   // 8 waves, wave tile 64x64
 
 template <typename T, typename Epi>
-int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int M, int N, int K, const void *A, const void *W, const Epi &epi,
-                int n_tiles_simple = 0) {
-  (void)n_tiles_simple;
+int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int K, const void *A, const void *W,
+                const Epi &epi) {
   if constexpr (std::is_same<T, bf16>::value) {
     if (!ctx->force_simple && K % 64 == 0) {
-      switch (ctx->gemm_cfg) {
+      switch (ctx->gemm_cfg[site]) {
         case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi);
         case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi);
         case 3: return launch_gemm_mfma<GemmCfg3>(st, M, N, K, A, W, epi);
         case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi);
+        case 5: return launch_gemm_mfma<GemmCfg5>(st, M, N, K, A, W, epi);
+        case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi);
+        case 7: return launch_gemm_mfma<GemmCfg7>(st, M, N, K, A, W, epi);
         default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi);
       }
     }
@@ -159,11 +167,14 @@ template <typename T>
 int lm_head_tiles(const hsd_ctx *ctx) {
   const int V = ctx->desc.vocab;
   if (std::is_same<T, bf16>::value && !ctx->force_simple && ctx->desc.d_model % 64 == 0) {
-    switch (ctx->gemm_cfg) {
+    switch (ctx->gemm_cfg[kSiteLM]) {
       case 1: return V / GemmCfg1::BP * GemmCfg1::WM;
       case 2: return V / GemmCfg2::BP * GemmCfg2::WM;
       case 3: return V / GemmCfg3::BP * GemmCfg3::WM;
       case 4: return V / GemmCfg4::BP * GemmCfg4::WM;
+      case 5: return V / GemmCfg5::BP * GemmCfg5::WM;
+      case 6: return V / GemmCfg6::BP * GemmCfg6::WM;
+      case 7: return V / GemmCfg7::BP * GemmCfg7::WM;
       default: return V / GemmCfg0::BP * GemmCfg0::WM;
     }
   }
@@ -241,7 +252,7 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
     EpiQKV<T> eq{d.n_q_heads, d.n_kv_heads, meta, kv, static_cast<T *>(ws.q)};
     {
       ProfScope ps(ctx, st, HSD_PROF_GEMM_QKV);
-      if ((rc = launch_gemm<T>(ctx, st, Tq, qdim + 2 * kvdim, d.d_model, ws.h, ctx->wqkv[l], eq))) return rc;
+      if ((rc = launch_gemm<T>(ctx, st, kSiteQKV, Tq, qdim + 2 * kvdim, d.d_model, ws.h, ctx->wqkv[l], eq))) return rc;
     }
     {
       ProfScope ps(ctx, st, HSD_PROF_ATTENTION);
@@ -250,7 +261,7 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
     EpiResidual er{ws.x, d.d_model};
     {
       ProfScope ps(ctx, st, HSD_PROF_GEMM_O);
-      if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_model, qdim, ws.a, ctx->wo[l], er))) return rc;
+      if ((rc = launch_gemm<T>(ctx, st, kSiteO, Tq, d.d_model, qdim, ws.a, ctx->wo[l], er))) return rc;
     }
     hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
                        ctx->ffn_norm[l], static_cast<T *>(ws.h));
@@ -258,11 +269,11 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
     EpiSwiGLU<T> es{static_cast<T *>(ws.u), d.d_ffn};
     {
       ProfScope ps(ctx, st, HSD_PROF_GEMM_GATE_UP);
-      if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_ffn, d.d_model, ws.h, ctx->w_gate_up[l], es))) return rc;
+      if ((rc = launch_gemm<T>(ctx, st, kSiteGateUp, Tq, d.d_ffn, d.d_model, ws.h, ctx->w_gate_up[l], es))) return rc;
     }
     {
       ProfScope ps(ctx, st, HSD_PROF_GEMM_DOWN);
-      if ((rc = launch_gemm<T>(ctx, st, Tq, d.d_model, d.d_ffn, ws.u, ctx->w_down[l], er))) return rc;
+      if ((rc = launch_gemm<T>(ctx, st, kSiteDown, Tq, d.d_model, d.d_ffn, ws.u, ctx->w_down[l], er))) return rc;
     }
   }
   if (!with_head) return HSD_OK;
@@ -283,7 +294,7 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
   EpiLMHead el{ws.lm_part, n_tiles, d.vocab, dump_slot, b->logits_dump};
   {
     ProfScope ps(ctx, st, HSD_PROF_GEMM_LM_HEAD);
-    if ((rc = launch_gemm<T>(ctx, st, Tq, d.vocab, d.d_model, ws.h, ctx->lm_head, el))) return rc;
+    if ((rc = launch_gemm<T>(ctx, st, kSiteLM, Tq, d.vocab, d.d_model, ws.h, ctx->lm_head, el))) return rc;
   }
   hipLaunchKernelGGL(k_lm_reduce, dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, n_tiles, ws.lm_part, b->argmax,
                      b->top2_margin);
@@ -411,8 +422,14 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   c->n_cu = prop.multiProcessorCount;
   const char *fs = std::getenv("HSD_FORCE_SIMPLE");
   c->force_simple = fs != nullptr && fs[0] == '1';
-  const char *gc = std::getenv("HSD_GEMM_CFG");
-  c->gemm_cfg = gc != nullptr ? std::atoi(gc) : 0;
+  // HSD_GEMM_CFG="q,o,g,d,l" (or one number for all) overrides the per-site tile configuration (experiments)
+  const int defaults[5] = {0, 0, 0, 0, 0};
+  for (int i = 0; i < 5; ++i) c->gemm_cfg[i] = defaults[i];
+  if (const char *gc = std::getenv("HSD_GEMM_CFG")) {
+    int vals[5], n = std::sscanf(gc, "%d,%d,%d,%d,%d", &vals[0], &vals[1], &vals[2], &vals[3], &vals[4]);
+    for (int i = 0; i < 5; ++i)
+      if (n == 1) c->gemm_cfg[i] = vals[0]; else if (i < n) c->gemm_cfg[i] = vals[i];
+  }
   *out = c;
   return HSD_OK;
 }

@@ -289,4 +289,7 @@ class Engine:
             B.hsd_kv_commit_rollback(self.ctx, self.stream, self.cpool, b, _ptr(tok_view))
             hist[step].copy_(self.bonus[:n])
         torch.cuda.current_stream(self.dev).synchronize()
+        status = int(self.status.item())
+        if status:
+            raise RuntimeError(f"greedy_decode: device status {status} (KV pool exhausted or block table too short)")
         return hist.cpu().numpy().T.copy()

@@ -5,7 +5,10 @@ For every sequence of a configuration it stores, as JSON:
   * the oracle's token-by-token greedy output ("target") and each step's top-1/top-2 margin: the sequence
     the synthetic drafts are derived from;
   * for each verification round of SpecDecode over the seeded corrupted draft (paper Section 3.2, Eq. 8-12):
-    draft offset, k, alpha, bonus, the model's top-1 token at every row, and every row's top-1/top-2 margin;
+    draft offset, k, alpha, bonus, the model's top-1 token at every row, every row's top-1/top-2 margin, and
+    every row's four largest logits with their token ids (the set of near-maximal tokens);
+  * "noise_floor": the logit deviation between two oracle evaluations that differ only in summation precision
+    (the tests derive their floating-point bars for deep bf16 models from it);
   * for a few rows of round 1, the logits at a seeded sample of vocabulary columns plus each row's top-8
     (value, index) pairs, for the element-wise logit comparison.
 
@@ -51,10 +54,11 @@ def one_sequence(args):
     t0 = time.time()
     desc = W.CONFIGS[cfg_index].model
     weights = _WEIGHTS
+    act = "bf16" if desc.dtype == "bf16" else None      # oracle at the model's storage precision
     vis, prompt = W.make_prefix(desc, seed, sp.seq_id, sp.n_visual, sp.n_prompt)
-    cache, pending = O.prefill(desc, weights, vis, prompt)
+    cache, pending = O.prefill(desc, weights, vis, prompt, act_dtype=act)
     base_len = len(cache)
-    target, tmargin = O.greedy_decode(desc, weights, cache, pending, sp.draft_len, return_margins=True)
+    target, tmargin = O.greedy_decode(desc, weights, cache, pending, sp.draft_len, return_margins=True, act_dtype=act)
     t1 = time.time()
     cache.truncate(base_len)
     draft = draft_for(cfg_index, desc, seed, sp, target)
@@ -64,7 +68,7 @@ def one_sequence(args):
     while committed < sp.draft_len and (max_rounds is None or len(rounds) < max_rounds):
         rest = draft[committed:]
         base = len(cache)
-        alpha, bonus, u_hat, logits = O.verify_block(desc, weights, cache, pend, rest)
+        alpha, bonus, u_hat, logits = O.verify_block(desc, weights, cache, pend, rest, act_dtype=act)
         cache.truncate(base + 1 + alpha)
         margin = O.top2_margin(logits)
         if not rounds:
@@ -74,8 +78,13 @@ def one_sequence(args):
                        "values": [[float(f"{x:.9g}") for x in logits[r, cols]] for r in rows],
                        "top8_idx": top_idx.tolist(),
                        "top8_val": [[float(f"{logits[r, j]:.9g}") for j in top_idx[i]] for i, r in enumerate(rows)]}
+        top4 = np.argpartition(-logits, 4, axis=1)[:, :4]
+        order = np.argsort(-np.take_along_axis(logits, top4, axis=1), axis=1, kind="stable")
+        top4 = np.take_along_axis(top4, order, axis=1)
         rounds.append({"offset": committed, "k": int(len(rest)), "alpha": int(alpha), "bonus": int(bonus),
-                       "u_hat": u_hat.tolist(), "margin": [float(f"{m:.6g}") for m in margin]})
+                       "u_hat": u_hat.tolist(), "margin": [float(f"{m:.6g}") for m in margin],
+                       "top4_idx": top4.tolist(),
+                       "top4_val": [[float(f"{x:.7g}") for x in row] for row in np.take_along_axis(logits, top4, axis=1)]})
         committed += alpha + 1
         pend = bonus
     print(f"  cfg{cfg_index} seq {sp.seq_id}: S={base_len} k={sp.draft_len} greedy {t1 - t0:.0f}s rounds {len(rounds)} "
@@ -84,6 +93,22 @@ def one_sequence(args):
             "cached_len": base_len, "pending": int(pending), "target": target.tolist(),
             "target_margin": [float(f"{m:.6g}") for m in tmargin], "rounds": rounds,
             "complete": committed >= sp.draft_len, "logit_samples": samples}
+
+
+def noise_probe(cfg_index, seed):
+    """Deviation between two evaluations of the SAME model at the same storage precision that differ only in
+    the precision of their sums (fp64 vs fp32): the floor below which no two correct implementations of a
+    bf16-storage decoder agree.  Probe: 256 visual rows + 64 random draft tokens of sequence 0."""
+    desc = W.CONFIGS[cfg_index].model
+    act = "bf16" if desc.dtype == "bf16" else None
+    vis, _ = W.make_prefix(desc, seed, 0, 256, 0)
+    draft = np.random.default_rng([seed, cfg_index, 999]).integers(0, desc.vocab, size=64)
+    out = []
+    for dt in (np.float64, np.float32):
+        cache, pending = O.prefill(desc, _WEIGHTS, vis, [], dt, act_dtype=act)
+        out.append(O.verify_block(desc, _WEIGHTS, cache, pending, draft, dt, act_dtype=act)[3].astype(np.float64))
+    d = out[0] - out[1]
+    return {"rows": 65, "rms": float(f"{np.sqrt((d ** 2).mean()):.4g}"), "max_abs": float(f"{np.abs(d).max():.4g}")}
 
 
 _WEIGHTS = None
@@ -106,6 +131,8 @@ def main():
         specs = specs[int(a):int(b)]
     _WEIGHTS = W.make_weights(desc, seed)
     O.hsd_oracle._cast_weights(_WEIGHTS, np.float64)     # cast once, before forking
+    noise = noise_probe(args.config, seed)
+    print("noise probe (fp64 vs fp32 sums):", noise, flush=True)
     threads = max(1, (os.cpu_count() or 8) // args.procs)
     jobs = [(args.config, seed, sp, args.max_rounds, threads) for sp in specs]
     t0 = time.time()
@@ -115,8 +142,9 @@ def main():
             seqs = pool.map(one_sequence, jobs, chunksize=1)
     else:
         seqs = [one_sequence(j) for j in jobs]
-    out = {"config": args.config, "seed": seed, "oracle_dtype": "float64", "generator": "tests/golden/make_golden.py",
-           "sequences": seqs}
+    out = {"config": args.config, "seed": seed, "oracle_dtype": "float64",
+           "oracle_act_dtype": "bf16" if desc.dtype == "bf16" else None, "generator": "tests/golden/make_golden.py",
+           "noise_floor": noise, "sequences": seqs}
     path = args.out or os.path.join(os.path.dirname(os.path.abspath(__file__)), f"cfg{args.config}.json")
     with open(path, "w") as f:
         json.dump(out, f, separators=(",", ":"))

@@ -1,0 +1,85 @@
+"""The lossless property on the GPU path itself, at full model size and exactly.
+
+Speculative verification must reproduce plain token-by-token greedy decoding of the same model (the premise
+of the method, Section 3.2: verification preserves autoregressive conditioning; the verifier accepts the longest
+matching prefix).  Here BOTH sides are the HIP path: greedy decoding with blocks of length 1, and verification
+rounds over corrupted drafts run freely (no teacher forcing).  Because every kernel computes a row's result
+independently of which other rows share the launch, the two agree bit for bit, for any model depth -- a property
+that holds at any size and does not involve the oracle (whose parity is tested separately).  Acceptance lengths
+are also checked against the closed form given by the corruption positions.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from workloads.generators import SequenceSpec
+
+from hsd_testlib import make_engine, prefix_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def _lossless(desc, specs, seed, mode):
+    weights = W.make_weights(desc, seed)
+    n = len(specs)
+    eng = make_engine(desc, weights, specs, max_total_q=max(sum(s.draft_len + 1 for s in specs), 4096))
+    toks, embs, pend = [], [], []
+    for sp in specs:
+        _, _, tok, emb, pending = prefix_rows(desc, seed, sp)
+        toks.append(tok), embs.append(emb), pend.append(pending)
+    slots = list(range(n))
+    eng.prefill(slots, toks, embs)
+    k_max = max(sp.draft_len for sp in specs)
+    target = eng.greedy_decode(slots, pend, k_max)
+    eng.reset()
+    eng.prefill(slots, toks, embs)
+    drafts, masks = [], []
+    for i, sp in enumerate(specs):
+        d, m = W.corrupt_draft_forced(target[i][:sp.draft_len], sp.corrupt_p, desc.vocab, seed, f"ll.{sp.seq_id}")
+        drafts.append(d), masks.append(np.nonzero(m)[0])
+    committed = [[] for _ in range(n)]
+    pending = list(pend)
+    rounds = 0
+    active = slots
+    while active:
+        blocks = [np.concatenate([[pending[i]], drafts[i][len(committed[i]):]]).astype(np.int32) for i in active]
+        eng.verify(active, blocks, mode)
+        eng.commit()
+        alpha, bonus, status = eng.read_acceptance(len(active))
+        assert status == 0
+        nxt = []
+        for j, i in enumerate(active):
+            o = len(committed[i])
+            later = masks[i][masks[i] >= o]
+            expect = int(later[0] - o) if len(later) else specs[i].draft_len - o
+            assert alpha[j] == expect, f"seq {i} round {rounds}: alpha {alpha[j]} != {expect}"
+            committed[i].extend(drafts[i][o:o + alpha[j]].tolist())
+            committed[i].append(int(bonus[j]))
+            pending[i] = int(bonus[j])
+            if len(committed[i]) < specs[i].draft_len:
+                nxt.append(i)
+        active = nxt
+        rounds += 1
+    for i, sp in enumerate(specs):
+        np.testing.assert_array_equal(np.asarray(committed[i][:sp.draft_len]), target[i][:sp.draft_len])
+    torch.cuda.synchronize()
+    owned = int((eng.block_table.cpu().numpy() >= 0).sum())
+    assert owned + int(eng.free_count.item()) == eng.n_blocks
+    eng.close()
+    return rounds
+
+
+@pytest.mark.parametrize("mode", ["region", "page"])
+def test_lossless_small_models(mode):
+    for desc in (W.ModelDesc(2, 128, 4, 1, 64, 256, 512, "fp32"), W.ModelDesc(3, 256, 8, 2, 64, 512, 1024, "bf16")):
+        specs = [SequenceSpec(0, 40, 3, 90, 0.1), SequenceSpec(1, 5, 2, 70, 0.3), SequenceSpec(2, 130, 5, 33, 0.0),
+                 SequenceSpec(3, 0, 4, 150, 0.05)]
+        assert _lossless(desc, specs, 11, mode) >= 2
+
+
+def test_lossless_config1_model_m():
+    """configs[1] shapes (16 regions, 1055 cached tokens, drafts U[16,256], 5 % corruption), 24-layer bf16 model."""
+    specs = W.draw_sequences(1, W.SEED_BASE)
+    rounds = _lossless(W.MODEL_M, specs, W.SEED_BASE, "region")
+    print("cfg1 lossless rounds", rounds)

@@ -11,7 +11,7 @@ import oracle as O
 import workloads as W
 from workloads.generators import SequenceSpec
 
-from hsd_testlib import MARGIN_GATE, make_engine, prefix_rows, oracle_targets, gated_compare_argmax
+from hsd_testlib import MARGIN_GATE, act_dtype_of, make_engine, prefix_rows, oracle_targets, gated_compare_argmax
 
 pytestmark = pytest.mark.gpu
 
@@ -22,7 +22,7 @@ def _oracle_state(desc, weights, seed, specs):
     st = []
     for sp in specs:
         vis, prompt = W.make_prefix(desc, seed, sp.seq_id, sp.n_visual, sp.n_prompt)
-        cache, pending = O.prefill(desc, weights, vis, prompt)
+        cache, pending = O.prefill(desc, weights, vis, prompt, act_dtype=act_dtype_of(desc))
         st.append([cache, pending])
     return st
 
@@ -58,7 +58,8 @@ def run_rounds_parity(desc, weights, seed, specs, drafts, mode="region", check_l
             rest = drafts[s][committed[s]:]
             blocks.append(np.concatenate([[ora[s][1]], rest]).astype(np.int32))
             base = len(ora[s][0])
-            alpha, bonus, u_hat, logits = O.verify_block(desc, weights, ora[s][0], ora[s][1], rest)
+            alpha, bonus, u_hat, logits = O.verify_block(desc, weights, ora[s][0], ora[s][1], rest,
+                                                         act_dtype=act_dtype_of(desc))
             ora[s][0].truncate(base + 1 + alpha)
             recs.append((alpha, bonus, u_hat, logits, O.top2_margin(logits)))
         T = sum(len(b) for b in blocks)

@@ -112,3 +112,17 @@ def test_aal_expectation_iid_corruption():
         alphas.append(int(nz[0]) if len(nz) else k)
     expect = sum((1 - p) ** j for j in range(1, k + 1))
     assert abs(np.mean(alphas) - expect) < 4 * np.std(alphas) / np.sqrt(n)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_lossless_invariant_with_bf16_storage(seed):
+    """The invariant is a property of the operator, not of the precision: it also holds when the decoder
+    stores its activations in bf16."""
+    desc = W.tiny_model(n_layers=2, d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ffn=128, vocab=257, dtype="bf16")
+    w, vis, prompt = _setup(desc, seed)
+    cache, pending = O.prefill(desc, w, vis, prompt, act_dtype="bf16")
+    g = O.greedy_decode(desc, w, cache, pending, 16, act_dtype="bf16")
+    draft, _ = W.corrupt_draft(g, 0.3, desc.vocab, seed, "b")
+    cache, pending = O.prefill(desc, w, vis, prompt, act_dtype="bf16")
+    out, rounds = O.spec_decode(desc, w, cache, pending, draft, 16, act_dtype="bf16")
+    np.testing.assert_array_equal(out, g)

@@ -239,3 +239,41 @@ def test_argmax_ties_and_margin():
     y = rng.standard_normal((20, 50))
     s = np.sort(y, axis=-1)
     np.testing.assert_allclose(O.top2_margin(y), s[:, -1] - s[:, -2])
+
+
+# ---------------------------------------------------------------- bf16 storage-precision mode
+
+def test_round_bf16_matches_torch_conversion():
+    rng = np.random.default_rng(12)
+    x = np.concatenate([rng.standard_normal(5000) * 10.0 ** rng.integers(-6, 6, size=5000),
+                        # exact ties between two bf16 neighbours (must go to the even one) and exact bf16 values
+                        np.array([1.00390625, 1.01171875, -1.00390625, 3.0, 0.0, 65280.0 + 128.0, 2.0 ** -120])])
+    ref = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(O.round_bf16(x), ref)
+    assert O.round_bf16(x).dtype == x.dtype
+    assert O.round_bf16(np.array([1.00390625]))[0] == 1.0 and O.round_bf16(np.array([1.01171875]))[0] == 1.015625
+
+
+def test_bf16_mode_is_the_same_forward_with_rounded_storage():
+    """act_dtype=None leaves the pinned fp64 forward untouched; act_dtype='bf16' perturbs it by rounding noise only;
+    attention with rounded probabilities keeps the unrounded normaliser."""
+    desc = W.tiny_model(n_layers=2, d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ffn=96, vocab=150, dtype="bf16")
+    w = W.make_weights(desc, seed=8)
+    vis, prompt = W.make_prefix(desc, 8, 0, 10, 5)
+    rows = np.concatenate([vis, np.asarray(w["tok_embed"])[prompt]]).astype(np.float64)
+    a = O.decoder_forward(desc, w, rows, O.KVCache(2, 2, 16))
+    b = O.decoder_forward(desc, w, rows, O.KVCache(2, 2, 16), act_dtype="bf16")
+    rel = np.abs(a - b).max() / np.abs(a).max()
+    assert 1e-5 < rel < 5e-2
+    rng = np.random.default_rng(0)
+    q, k, v = rng.standard_normal((3, 2, 8)), rng.standard_normal((7, 2, 8)), rng.standard_normal((7, 2, 8))
+    out = O.causal_gqa_attention(q, k, v, 4, act_dtype="bf16")
+    for i in range(3):
+        for h in range(2):
+            t = (k[: 5 + i, h] @ q[i, h]) / np.sqrt(8) * np.log2(np.e)
+            e = 2.0 ** (t - np.ceil(t.max()))
+            np.testing.assert_allclose(out[i, h], (O.round_bf16(e) @ v[: 5 + i, h]) / e.sum(), rtol=1e-12)
+            # the rounded probabilities do not depend on the order/grouping in which keys are visited:
+            # any other integer reference point only moves the exponent
+            e2 = 2.0 ** (t - np.ceil(t.max()) - 3)
+            np.testing.assert_array_equal(O.round_bf16(e2) * 8, O.round_bf16(e))
