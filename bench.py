@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--random-target", action="store_true",
                     help="profiling aid: skip the greedy target generation and corrupt a random token sequence instead "
                          "(same shapes and kernels; acceptance lengths are then meaningless)")
+    ap.add_argument("--calibration-copy-mb", type=int, default=0,
+                    help="profiling aid: after the timed region run one plain device-to-device copy of this many MiB "
+                         "(a kernel of known traffic against which HBM counters are scaled)")
     ap.add_argument("--breakdown", action="store_true",
                     help="after the timed region, time every kernel class in turn (extra steps) and report avg us per launch")
     args = ap.parse_args()
@@ -172,6 +175,13 @@ def main():
         "gemm_tflops_whole_step": round(gemm_flops_step / (ms_step * 1e-3) / 1e12, 1),
         "roofline": roofline,
     }
+    if args.calibration_copy_mb > 0:
+        src = torch.ones(args.calibration_copy_mb * (1 << 20) // 4, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.breakdown:
         bd = {}
         for name, cls in prof_map.items():
