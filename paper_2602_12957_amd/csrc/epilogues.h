@@ -14,6 +14,8 @@ namespace hsd {
 template <typename T>
 struct EpiQKV {
   static constexpr bool kDual = false;
+  static constexpr bool kChunked = false;
+  __device__ __forceinline__ const EpiQKV &for_split(int, int) const { return *this; }
   int n_q_heads, n_kv_heads;
   RowMeta meta;
   PagedKV kv;
@@ -51,15 +53,32 @@ struct EpiQKV {
   }
 };
 
-// x += A W^T (fp32 residual stream, each element owned by one thread: deterministic).
+// x += A W^T (fp32 residual stream, each element owned by one thread: deterministic).  When the GEMM runs as
+// split-K, the chunk's partial sum goes to part[split][m][n] instead and a later kernel adds the partials in
+// chunk order to x (k_reduce_rmsnorm).
 struct EpiResidual {
   static constexpr bool kDual = false;
+  static constexpr bool kChunked = true;
   float *x;
   int ld;
+  float *part;  // [k_chunks][M][ld] or nullptr when the GEMM is never launched split
+  bool to_part;
+  __device__ __forceinline__ EpiResidual for_split(int split, int M) const {
+    EpiResidual e = *this;
+    e.to_part = split >= 0;
+    if (split >= 0) e.part = part + static_cast<size_t>(split) * M * ld;
+    return e;
+  }
   __device__ __forceinline__ void pair(int m, int n, float lo, float hi) const {
-    float *p = x + static_cast<size_t>(m) * ld + n;
-    p[0] += lo;
-    p[32] += hi;
+    if (to_part) {
+      float *p = part + static_cast<size_t>(m) * ld + n;
+      p[0] = lo;
+      p[32] = hi;
+    } else {
+      float *p = x + static_cast<size_t>(m) * ld + n;
+      p[0] += lo;
+      p[32] += hi;
+    }
   }
 };
 
@@ -67,6 +86,8 @@ struct EpiResidual {
 template <typename T>
 struct EpiSwiGLU {
   static constexpr bool kDual = true;
+  static constexpr bool kChunked = false;
+  __device__ __forceinline__ const EpiSwiGLU &for_split(int, int) const { return *this; }
   T *u;
   int ld;
   __device__ __forceinline__ static float f(float g, float up) { return g / (1.0f + expf(-g)) * up; }
@@ -84,6 +105,8 @@ struct EpiSwiGLU {
 // kernel reduces the records of one row within the column tile and stores one record per (row, tile).
 struct EpiLMHead {
   static constexpr bool kDual = false;
+  static constexpr bool kChunked = false;
+  __device__ __forceinline__ const EpiLMHead &for_split(int, int) const { return *this; }
   Top2 *part;  // [T][n_tiles]
   int n_tiles;
   int vocab;

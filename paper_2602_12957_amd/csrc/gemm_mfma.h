@@ -68,153 +68,11 @@ __host__ __device__ inline void gemm_tiles(int M, int N, int &tiles_act, int &ti
   }
 }
 
-// grid: 1-D, tiles_act * tiles_w workgroups of Cfg::kThreads threads, Cfg::kSmemBytes dynamic LDS.
-// N is the number of output columns (for dual mode the weight matrix has 2N rows: gate | up).
+// Hands the accumulators of one wave to the epilogue functor (see the mode descriptions above).
 template <typename Cfg, int MODE, typename Epi>
-__global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K, const bf16 *__restrict__ A,
-                                                             const bf16 *__restrict__ W, Epi epi) {
-  constexpr int BP = Cfg::BP, BQ = Cfg::BQ, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN, LS = Cfg::kStride;
-  constexpr int NT = Cfg::kThreads, CH = Cfg::kChunks;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  uint16_t *smem = reinterpret_cast<uint16_t *>(smem_raw);
-
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wi = wave / Cfg::WN, wj = wave % Cfg::WN;
-  int tiles_act, tiles_w, ta, tw;
-  gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
-  xcd_tile(blockIdx.x, tiles_act, tiles_act * tiles_w, ta, tw);
-  // first activation row / first output column of this tile
-  const int m0 = ta * ((MODE == kModeSwapLM) ? BQ : BP);
-  const int n0 = tw * ((MODE == kModeSwapLM) ? BP : ((MODE == kModeDual) ? BQ / 2 : BQ));
-
-  // ---- global source of every 16-byte chunk this thread stages (fixed over the K loop)
-  const bf16 *srcP[Cfg::kLoadsP];
-  const bf16 *srcQ[Cfg::kLoadsQ];
-#pragma unroll
-  for (int i = 0; i < Cfg::kLoadsP; ++i) {
-    int c = t + NT * i, r = c / CH, kc = c % CH;
-    int row = (MODE == kModeSwapLM) ? min(n0 + r, N - 1) : min(m0 + r, M - 1);
-    srcP[i] = ((MODE == kModeSwapLM) ? W : A) + static_cast<size_t>(row) * K + kc * 8;
-  }
-#pragma unroll
-  for (int i = 0; i < Cfg::kLoadsQ; ++i) {
-    int c = t + NT * i, r = c / CH, kc = c % CH;
-    int row;
-    if (MODE == kModeSwapLM) {
-      row = min(m0 + r, M - 1);
-    } else if (MODE == kModeDual) {
-      constexpr int WNC = BQ / Cfg::WN;  // Q rows per wave column
-      int wq = r / WNC, tn = (r % WNC) >> 5, j = r & 31;
-      row = min(((tn & 1) ? N : 0) + n0 + wq * (WNC / 2) + (tn >> 1) * 32 + j, 2 * N - 1);
-    } else {
-      row = min(n0 + r, N - 1);
-    }
-    srcQ[i] = ((MODE == kModeSwapLM) ? A : W) + static_cast<size_t>(row) * K + kc * 8;
-  }
-
-  floatx16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  const int frag_p = (wi * (BP / Cfg::WM) + (lane & 31)) * LS + (lane >> 5) * 8;
-  const int frag_q = BP * LS + (wj * (BQ / Cfg::WN) + (lane & 31)) * LS + (lane >> 5) * 8;
-
-  u32x4 regP[Cfg::kLoadsP], regQ[Cfg::kLoadsQ];
-  const int nk = K / BK;
-
-#define HSD_GEMM_LOAD(k0)                                                              \
-  _Pragma("unroll") for (int i = 0; i < Cfg::kLoadsP; ++i) regP[i] =                   \
-      *reinterpret_cast<const u32x4 *>(srcP[i] + (k0));                                \
-  _Pragma("unroll") for (int i = 0; i < Cfg::kLoadsQ; ++i) regQ[i] =                   \
-      *reinterpret_cast<const u32x4 *>(srcQ[i] + (k0));
-#define HSD_GEMM_STORE(stage)                                                          \
-  {                                                                                    \
-    uint16_t *sp = smem + (stage) * Cfg::kStage;                                       \
-    _Pragma("unroll") for (int i = 0; i < Cfg::kLoadsP; ++i) {                         \
-      int c = t + NT * i;                                                              \
-      *reinterpret_cast<u32x4 *>(sp + (c / CH) * LS + (c % CH) * 8) = regP[i];         \
-    }                                                                                  \
-    _Pragma("unroll") for (int i = 0; i < Cfg::kLoadsQ; ++i) {                         \
-      int c = t + NT * i;                                                              \
-      *reinterpret_cast<u32x4 *>(sp + BP * LS + (c / CH) * LS + (c % CH) * 8) = regQ[i]; \
-    }                                                                                  \
-  }
-
-  HSD_GEMM_LOAD(0)
-  HSD_GEMM_STORE(0)
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) {
-      HSD_GEMM_LOAD((kt + 1) * BK)
-    }
-    const uint16_t *sp = smem + (kt & 1) * Cfg::kStage;
-#ifndef HSD_GEMM_VARIANT
-#define HSD_GEMM_VARIANT 1
-#endif
-#if HSD_GEMM_VARIANT == 2
-    // all operand fragments of the slice are read up front, then the MFMAs run from registers
-    bf16x8 a[BK / 16][TM], b[BK / 16][TN];
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-#pragma unroll
-      for (int i = 0; i < TM; ++i) a[kk][i] = *reinterpret_cast<const bf16x8 *>(sp + frag_p + i * 32 * LS + kk * 16);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) b[kk][j] = *reinterpret_cast<const bf16x8 *>(sp + frag_q + j * 32 * LS + kk * 16);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk)
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][i], b[kk][j], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-#else
-    // operand fragments are double buffered in registers: the LDS reads of k-step kk+1 are issued before the
-    // MFMAs of k-step kk, into registers that no MFMA still in flight reads
-    bf16x8 a[2][TM], b[2][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) a[0][i] = *reinterpret_cast<const bf16x8 *>(sp + frag_p + i * 32 * LS);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) b[0][j] = *reinterpret_cast<const bf16x8 *>(sp + frag_q + j * 32 * LS);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      const int cur = kk & 1, nxt = cur ^ 1;
-      if (kk + 1 < BK / 16) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-          a[nxt][i] = *reinterpret_cast<const bf16x8 *>(sp + frag_p + i * 32 * LS + (kk + 1) * 16);
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          b[nxt][j] = *reinterpret_cast<const bf16x8 *>(sp + frag_q + j * 32 * LS + (kk + 1) * 16);
-      }
-#if HSD_GEMM_VARIANT == 1
-      __builtin_amdgcn_sched_barrier(0);
-#endif
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
-#if HSD_GEMM_VARIANT == 1
-      __builtin_amdgcn_sched_barrier(0);
-#endif
-    }
-#endif
-    if (kt + 1 < nk) {
-      HSD_GEMM_STORE((kt + 1) & 1)
-    }
-    __syncthreads();
-  }
-#undef HSD_GEMM_LOAD
-#undef HSD_GEMM_STORE
-
-  // ---- epilogue
+__device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[Cfg::TM][Cfg::TN], int M, int N, int m0, int n0, int tw,
+                                              int wi, int wj, int lane, const Epi &epi) {
+  constexpr int BP = Cfg::BP, BQ = Cfg::BQ, TM = Cfg::TM, TN = Cfg::TN;
   const int col = lane & 31, half = lane >> 5;
   if constexpr (MODE == kModeSwapLM) {
     // i side = vocabulary rows, j side = tokens: fold the lane's TM*16 values per token, merge the lane halves
@@ -266,6 +124,164 @@ __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K
         }
       }
   }
+}
+
+// grid: 1-D, tiles_act * tiles_w workgroups of Cfg::kThreads threads, Cfg::kSmemBytes dynamic LDS.
+// N is the number of output columns (for dual mode the weight matrix has 2N rows: gate | up).
+//
+// K may be reduced in `k_chunks` equal chunks whose sums are added in chunk order (chunk 0 first).  With
+// gridDim.y == k_chunks each workgroup handles one chunk and hands its partial sum to the epilogue (split-K; the
+// caller adds the partials in chunk order); with gridDim.y == 1 the workgroup walks all chunks itself, restarting
+// its accumulators at every chunk boundary and adding chunk sums in the same order.  Both forms round identically,
+// so the choice between them (made from the number of tiles) never changes a result bit.
+// WALK_CHUNKS selects the second form at compile time (it needs a second set of accumulators).
+template <typename Cfg, int MODE, typename Epi, bool WALK_CHUNKS = false>
+__global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K, int k_chunks,
+                                                             const bf16 *__restrict__ A,
+                                                             const bf16 *__restrict__ W, Epi epi) {
+  constexpr int BP = Cfg::BP, BQ = Cfg::BQ, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN, LS = Cfg::kStride;
+  constexpr int NT = Cfg::kThreads, CH = Cfg::kChunks;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  uint16_t *smem = reinterpret_cast<uint16_t *>(smem_raw);
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wi = wave / Cfg::WN, wj = wave % Cfg::WN;
+  int tiles_act, tiles_w, ta, tw;
+  gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
+  xcd_tile(blockIdx.x, tiles_act, tiles_act * tiles_w, ta, tw);
+  // first activation row / first output column of this tile
+  const int m0 = ta * ((MODE == kModeSwapLM) ? BQ : BP);
+  const int n0 = tw * ((MODE == kModeSwapLM) ? BP : ((MODE == kModeDual) ? BQ / 2 : BQ));
+
+  // ---- global source of every 16-byte chunk this thread stages (fixed over the K loop)
+  const bf16 *srcP[Cfg::kLoadsP];
+  const bf16 *srcQ[Cfg::kLoadsQ];
+#pragma unroll
+  for (int i = 0; i < Cfg::kLoadsP; ++i) {
+    int c = t + NT * i, r = c / CH, kc = c % CH;
+    int row = (MODE == kModeSwapLM) ? min(n0 + r, N - 1) : min(m0 + r, M - 1);
+    srcP[i] = ((MODE == kModeSwapLM) ? W : A) + static_cast<size_t>(row) * K + kc * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < Cfg::kLoadsQ; ++i) {
+    int c = t + NT * i, r = c / CH, kc = c % CH;
+    int row;
+    if (MODE == kModeSwapLM) {
+      row = min(m0 + r, M - 1);
+    } else if (MODE == kModeDual) {
+      constexpr int WNC = BQ / Cfg::WN;  // Q rows per wave column
+      int wq = r / WNC, tn = (r % WNC) >> 5, j = r & 31;
+      row = min(((tn & 1) ? N : 0) + n0 + wq * (WNC / 2) + (tn >> 1) * 32 + j, 2 * N - 1);
+    } else {
+      row = min(n0 + r, N - 1);
+    }
+    srcQ[i] = ((MODE == kModeSwapLM) ? A : W) + static_cast<size_t>(row) * K + kc * 8;
+  }
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int frag_p = (wi * (BP / Cfg::WM) + (lane & 31)) * LS + (lane >> 5) * 8;
+  const int frag_q = BP * LS + (wj * (BQ / Cfg::WN) + (lane & 31)) * LS + (lane >> 5) * 8;
+
+  // Two register sets hold the K slices in flight: while slice kt is multiplied out of LDS stage kt & 1, slice
+  // kt+1 (requested one iteration earlier) is written from its set to the other stage, and the requests for slice
+  // kt+2 go out into the set that was stored last iteration.  Loads and LDS stores are issued between the MFMA
+  // groups of the four k-steps so that neither blocks a long MFMA run.
+  u32x4 regP[2][Cfg::kLoadsP], regQ[2][Cfg::kLoadsQ];
+  static_assert(BK == 64 && Cfg::kLoadsP % 2 == 0 && Cfg::kLoadsQ % 2 == 0, "pipeline is written for 4 k-steps");
+  const int k_len = K / k_chunks, nk = k_len / BK;
+  const bool split = gridDim.y > 1;
+  const int c_begin = split ? blockIdx.y : 0, c_end = split ? blockIdx.y + 1 : k_chunks;
+  floatx16 tot[WALK_CHUNKS ? TM : 1][WALK_CHUNKS ? TN : 1];
+
+#define HSD_GEMM_LOAD(set, k0, h)                                                                   \
+  _Pragma("unroll") for (int i = (h) * (Cfg::kLoadsP / 2); i < ((h) + 1) * (Cfg::kLoadsP / 2); ++i) \
+      regP[set][i] = *reinterpret_cast<const u32x4 *>(srcP[i] + (k0));                              \
+  _Pragma("unroll") for (int i = (h) * (Cfg::kLoadsQ / 2); i < ((h) + 1) * (Cfg::kLoadsQ / 2); ++i) \
+      regQ[set][i] = *reinterpret_cast<const u32x4 *>(srcQ[i] + (k0));
+#define HSD_GEMM_STORE(set, stage, h)                                                               \
+  {                                                                                                 \
+    uint16_t *sd = smem + (stage) * Cfg::kStage;                                                    \
+    _Pragma("unroll") for (int i = (h) * (Cfg::kLoadsP / 2); i < ((h) + 1) * (Cfg::kLoadsP / 2); ++i) { \
+      int c = t + NT * i;                                                                           \
+      *reinterpret_cast<u32x4 *>(sd + (c / CH) * LS + (c % CH) * 8) = regP[set][i];                 \
+    }                                                                                               \
+    _Pragma("unroll") for (int i = (h) * (Cfg::kLoadsQ / 2); i < ((h) + 1) * (Cfg::kLoadsQ / 2); ++i) { \
+      int c = t + NT * i;                                                                           \
+      *reinterpret_cast<u32x4 *>(sd + BP * LS + (c / CH) * LS + (c % CH) * 8) = regQ[set][i];       \
+    }                                                                                               \
+  }
+#define HSD_GEMM_KSTEP(kk)                                                                          \
+  {                                                                                                 \
+    bf16x8 a[TM], b[TN];                                                                            \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) a[i] =                                           \
+        *reinterpret_cast<const bf16x8 *>(sp + frag_p + i * 32 * LS + (kk) * 16);                   \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j) b[j] =                                           \
+        *reinterpret_cast<const bf16x8 *>(sp + frag_q + j * 32 * LS + (kk) * 16);                   \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)   \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);         \
+  }
+#define HSD_GEMM_ITER(kt, ld, st)                                                                   \
+  {                                                                                                 \
+    const uint16_t *sp = smem + ((kt) & 1) * Cfg::kStage;                                           \
+    const bool req = (kt) + 2 < nk, put = (kt) + 1 < nk;                                            \
+    const int knext = kc0 + ((kt) + 2) * BK;                                                        \
+    if (req) { HSD_GEMM_LOAD(ld, knext, 0) }                                                        \
+    HSD_GEMM_KSTEP(0)                                                                               \
+    __builtin_amdgcn_sched_barrier(0);                                                              \
+    if (req) { HSD_GEMM_LOAD(ld, knext, 1) }                                                        \
+    HSD_GEMM_KSTEP(1)                                                                               \
+    __builtin_amdgcn_sched_barrier(0);                                                              \
+    if (put) HSD_GEMM_STORE(st, ((kt) + 1) & 1, 0)                                                  \
+    HSD_GEMM_KSTEP(2)                                                                               \
+    __builtin_amdgcn_sched_barrier(0);                                                              \
+    if (put) HSD_GEMM_STORE(st, ((kt) + 1) & 1, 1)                                                  \
+    HSD_GEMM_KSTEP(3)                                                                               \
+    __syncthreads();                                                                                \
+  }
+
+  for (int chunk = c_begin; chunk < c_end; ++chunk) {
+    const int kc0 = chunk * k_len;
+    HSD_GEMM_LOAD(0, kc0, 0) HSD_GEMM_LOAD(0, kc0, 1)
+    if (nk > 1) { HSD_GEMM_LOAD(1, kc0 + BK, 0) HSD_GEMM_LOAD(1, kc0 + BK, 1) }
+    HSD_GEMM_STORE(0, 0, 0) HSD_GEMM_STORE(0, 0, 1)
+    __syncthreads();
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+      HSD_GEMM_ITER(kt, 0, 1)
+      HSD_GEMM_ITER(kt + 1, 1, 0)
+    }
+    if (kt < nk) HSD_GEMM_ITER(kt, 0, 1)
+    if constexpr (WALK_CHUNKS) {
+      // chunk sums are added in chunk order; the first chunk initialises the total
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          tot[i][j] = (chunk == 0) ? acc[i][j] : tot[i][j] + acc[i][j];
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        }
+    }
+  }  // chunk loop
+#undef HSD_GEMM_LOAD
+#undef HSD_GEMM_STORE
+#undef HSD_GEMM_KSTEP
+#undef HSD_GEMM_ITER
+  if constexpr (WALK_CHUNKS) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = tot[i][j];
+  }
+
+  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(split ? blockIdx.y : -1, M));
 }
 
 }  // namespace hsd

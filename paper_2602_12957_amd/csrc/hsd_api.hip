@@ -15,6 +15,7 @@
 #include "common.h"
 #include "epilogues.h"
 #include "gemm_mfma.h"
+#include "gemm_mfma8.h"
 #include "gemm_simple.h"
 #include "misc_kernels.h"
 
@@ -29,6 +30,7 @@ struct hsd_ctx {
   std::vector<const void *> wqkv, wo, w_gate_up, w_down;
   int n_cu;
   bool force_simple;  // HSD_FORCE_SIMPLE=1: run the plain kernels also for bf16 (cross-check of the MFMA path)
+  int64_t split_rows; // largest row count for which the O / down projections run as split-K
   int gemm_cfg[5];    // tile configuration of the MFMA GEMM per call site (qkv, o, gate_up, down, lm_head)
   // per-kernel timing (hsd_profile_*)
   int prof_which = HSD_PROF_NONE;
@@ -47,8 +49,17 @@ struct Workspace {
   int32_t *row_seq, *row_pos, *dump_slot, *tile_cu;
   float2 *rope_cs;
   Top2 *lm_part;
+  float *part;  // split-K partial sums of the O / down projections
   size_t total;
 };
+
+// The O and down projections run as split-K while the launch would otherwise leave most CUs idle: fewer output
+// tiles than twice the 256 CUs of the chip.  Returns the largest row count for which that is the case.
+inline int64_t split_row_limit(const hsd_model_desc &d) {
+  const int64_t tiles_n = d.d_model / 128;
+  return (512 / tiles_n) * 128;
+}
+constexpr int kChunksO = 2, kChunksDown = 4;  // fixed per projection: the K-reduction order never depends on the batch
 
 // Carves the workspace; with base == nullptr only the size is computed.
 Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
@@ -72,6 +83,8 @@ Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
   w.tile_cu = reinterpret_cast<int32_t *>(take((n_seq + 1) * sizeof(int32_t)));
   w.rope_cs = reinterpret_cast<float2 *>(take(T * 32 * sizeof(float2)));
   w.lm_part = reinterpret_cast<Top2 *>(take(T * (d.vocab / 64) * sizeof(Top2)));
+  const int64_t part_rows = T < split_row_limit(d) ? T : split_row_limit(d);
+  w.part = reinterpret_cast<float *>(take(d.dtype == HSD_BF16 ? kChunksDown * part_rows * d.d_model * sizeof(float) : 0));
   w.total = off;
   return w;
 }
@@ -106,10 +119,11 @@ struct GemmModeOf {
   static constexpr int value = Epi::kDual ? kModeDual : (std::is_same<Epi, EpiLMHead>::value ? kModeSwapLM : kModeNormal);
 };
 
-template <typename Cfg, typename Epi>
-int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi) {
+template <typename Cfg, typename Epi, bool WALK>
+int launch_gemm_mfma_impl(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks,
+                          bool split) {
   constexpr int MODE = GemmModeOf<Epi>::value;
-  auto kern = k_gemm_mfma<Cfg, MODE, Epi>;
+  auto kern = k_gemm_mfma<Cfg, MODE, Epi, WALK>;
   constexpr int smem = Cfg::kSmemBytes;
   static bool attr_done = false;  // per instantiation; the attribute is per function, setting it twice is harmless
   if (!attr_done) {
@@ -122,8 +136,40 @@ int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const v
   if constexpr (MODE == kModeSwapLM) epi.n_tiles = (N / Cfg::BP) * Cfg::WM;
   int tiles_act, tiles_w;
   gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
-  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(Cfg::kThreads), smem, st, M, N, K,
-                     static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), epi);
+  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w, split ? k_chunks : 1), dim3(Cfg::kThreads), smem, st, M, N, K,
+                     k_chunks, static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), epi);
+  HSD_LAUNCH_CHECK();
+  return HSD_OK;
+}
+
+// k_chunks > 1 without split: the workgroup walks the chunks itself (kernel variant with a second accumulator set)
+template <typename Cfg, typename Epi>
+int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks = 1,
+                     bool split = false) {
+  if constexpr (Epi::kChunked) {
+    if (k_chunks > 1 && !split) return launch_gemm_mfma_impl<Cfg, Epi, true>(st, M, N, K, A, W, epi, k_chunks, false);
+  }
+  return launch_gemm_mfma_impl<Cfg, Epi, false>(st, M, N, K, A, W, epi, k_chunks, split);
+}
+
+template <typename Epi>
+int launch_gemm_mfma8(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi) {
+  constexpr int MODE = GemmModeOf<Epi>::value;
+  using Cfg = GemmCfg8;
+  auto kern = k_gemm_mfma8<MODE, Epi>;
+  constexpr int smem = Cfg::kSmemBytes;
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
+        hipSuccess)
+      return HSD_EHIP;
+    attr_done = true;
+  }
+  if constexpr (MODE == kModeSwapLM) epi.n_tiles = (N / Cfg::BP) * Cfg::WM;
+  int tiles_act, tiles_w;
+  gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
+  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(512), smem, st, M, N, K, static_cast<const bf16 *>(A),
+                     static_cast<const bf16 *>(W), epi);
   HSD_LAUNCH_CHECK();
   return HSD_OK;
 }
@@ -131,27 +177,23 @@ int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const v
 // Tile configurations of the MFMA GEMM (HSD_GEMM_CFG selects one for experiments; default per call site).
 using GemmCfg0 = GemmCfg<128, 128, 64, 2, 2>;
 using GemmCfg1 = GemmCfg<256, 128, 64, 2, 2>;
-using GemmCfg2 = GemmCfg<256, 256, 64, 2, 2>;
-using GemmCfg3 = GemmCfg<256, 256, 32, 2, 2>;
 using GemmCfg4 = GemmCfg<128, 256, 64, 2, 2>;
-using GemmCfg5 = GemmCfg<256, 256, 64, 2, 4>;   // 8 waves, wave tile 128x64
 using GemmCfg6 = GemmCfg<256, 128, 64, 4, 2>;   // 8 waves, wave tile 64x64
-using GemmCfg7 = GemmCfg<128, 256, 64, 2, 4>;   // 8 waves, wave tile 64x64
+
 
 template <typename T, typename Epi>
 int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int K, const void *A, const void *W,
-                const Epi &epi) {
+                const Epi &epi, int k_chunks = 1, bool split = false) {
   if constexpr (std::is_same<T, bf16>::value) {
     if (!ctx->force_simple && K % 64 == 0) {
       switch (ctx->gemm_cfg[site]) {
-        case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi);
-        case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi);
-        case 3: return launch_gemm_mfma<GemmCfg3>(st, M, N, K, A, W, epi);
-        case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi);
-        case 5: return launch_gemm_mfma<GemmCfg5>(st, M, N, K, A, W, epi);
-        case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi);
-        case 7: return launch_gemm_mfma<GemmCfg7>(st, M, N, K, A, W, epi);
-        default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi);
+        case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi, k_chunks, split);
+        case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi, k_chunks, split);
+        case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi, k_chunks, split);
+        case 8:
+          if (k_chunks == 1) return launch_gemm_mfma8(st, M, N, K, A, W, epi);
+          [[fallthrough]];
+        default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi, k_chunks, split);
       }
     }
   }
@@ -169,12 +211,9 @@ int lm_head_tiles(const hsd_ctx *ctx) {
   if (std::is_same<T, bf16>::value && !ctx->force_simple && ctx->desc.d_model % 64 == 0) {
     switch (ctx->gemm_cfg[kSiteLM]) {
       case 1: return V / GemmCfg1::BP * GemmCfg1::WM;
-      case 2: return V / GemmCfg2::BP * GemmCfg2::WM;
-      case 3: return V / GemmCfg3::BP * GemmCfg3::WM;
       case 4: return V / GemmCfg4::BP * GemmCfg4::WM;
-      case 5: return V / GemmCfg5::BP * GemmCfg5::WM;
       case 6: return V / GemmCfg6::BP * GemmCfg6::WM;
-      case 7: return V / GemmCfg7::BP * GemmCfg7::WM;
+      case 8: return V / GemmCfg8::BP * GemmCfg8::WM;
       default: return V / GemmCfg0::BP * GemmCfg0::WM;
     }
   }
@@ -241,14 +280,38 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
   HSD_LAUNCH_CHECK();
 
   RowMeta meta{ws.row_seq, ws.row_pos, ws.rope_cs};
+  const bool mfma_path = std::is_same<T, bf16>::value && !ctx->force_simple;
+  auto chunks_for = [&](int want, int K) { return (mfma_path && K % (want * 64) == 0) ? want : 1; };
+  const bool split_ok = mfma_path && Tq <= ctx->split_rows;
+
+  // RMSNorm of the residual stream; when the projection before it ran as split-K (`pending_chunks` > 0) the same
+  // kernel first adds the partial sums to x in chunk order.
+  auto norm = [&](const float *gain, int pending_chunks) -> int {
+    ProfScope ps(ctx, st, HSD_PROF_RMSNORM);
+    if (pending_chunks > 0)
+      hipLaunchKernelGGL((k_reduce_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
+                         ws.part, pending_chunks, gain, static_cast<T *>(ws.h));
+    else if (gain != nullptr)
+      hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x, gain,
+                         static_cast<T *>(ws.h));
+    HSD_LAUNCH_CHECK();
+    return HSD_OK;
+  };
+  // x += A W^T with a fixed chunking of K; returns (through `pending`) the number of partials left to add
+  auto residual_proj = [&](int site, int prof, const void *A, const void *W, int K, int want_chunks,
+                           int *pending) -> int {
+    ProfScope ps(ctx, st, prof);
+    const int chunks = chunks_for(want_chunks, K);
+    const bool split = split_ok && chunks > 1;
+    EpiResidual er{ws.x, d.d_model, ws.part, false};
+    *pending = split ? chunks : 0;
+    return launch_gemm<T>(ctx, st, site, Tq, d.d_model, K, A, W, er, chunks, split);
+  };
+
+  int pending = 0;
+  if ((rc = norm(ctx->attn_norm[0], 0))) return rc;
   for (int l = 0; l < d.n_layers; ++l) {
     PagedKV kv{pool->k_pool, pool->v_pool, b->block_table, b->max_blocks_per_seq, pool->n_blocks, d.n_kv_heads, l};
-    {
-      ProfScope ps(ctx, st, HSD_PROF_RMSNORM);
-      hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
-                         ctx->attn_norm[l], static_cast<T *>(ws.h));
-      HSD_LAUNCH_CHECK();
-    }
     EpiQKV<T> eq{d.n_q_heads, d.n_kv_heads, meta, kv, static_cast<T *>(ws.q)};
     {
       ProfScope ps(ctx, st, HSD_PROF_GEMM_QKV);
@@ -258,29 +321,22 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
       ProfScope ps(ctx, st, HSD_PROF_ATTENTION);
       if ((rc = launch_attention<T>(ctx, st, b, meta, kv, ws))) return rc;
     }
-    EpiResidual er{ws.x, d.d_model};
-    {
-      ProfScope ps(ctx, st, HSD_PROF_GEMM_O);
-      if ((rc = launch_gemm<T>(ctx, st, kSiteO, Tq, d.d_model, qdim, ws.a, ctx->wo[l], er))) return rc;
-    }
-    hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
-                       ctx->ffn_norm[l], static_cast<T *>(ws.h));
-    HSD_LAUNCH_CHECK();
+    if ((rc = residual_proj(kSiteO, HSD_PROF_GEMM_O, ws.a, ctx->wo[l], qdim, kChunksO, &pending))) return rc;
+    if ((rc = norm(ctx->ffn_norm[l], pending))) return rc;
     EpiSwiGLU<T> es{static_cast<T *>(ws.u), d.d_ffn};
     {
       ProfScope ps(ctx, st, HSD_PROF_GEMM_GATE_UP);
       if ((rc = launch_gemm<T>(ctx, st, kSiteGateUp, Tq, d.d_ffn, d.d_model, ws.h, ctx->w_gate_up[l], es))) return rc;
     }
-    {
-      ProfScope ps(ctx, st, HSD_PROF_GEMM_DOWN);
-      if ((rc = launch_gemm<T>(ctx, st, kSiteDown, Tq, d.d_model, d.d_ffn, ws.u, ctx->w_down[l], er))) return rc;
-    }
+    if ((rc = residual_proj(kSiteDown, HSD_PROF_GEMM_DOWN, ws.u, ctx->w_down[l], d.d_ffn, kChunksDown, &pending)))
+      return rc;
+    // the norm that follows: next layer's attention norm, or the final norm before the LM head (none for prefill)
+    const float *next_gain = (l + 1 < d.n_layers) ? ctx->attn_norm[l + 1] : (with_head ? ctx->final_norm : nullptr);
+    if (next_gain != nullptr || pending > 0)
+      if ((rc = norm(next_gain, pending))) return rc;
   }
   if (!with_head) return HSD_OK;
 
-  hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
-                     ctx->final_norm, static_cast<T *>(ws.h));
-  HSD_LAUNCH_CHECK();
   const int32_t *dump_slot = nullptr;
   if (b->n_dump > 0 && b->logits_dump != nullptr) {
     hipLaunchKernelGGL(k_fill_i32, dim3((Tq + 255) / 256), dim3(256), 0, st, ws.dump_slot, Tq, -1);
@@ -422,8 +478,14 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   c->n_cu = prop.multiProcessorCount;
   const char *fs = std::getenv("HSD_FORCE_SIMPLE");
   c->force_simple = fs != nullptr && fs[0] == '1';
+  // HSD_SPLIT_ROWS (tests): lower the row count up to which split-K is used, to exercise the chunk-walking GEMM
+  c->split_rows = split_row_limit(*desc);
+  if (const char *sr = std::getenv("HSD_SPLIT_ROWS")) {
+    const int64_t v = std::atoll(sr);
+    if (v >= 0 && v < c->split_rows) c->split_rows = v;
+  }
   // HSD_GEMM_CFG="q,o,g,d,l" (or one number for all) overrides the per-site tile configuration (experiments)
-  const int defaults[5] = {0, 0, 0, 0, 0};
+  const int defaults[5] = {0, 0, 8, 0, 8};  // 256x256 8-wave tiles for the wide projections (gate/up, LM head)
   for (int i = 0; i < 5; ++i) c->gemm_cfg[i] = defaults[i];
   if (const char *gc = std::getenv("HSD_GEMM_CFG")) {
     int vals[5], n = std::sscanf(gc, "%d,%d,%d,%d,%d", &vals[0], &vals[1], &vals[2], &vals[3], &vals[4]);

@@ -106,6 +106,49 @@ __global__ void k_rmsnorm(int n_rows, int d, float eps, const float *__restrict_
 }
 
 // ------------------------------------------------------------------------------------------------
+// Split-K reduction fused with the residual add and the following RMSNorm:
+//   x[r,:] += ((part[0][r,:] + part[1][r,:]) + ...)   (chunk order, the order the unsplit GEMM uses)
+//   h[r,:]  = rmsnorm(x[r,:]) * gain                  (skipped when gain == nullptr)
+// One wave per row, 4 rows per block.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_reduce_rmsnorm(int n_rows, int d, float eps, float *__restrict__ x, const float *__restrict__ part,
+                                 int n_splits, const float *__restrict__ gain, T *__restrict__ h) {
+  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int r = blockIdx.x * 4 + wave;
+  if (r >= n_rows) return;
+  float4 *xr = reinterpret_cast<float4 *>(x + static_cast<size_t>(r) * d);
+  const size_t split_stride = static_cast<size_t>(n_rows) * d / 4;
+  const float4 *pr = reinterpret_cast<const float4 *>(part) + static_cast<size_t>(r) * d / 4;
+  int n4 = d >> 2;
+  float ss = 0.f;
+  for (int c = lane; c < n4; c += kWave) {
+    float4 s = pr[c];
+    for (int k = 1; k < n_splits; ++k) {
+      float4 p = pr[k * split_stride + c];
+      s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+    float4 v = xr[c];
+    v.x += s.x; v.y += s.y; v.z += s.z; v.w += s.w;
+    xr[c] = v;
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  if (gain == nullptr) return;
+  ss = wave_sum(ss);
+  float rstd = 1.0f / sqrtf(ss / static_cast<float>(d) + eps);
+  const float4 *g4 = reinterpret_cast<const float4 *>(gain);
+  T *hr = h + static_cast<size_t>(r) * d;
+  for (int c = lane; c < n4; c += kWave) {
+    float4 v = xr[c];
+    float4 g = g4[c];
+    hr[4 * c + 0] = from_f32<T>(v.x * rstd * g.x);
+    hr[4 * c + 1] = from_f32<T>(v.y * rstd * g.y);
+    hr[4 * c + 2] = from_f32<T>(v.z * rstd * g.z);
+    hr[4 * c + 3] = from_f32<T>(v.w * rstd * g.w);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Block-wide exclusive scan of up to HSD_MAX_SEQ ints held in LDS (1024 threads, 4 items each).
 // On return s_val[i] holds the exclusive prefix and the function returns the grand total.
 // ------------------------------------------------------------------------------------------------
