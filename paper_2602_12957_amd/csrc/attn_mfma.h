@@ -107,35 +107,44 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
   const int key = t >> 3, ch = t & 7, pg = t >> 7, vd = (t & 127) >> 1, hf = t & 1;
   uint4 rk, rv;
   int bid;
+  // fetch_id only ISSUES the block-table read (the index is range-checked, the value is not looked at until the
+  // next iteration): examining the id here would stall the wave for a full memory latency every iteration
   auto fetch_id = [&](int kt) {
     const int p0 = kt * kAttnKeys + pg * kBlk;
-    bid = (p0 < n_valid) ? kv_lookup_block(kv, slot, p0) : -1;
+    const int bi = p0 / kBlk;
+    bid = -1;
+    if (p0 < n_valid && bi < kv.max_blocks_per_seq)
+      bid = kv.block_table[static_cast<size_t>(slot) * kv.max_blocks_per_seq + bi];
   };
+  // prefetch only ISSUES the loads; nothing here may depend on the loaded values, or the wave would wait for
+  // them on the spot and the whole point of requesting a tile ahead would be lost
   auto prefetch = [&](int kt) {
-    const int kb = kt * kAttnKeys;
-    rk = make_uint4(0, 0, 0, 0);
-    Frag8 f;
-    f.u = make_uint4(0, 0, 0, 0);
-    if (bid >= 0) {
-      const size_t off = kv_block_offset(kv, bid, kvh);
-      rk = *reinterpret_cast<const uint4 *>(kpool + off + (key & 15) * kHd + ch * 8);
-      f.u = *reinterpret_cast<const uint4 *>(vpool + off + vd * kBlk + hf * 8);
-      if (kb + pg * kBlk + kBlk > n_valid) {
-        // last, partly filled page: slots of positions that hold no data of this sequence must read as 0
-        // (their probability is 0, but 0 * stale-NaN would poison the product)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          int tok = (e < 4) ? 4 * hf + e : 8 + 4 * hf + (e - 4);
-          if (kb + pg * kBlk + tok >= n_valid) f.h[e] = 0;
-        }
-      }
-    }
-    rv = f.u;
+    (void)kt;
+    // unconditional loads: a page id that is absent (-1, beyond the data of this round) or out of range reads
+    // block 0 instead; such a page lies wholly past n_valid, so store_lds zeroes its V and the causal mask
+    // discards its scores.  A branch here would make the compiler wait for the loads inside it.
+    const int b = (bid >= 0 && bid < kv.n_blocks) ? bid : 0;
+    const size_t off = kv_block_offset(kv, b, kvh);
+    rk = *reinterpret_cast<const uint4 *>(kpool + off + (key & 15) * kHd + ch * 8);
+    rv = *reinterpret_cast<const uint4 *>(vpool + off + vd * kBlk + hf * 8);
   };
-  auto store_lds = [&](int stage) {
+  // kt = tile the staged registers belong to
+  auto store_lds = [&](int stage, int kt) {
     uint16_t *ks = smem + stage * kAttnStage, *vt = ks + kAttnKeys * kKsStride;
     *reinterpret_cast<uint4 *>(ks + key * kKsStride + ch * 8) = rk;
-    *reinterpret_cast<uint4 *>(vt + (pg * kHd + vd) * kVtStride + hf * 8) = rv;
+    Frag8 f;
+    f.u = rv;
+    const int p0 = kt * kAttnKeys + pg * kBlk;
+    if (p0 + kBlk > n_valid) {
+      // last, partly filled page: slots of positions that hold no data of this sequence must read as 0
+      // (their probability is 0, but 0 * stale-NaN would poison the product)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        int tok = (e < 4) ? 4 * hf + e : 8 + 4 * hf + (e - 4);
+        if (p0 + tok >= n_valid) f.h[e] = 0;
+      }
+    }
+    *reinterpret_cast<uint4 *>(vt + (pg * kHd + vd) * kVtStride + hf * 8) = f.u;
   };
 
   floatx16 o[2];
@@ -149,7 +158,7 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
   fetch_id(0);
   prefetch(0);
   if (n_tiles > 1) fetch_id(1);
-  store_lds(0);
+  store_lds(0, 0);
   __syncthreads();
   for (int kt = 0; kt < n_tiles; ++kt) {
     if (kt + 1 < n_tiles) {
@@ -188,18 +197,24 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
       // the reference point 0 then yields p = 0 and corr = 0 without producing inf - inf
       const float msc = (m_new == -INFINITY) ? 0.f : m_new;
       const float corr = (m_run == -INFINITY) ? 0.f : ldexpf(1.0f, static_cast<int>(m_run - msc));
-      l_run *= corr;
+      // the reference point is an integer and seldom moves after the first tiles; when it moved for no lane
+      // every factor is exactly 1 and the rescale is skipped (wave-uniform branch, same bits either way)
+      if (__any(m_new != m_run)) {
+        l_run *= corr;
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[i][v] *= corr;
+          for (int v = 0; v < 16; ++v) o[i][v] *= corr;
+      }
       bf16x8 pf[2];
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
         floatx8 pv;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const float p = exp2f(fmaf(st[8 * kk + e], sc, -msc));
+          // bare hardware exponential: arguments are <= 0 and results below 2^-126 may flush to zero, far
+          // beneath half a bf16 unit of any probability that matters
+          const float p = __builtin_amdgcn_exp2f(fmaf(st[8 * kk + e], sc, -msc));
           l_run += p;
           pv[e] = p;
         }
@@ -216,7 +231,7 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
         }
       }
     }
-    if (kt + 1 < n_tiles) store_lds((kt + 1) & 1);
+    if (kt + 1 < n_tiles) store_lds((kt + 1) & 1, kt + 1);
     __syncthreads();
   }
 

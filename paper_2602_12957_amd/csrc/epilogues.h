@@ -5,6 +5,8 @@
 // of the same output column side by side.
 #pragma once
 
+#include <type_traits>
+
 #include "common.h"
 
 namespace hsd {
@@ -90,7 +92,15 @@ struct EpiSwiGLU {
   __device__ __forceinline__ const EpiSwiGLU &for_split(int, int) const { return *this; }
   T *u;
   int ld;
-  __device__ __forceinline__ static float f(float g, float up) { return g / (1.0f + expf(-g)) * up; }
+  // silu(g) * up with the hardware exp2 and reciprocal (each within 1 ulp; the result is rounded to the operand
+  // type right after).  g -> -inf gives exp2 = +inf, rcp = 0, result -0.
+  __device__ __forceinline__ static float f(float g, float up) {
+    if constexpr (std::is_same<T, float>::value) {
+      return g / (1.0f + expf(-g)) * up;   // fp32 debug path: full-precision library routines
+    } else {
+      return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * up;
+    }
+  }
   __device__ __forceinline__ void one2(int m, int n, float g, float up) const {
     u[static_cast<size_t>(m) * ld + n] = from_f32<T>(f(g, up));
   }

@@ -98,34 +98,21 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, const b
       *reinterpret_cast<u32x4 *>(sd + BP * LS + lds_dst + i * 64 * LS) = regQ[set][i];                \
     }                                                                                                 \
   }
-#ifndef HSD_G8_DBG
-#define HSD_G8_DBG 0
-#endif
 #define HSD_G8_KSTEP(kk)                                                                              \
   {                                                                                                   \
     bf16x8 a[TM], b[TN];                                                                              \
-    if (!(HSD_G8_DBG & 8) || kt == 0) {                                                               \
     _Pragma("unroll") for (int i = 0; i < TM; ++i) a[i] =                                             \
         *reinterpret_cast<const bf16x8 *>(sp + frag_p + i * 32 * LS + (kk) * 16);                     \
     _Pragma("unroll") for (int j = 0; j < TN; ++j) b[j] =                                             \
         *reinterpret_cast<const bf16x8 *>(sp + frag_q + j * 32 * LS + (kk) * 16);                     \
-    } else {                                                                                          \
-    _Pragma("unroll") for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8 *>(&regP[0][i]); \
-    _Pragma("unroll") for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8 *>(&regQ[0][j]); \
-    }                                                                                                 \
-    if (!(HSD_G8_DBG & 1)) {                                                                          \
     _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)     \
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);           \
-    } else {                                                                                          \
-    _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)     \
-        acc[i][j][0] += (float)a[i][0] + (float)b[j][1];                                              \
-    }                                                                                                 \
   }
   // one iteration: multiply slice kt (LDS stage kt & 1); request slice kt+2 into set `ld`; store set `st` (kt+1)
 #define HSD_G8_ITER(kt, ld, st)                                                                       \
   {                                                                                                   \
     const uint16_t *sp = smem + ((kt) & 1) * Cfg::kStage;                                             \
-    const bool req = (kt) + 2 < nk && !(HSD_G8_DBG & 2), put = (kt) + 1 < nk && !(HSD_G8_DBG & 4);                                              \
+    const bool req = (kt) + 2 < nk, put = (kt) + 1 < nk;                                              \
     const int kbyte = ((kt) + 2) * BK * 2;                                                            \
     if (req) { HSD_G8_LOAD(ld, 0, kbyte) HSD_G8_LOAD(ld, 1, kbyte) }                                  \
     HSD_G8_KSTEP(0)                                                                                   \
@@ -138,7 +125,7 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, const b
     __builtin_amdgcn_sched_barrier(0);                                                                \
     if (put) HSD_G8_STORE(st, ((kt) + 1) & 1, 2, 4)                                                   \
     HSD_G8_KSTEP(3)                                                                                   \
-    if (!(HSD_G8_DBG & 16)) __syncthreads();                                                                                  \
+    __syncthreads();                                                                                  \
   }
 
   HSD_G8_LOAD(0, 0, 0) HSD_G8_LOAD(0, 1, 0) HSD_G8_LOAD(0, 2, 0) HSD_G8_LOAD(0, 3, 0)

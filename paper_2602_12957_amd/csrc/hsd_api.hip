@@ -179,6 +179,8 @@ using GemmCfg0 = GemmCfg<128, 128, 64, 2, 2>;
 using GemmCfg1 = GemmCfg<256, 128, 64, 2, 2>;
 using GemmCfg4 = GemmCfg<128, 256, 64, 2, 2>;
 using GemmCfg6 = GemmCfg<256, 128, 64, 4, 2>;   // 8 waves, wave tile 64x64
+using GemmCfg2 = GemmCfg<64, 128, 64, 2, 2>;    // small tiles for narrow projections (more workgroups)
+using GemmCfg3 = GemmCfg<128, 64, 64, 2, 1>;
 
 
 template <typename T, typename Epi>
@@ -186,8 +188,12 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
                 const Epi &epi, int k_chunks = 1, bool split = false) {
   if constexpr (std::is_same<T, bf16>::value) {
     if (!ctx->force_simple && K % 64 == 0) {
-      switch (ctx->gemm_cfg[site]) {
+      int cfg = ctx->gemm_cfg[site];
+      if (site == kSiteLM && (cfg == 2 || cfg == 3)) cfg = 0;  // the LM-head partial buffer assumes >= 64 rows per wave
+      switch (cfg) {
         case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi, k_chunks, split);
+        case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi, k_chunks, split);
+        case 3: return launch_gemm_mfma<GemmCfg3>(st, M, N, K, A, W, epi, k_chunks, split);
         case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi, k_chunks, split);
         case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi, k_chunks, split);
         case 8:
@@ -223,7 +229,8 @@ int lm_head_tiles(const hsd_ctx *ctx) {
 // Verification attention: bf16 goes to the MFMA kernel when the GQA group size fits its wave mapping.
 template <typename T>
 int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, const RowMeta &meta, const PagedKV &kv,
-                     const Workspace &ws) {
+                     const Workspace &ws, bool page_mode) {
+  (void)page_mode;  // both entry points share one tiling so far
   const hsd_model_desc &d = ctx->desc;
   const int group = d.n_q_heads / d.n_kv_heads;
   if constexpr (std::is_same<T, bf16>::value) {
@@ -232,13 +239,13 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
       const int q_tile = 32 * (4 / g4);
       const int max_tiles = b->total_q / q_tile + b->n_seq;
       const dim3 grid(max_tiles, d.n_kv_heads * ((group + g4 - 1) / g4));
-      const size_t smem = 2 * kAttnStage * sizeof(uint16_t);
       const bf16 *q = static_cast<const bf16 *>(ws.q);
       bf16 *o = static_cast<bf16 *>(ws.a);
       if (kv.layer == 0) {  // the tile map depends on the batch only: built once per pass
         hipLaunchKernelGGL(k_attn_tiles, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, q_tile, ws.tile_cu);
         HSD_LAUNCH_CHECK();
       }
+      const size_t smem = 2 * kAttnStage * sizeof(uint16_t);
       if (g4 == 4)
         hipLaunchKernelGGL((k_attn_mfma<4>), grid, dim3(512), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
                            b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);
@@ -261,7 +268,6 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
 template <typename T>
 int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_batch *b, void *ws_base, bool page_mode,
             bool with_head) {
-  (void)page_mode;
   const hsd_model_desc &d = ctx->desc;
   const int Tq = b->total_q;
   Workspace ws = carve(d, Tq, b->n_seq, ws_base);
@@ -319,7 +325,7 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
     }
     {
       ProfScope ps(ctx, st, HSD_PROF_ATTENTION);
-      if ((rc = launch_attention<T>(ctx, st, b, meta, kv, ws))) return rc;
+      if ((rc = launch_attention<T>(ctx, st, b, meta, kv, ws, page_mode))) return rc;
     }
     if ((rc = residual_proj(kSiteO, HSD_PROF_GEMM_O, ws.a, ctx->wo[l], qdim, kChunksO, &pending))) return rc;
     if ((rc = norm(ctx->ffn_norm[l], pending))) return rc;
@@ -485,7 +491,9 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
     if (v >= 0 && v < c->split_rows) c->split_rows = v;
   }
   // HSD_GEMM_CFG="q,o,g,d,l" (or one number for all) overrides the per-site tile configuration (experiments)
-  const int defaults[5] = {0, 0, 8, 0, 8};  // 256x256 8-wave tiles for the wide projections (gate/up, LM head)
+  // 256x256 8-wave tiles for the wide projections (gate/up, LM head), 64x128 tiles for QKV and O (more workgroups),
+  // 128x128 for the split-K down projection
+  const int defaults[5] = {2, 2, 8, 0, 8};
   for (int i = 0; i < 5; ++i) c->gemm_cfg[i] = defaults[i];
   if (const char *gc = std::getenv("HSD_GEMM_CFG")) {
     int vals[5], n = std::sscanf(gc, "%d,%d,%d,%d,%d", &vals[0], &vals[1], &vals[2], &vals[3], &vals[4]);

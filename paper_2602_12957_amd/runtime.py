@@ -277,15 +277,17 @@ class Engine:
         h = self._h_out.numpy()
         return h[:n].copy(), h[n:2 * n].copy(), int(h[2 * n])
 
-    def greedy_decode(self, slots: Sequence[int], pending: Sequence[int], n_tokens: int) -> np.ndarray:
+    def greedy_decode(self, slots: Sequence[int], pending: Sequence[int], n_tokens: int,
+                      mode: str = "region") -> np.ndarray:
         """Plain autoregressive decoding with blocks of length 1 (no draft): each step's bonus token is
         written by the commit kernel straight into the next step's token buffer.  Returns [n_seq, n_tokens]."""
         n = len(slots)
         hist = torch.zeros((n_tokens, n), dtype=torch.int32, device=self.dev)
         b = self._make_batch(slots, [np.asarray([p], dtype=np.int32) for p in pending])
         tok_view = self._d_meta[2 * n + 1: 3 * n + 1]
+        fn = B.hsd_verify_region_batch if mode == "region" else B.hsd_verify_page
         for step in range(n_tokens):
-            B.hsd_verify_region_batch(self.ctx, self.stream, self.cpool, b, _ptr(self.ws), self.ws_bytes)
+            fn(self.ctx, self.stream, self.cpool, b, _ptr(self.ws), self.ws_bytes)
             B.hsd_kv_commit_rollback(self.ctx, self.stream, self.cpool, b, _ptr(tok_view))
             hist[step].copy_(self.bonus[:n])
         torch.cuda.current_stream(self.dev).synchronize()

@@ -31,7 +31,7 @@ def _lossless(desc, specs, seed, mode):
     slots = list(range(n))
     eng.prefill(slots, toks, embs)
     k_max = max(sp.draft_len for sp in specs)
-    target = eng.greedy_decode(slots, pend, k_max)
+    target = eng.greedy_decode(slots, pend, k_max, mode)   # same entry point: the two are tiled differently
     eng.reset()
     eng.prefill(slots, toks, embs)
     drafts, masks = [], []
