@@ -46,9 +46,6 @@ union Frag8 {
   bf16x8 v;
   uint16_t h[8];
 };
-typedef float floatx8 __attribute__((ext_vector_type(8)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 // G4 = query heads of one kv head handled per workgroup (1, 2 or 4); 4/G4 row sub-tiles of 32 queries.
 // The workgroup has 8 waves: waves w and w+4 own the same 32 queries and split every 64-key tile between them

@@ -12,6 +12,14 @@ constexpr int kWave = 64;        // CDNA wavefront width
 constexpr int kHd = HSD_HEAD_DIM;
 constexpr int kBlk = HSD_KV_BLOCK_TOKENS;
 
+// native vector types (kept in VGPRs as whole registers; HIP's uint4 / float4 structs are not)
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 // bf16 is handled as raw 16-bit patterns; arithmetic is always fp32.
 struct bf16 {
   uint16_t v;
@@ -40,6 +48,22 @@ __device__ __forceinline__ bf16 from_f32<bf16>(float x) {
   bf16 r;
   r.v = f32_to_bf16(x);
   return r;
+}
+
+// Consecutive outputs of one row written as one 16-byte piece (dst 16-byte aligned): 4 floats, or 8 values
+// converted to bf16 with the hardware round-to-nearest-even conversion (same rounding as f32_to_bf16).
+__device__ __forceinline__ void store_row(float *dst, const float (&v)[4]) {
+  floatx4 f = {v[0], v[1], v[2], v[3]};
+  *reinterpret_cast<floatx4 *>(dst) = f;
+}
+__device__ __forceinline__ void store_row(bf16 *dst, const float (&v)[8]) {
+  floatx8 f = {v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7]};
+  *reinterpret_cast<bf16x8 *>(dst) = __builtin_convertvector(f, bf16x8);
+}
+__device__ __forceinline__ void store_row(float *dst, const float (&v)[8]) {
+  floatx4 f0 = {v[0], v[1], v[2], v[3]}, f1 = {v[4], v[5], v[6], v[7]};
+  *reinterpret_cast<floatx4 *>(dst) = f0;
+  *reinterpret_cast<floatx4 *>(dst + 4) = f1;
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -105,6 +129,7 @@ struct RowMeta {
   const int32_t *row_seq;  // [T] state row (slot) of the row's sequence
   const int32_t *row_pos;  // [T] absolute position of the row in its sequence
   const float2 *rope_cs;   // [T][32] (cos, sin) of pos * theta^(-2i/64)
+  const int32_t *row_kv;   // [T] 16 * (block id holding the row's position) + position % 16, or -1 if no valid block
 };
 
 // Everything a kernel needs to find a (sequence, position) slot in the paged pools.

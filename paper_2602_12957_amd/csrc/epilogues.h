@@ -23,12 +23,13 @@ struct EpiQKV {
   PagedKV kv;
   T *q_out;  // [T, n_q_heads*64]
 
-  __device__ __forceinline__ void pair(int m, int n, float lo, float hi) const {
-    int head = n >> 6, dim = n & 63;  // dim in [0, 32)
+  // One (row, column pair) at a time, given the row's rotary pair cs = rope_cs[m][n & 31] and cache destination
+  // kvd = row_kv[m].
+  __device__ __forceinline__ void pair_rw(int m, int n, float lo, float hi, float2 cs, int kvd) const {
+    const int head = n >> 6, dim = n & 63;  // dim in [0, 32)
     if (head < n_q_heads + n_kv_heads) {
-      float2 cs = meta.rope_cs[static_cast<size_t>(m) * 32 + dim];
-      float rlo = lo * cs.x - hi * cs.y;
-      float rhi = hi * cs.x + lo * cs.y;
+      const float rlo = lo * cs.x - hi * cs.y;
+      const float rhi = hi * cs.x + lo * cs.y;
       lo = rlo;
       hi = rhi;
     }
@@ -38,20 +39,62 @@ struct EpiQKV {
       dst[32] = from_f32<T>(hi);
       return;
     }
-    int s = meta.row_seq[m], pos = meta.row_pos[m];
-    int b = kv_lookup_block(kv, s, pos);
-    if (b < 0) return;
-    bool is_k = head < n_q_heads + n_kv_heads;
-    int kvh = is_k ? head - n_q_heads : head - n_q_heads - n_kv_heads;
-    if (is_k) {
-      T *dst = static_cast<T *>(kv.k_pool) + kv_block_offset(kv, b, kvh) + (pos % kBlk) * kHd + dim;
+    if (kvd < 0) return;
+    const int b = kvd / kBlk, tok = kvd % kBlk;
+    if (head < n_q_heads + n_kv_heads) {
+      T *dst = static_cast<T *>(kv.k_pool) + kv_block_offset(kv, b, head - n_q_heads) + tok * kHd + dim;
       dst[0] = from_f32<T>(lo);
       dst[32] = from_f32<T>(hi);
     } else {
-      T *dst = static_cast<T *>(kv.v_pool) + kv_block_offset(kv, b, kvh) + kv_v_elem(pos % kBlk, dim);
+      T *dst = static_cast<T *>(kv.v_pool) + kv_block_offset(kv, b, head - n_q_heads - n_kv_heads) + kv_v_elem(tok, dim);
       dst[0] = from_f32<T>(lo);
       dst[32 * kBlk] = from_f32<T>(hi);
     }
+  }
+  // Row-piece form used by the MFMA kernels: kPiece consecutive columns n .. n+7 (lo; n % 64 < 32) of row m and
+  // their rotary partners n+32 .. n+39 (hi).  All loads first, then 16-byte stores.  The head index is the same
+  // for a whole wave (wave-uniform branches).
+  static constexpr int kPiece = 8;
+  __device__ __forceinline__ void piece(int m, int n, float (&lo)[8], float (&hi)[8]) const {
+    const int head = n >> 6, dim = n & 63;
+    const bool rot = head < n_q_heads + n_kv_heads;
+    const int kvd = (head >= n_q_heads) ? meta.row_kv[m] : 0;
+    if (rot) {
+      const floatx4 *cp = reinterpret_cast<const floatx4 *>(meta.rope_cs + static_cast<size_t>(m) * 32 + dim);
+      floatx4 cs[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) cs[q] = cp[q];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float c = cs[e >> 1][2 * (e & 1)], sn = cs[e >> 1][2 * (e & 1) + 1];
+        const float rlo = lo[e] * c - hi[e] * sn;
+        hi[e] = hi[e] * c + lo[e] * sn;
+        lo[e] = rlo;
+      }
+    }
+    if (head < n_q_heads) {
+      T *dst = q_out + static_cast<size_t>(m) * (n_q_heads * kHd) + head * kHd + dim;
+      store_row(dst, lo);
+      store_row(dst + 32, hi);
+      return;
+    }
+    if (kvd < 0) return;
+    const int b = kvd / kBlk, tok = kvd % kBlk;
+    if (rot) {
+      T *dst = static_cast<T *>(kv.k_pool) + kv_block_offset(kv, b, head - n_q_heads) + tok * kHd + dim;
+      store_row(dst, lo);
+      store_row(dst + 32, hi);
+    } else {
+      T *dst = static_cast<T *>(kv.v_pool) + kv_block_offset(kv, b, head - n_q_heads - n_kv_heads) + kv_v_elem(tok, dim);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        dst[e * kBlk] = from_f32<T>(lo[e]);
+        dst[(32 + e) * kBlk] = from_f32<T>(hi[e]);
+      }
+    }
+  }
+  __device__ __forceinline__ void pair(int m, int n, float lo, float hi) const {
+    pair_rw(m, n, lo, hi, meta.rope_cs[static_cast<size_t>(m) * 32 + (n & 31)], meta.row_kv[m]);
   }
 };
 
@@ -70,6 +113,26 @@ struct EpiResidual {
     e.to_part = split >= 0;
     if (split >= 0) e.part = part + static_cast<size_t>(split) * M * ld;
     return e;
+  }
+  // Row-piece form used by the MFMA kernels: four consecutive columns n .. n+3 (lo) and n+32 .. n+35 (hi); eight
+  // adjacent lanes cover a full 128-byte line of the row.
+  static constexpr int kPiece = 4;
+  __device__ __forceinline__ void piece(int m, int n, float (&lo)[4], float (&hi)[4]) const {
+    if (to_part) {
+      float *p = part + static_cast<size_t>(m) * ld + n;
+      store_row(p, lo);
+      store_row(p + 32, hi);
+    } else {
+      float *p = x + static_cast<size_t>(m) * ld + n;
+      const floatx4 a = *reinterpret_cast<const floatx4 *>(p), b = *reinterpret_cast<const floatx4 *>(p + 32);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        lo[e] += a[e];
+        hi[e] += b[e];
+      }
+      store_row(p, lo);
+      store_row(p + 32, hi);
+    }
   }
   __device__ __forceinline__ void pair(int m, int n, float lo, float hi) const {
     if (to_part) {
@@ -100,6 +163,14 @@ struct EpiSwiGLU {
     } else {
       return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * up;
     }
+  }
+  // Row-piece form used by the MFMA kernels: eight consecutive output columns n .. n+7 of row m
+  static constexpr int kPiece = 8;
+  __device__ __forceinline__ void piece_dual(int m, int n, const float (&g)[8], const float (&up)[8]) const {
+    float r[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = f(g[e], up[e]);
+    store_row(u + static_cast<size_t>(m) * ld + n, r);
   }
   __device__ __forceinline__ void one2(int m, int n, float g, float up) const {
     u[static_cast<size_t>(m) * ld + n] = from_f32<T>(f(g, up));

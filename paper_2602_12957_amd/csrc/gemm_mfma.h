@@ -25,9 +25,6 @@
 
 namespace hsd {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // 16-byte staging register (native vector: stays in VGPRs)
 
 enum GemmMode { kModeNormal = 0, kModeDual = 1, kModeSwapLM = 2 };
 
@@ -41,6 +38,8 @@ struct GemmCfg {
   static constexpr int kSmemBytes = 2 * kStage * 2;
   static constexpr int kChunks = BK / 8;                      // 16-byte chunks per tile row
   static constexpr int kLoadsP = BP * kChunks / kThreads, kLoadsQ = BQ * kChunks / kThreads;
+  static constexpr int kEpiStride = TN * 32 + 4;              // floats per row of a wave's epilogue staging region
+  static_assert(WM * WN * 32 * kEpiStride * 4 <= kSmemBytes, "epilogue staging must fit in the operand stages");
   static_assert(BP % (WM * 32) == 0 && BQ % (WN * 64) == 0, "wave tile must be made of 32-row / 64-col groups");
   static_assert(BP * kChunks % kThreads == 0 && BQ * kChunks % kThreads == 0, "tile loads must divide evenly");
 };
@@ -71,7 +70,7 @@ __host__ __device__ inline void gemm_tiles(int M, int N, int &tiles_act, int &ti
 // Hands the accumulators of one wave to the epilogue functor (see the mode descriptions above).
 template <typename Cfg, int MODE, typename Epi>
 __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[Cfg::TM][Cfg::TN], int M, int N, int m0, int n0, int tw,
-                                              int wi, int wj, int lane, const Epi &epi) {
+                                              int wi, int wj, int lane, const Epi &epi, float *stage) {
   constexpr int BP = Cfg::BP, BQ = Cfg::BQ, TM = Cfg::TM, TN = Cfg::TN;
   const int col = lane & 31, half = lane >> 5;
   if constexpr (MODE == kModeSwapLM) {
@@ -107,22 +106,54 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[Cfg::TM][Cfg::TN],
       if (half == 0 && m < M) epi.part[static_cast<size_t>(m) * epi.n_tiles + tw * Cfg::WM + wi] = tp;
     }
   } else {
+    // Accumulators go through LDS to turn the MFMA result layout (a lane owns one COLUMN of 16 scattered rows)
+    // into row pieces of PC = Epi::kPiece columns: in every 64-column group of a 32-row sub-tile, the 32/PC lanes
+    // l % (32/PC) of a row own columns PC*(l % (32/PC)) .. +PC-1 and their partners 32 further on (rotary pairs;
+    // gate/up pairs in dual mode), so that adjacent lanes write adjacent 16-byte pieces of one row.  Each wave
+    // uses a private region (32 rows of TN*32 + 4 floats); LDS executes a wave's accesses in program order, so
+    // only the compiler has to be kept from reordering them (wave-scope fences).
+    constexpr int ST = Cfg::kEpiStride, PC = Epi::kPiece, LPR = 32 / PC, RPI = 64 / LPR;  // lanes per row, rows per pass
+    float *wst = stage + (wi * Cfg::WN + wj) * 32 * ST;
+    const int pc = lane % LPR, pr = lane / LPR;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wi * (BP / Cfg::WM) + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-        if (m >= M) continue;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int j = 0; j < TN; j += 2) {
+        for (int v = 0; v < 16; ++v) wst[(8 * (v >> 2) + 4 * half + (v & 3)) * ST + j * 32 + col] = acc[i][j][v];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        const int r = it * RPI + pr;
+        const int m = m0 + wi * (BP / Cfg::WM) + i * 32 + r;
+#pragma unroll
+        for (int jg = 0; jg < TN / 2; ++jg) {
+          float lo[PC], hi[PC];
+          const float *src = wst + r * ST + jg * 64 + PC * pc;
+#pragma unroll
+          for (int q = 0; q < PC / 4; ++q) {
+            const floatx4 a = *reinterpret_cast<const floatx4 *>(src + 4 * q);
+            const floatx4 b = *reinterpret_cast<const floatx4 *>(src + 32 + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              lo[4 * q + e] = a[e];
+              hi[4 * q + e] = b[e];
+            }
+          }
+          if (m >= M) continue;
           if constexpr (MODE == kModeDual) {
-            epi.one2(m, n0 + wj * (BQ / Cfg::WN / 2) + (j >> 1) * 32 + col, acc[i][j][v], acc[i][j + 1][v]);
+            epi.piece_dual(m, n0 + wj * (BQ / Cfg::WN / 2) + jg * 32 + PC * pc, lo, hi);
           } else {
-            int n = n0 + wj * (BQ / Cfg::WN) + j * 32 + col;
-            if (n < N) epi.pair(m, n, acc[i][j][v], acc[i][j + 1][v]);
+            const int n = n0 + wj * (BQ / Cfg::WN) + jg * 64 + PC * pc;
+            if (n < N) epi.piece(m, n, lo, hi);
           }
         }
       }
+    }
   }
 }
 
@@ -227,21 +258,23 @@ __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K
     _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)   \
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);         \
   }
-#define HSD_GEMM_ITER(kt, ld, st)                                                                   \
+  // REQ / PUT are compile-time: a run-time condition around the loads would make the compiler count the loads
+  // in flight for the path WITHOUT them, i.e. wait for everything before each LDS store, and the two-slice
+  // look-ahead would collapse to none.  The loop below therefore peels the last two iterations.
+#define HSD_GEMM_ITER(kt, ld, st, REQ, PUT)                                                         \
   {                                                                                                 \
     const uint16_t *sp = smem + ((kt) & 1) * Cfg::kStage;                                           \
-    const bool req = (kt) + 2 < nk, put = (kt) + 1 < nk;                                            \
     const int knext = kc0 + ((kt) + 2) * BK;                                                        \
-    if (req) { HSD_GEMM_LOAD(ld, knext, 0) }                                                        \
+    if (REQ) { HSD_GEMM_LOAD(ld, knext, 0) }                                                        \
     HSD_GEMM_KSTEP(0)                                                                               \
     __builtin_amdgcn_sched_barrier(0);                                                              \
-    if (req) { HSD_GEMM_LOAD(ld, knext, 1) }                                                        \
+    if (REQ) { HSD_GEMM_LOAD(ld, knext, 1) }                                                        \
     HSD_GEMM_KSTEP(1)                                                                               \
     __builtin_amdgcn_sched_barrier(0);                                                              \
-    if (put) HSD_GEMM_STORE(st, ((kt) + 1) & 1, 0)                                                  \
+    if (PUT) HSD_GEMM_STORE(st, ((kt) + 1) & 1, 0)                                                  \
     HSD_GEMM_KSTEP(2)                                                                               \
     __builtin_amdgcn_sched_barrier(0);                                                              \
-    if (put) HSD_GEMM_STORE(st, ((kt) + 1) & 1, 1)                                                  \
+    if (PUT) HSD_GEMM_STORE(st, ((kt) + 1) & 1, 1)                                                  \
     HSD_GEMM_KSTEP(3)                                                                               \
     __syncthreads();                                                                                \
   }
@@ -252,12 +285,23 @@ __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K
     if (nk > 1) { HSD_GEMM_LOAD(1, kc0 + BK, 0) HSD_GEMM_LOAD(1, kc0 + BK, 1) }
     HSD_GEMM_STORE(0, 0, 0) HSD_GEMM_STORE(0, 0, 1)
     __syncthreads();
+    // slice kt is in LDS stage kt & 1 and came through register set kt & 1; iteration kt requests slice kt+2
+    // into set kt & 1 and stores set (kt+1) & 1.  Full iterations run while kt + 2 < nk.
     int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
-      HSD_GEMM_ITER(kt, 0, 1)
-      HSD_GEMM_ITER(kt + 1, 1, 0)
+    for (; kt + 3 < nk; kt += 2) {
+      HSD_GEMM_ITER(kt, 0, 1, true, true)
+      HSD_GEMM_ITER(kt + 1, 1, 0, true, true)
     }
-    if (kt < nk) HSD_GEMM_ITER(kt, 0, 1)
+    if (kt + 2 < nk) {  // one more full iteration, then the two-iteration tail on swapped sets
+      HSD_GEMM_ITER(kt, 0, 1, true, true)
+      HSD_GEMM_ITER(kt + 1, 1, 0, false, true)
+      HSD_GEMM_ITER(kt + 2, 0, 1, false, false)
+    } else if (kt + 1 < nk) {
+      HSD_GEMM_ITER(kt, 0, 1, false, true)
+      HSD_GEMM_ITER(kt + 1, 1, 0, false, false)
+    } else {
+      HSD_GEMM_ITER(kt, 0, 1, false, false)
+    }
     if constexpr (WALK_CHUNKS) {
       // chunk sums are added in chunk order; the first chunk initialises the total
 #pragma unroll
@@ -281,7 +325,8 @@ __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K
       for (int j = 0; j < TN; ++j) acc[i][j] = tot[i][j];
   }
 
-  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(split ? blockIdx.y : -1, M));
+  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(split ? blockIdx.y : -1, M),
+                           reinterpret_cast<float *>(smem_raw));
 }
 
 }  // namespace hsd

@@ -109,44 +109,64 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, const b
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);           \
   }
   // one iteration: multiply slice kt (LDS stage kt & 1); request slice kt+2 into set `ld`; store set `st` (kt+1)
-#define HSD_G8_ITER(kt, ld, st)                                                                       \
+  // REQ / PUT are compile-time so that the compiler can count the loads in flight exactly (a run-time condition
+  // around the requests would force a wait for ALL loads before every LDS store)
+#define HSD_G8_ITER(kt, ld, st, REQ, PUT)                                                             \
   {                                                                                                   \
     const uint16_t *sp = smem + ((kt) & 1) * Cfg::kStage;                                             \
-    const bool req = (kt) + 2 < nk, put = (kt) + 1 < nk;                                              \
     const int kbyte = ((kt) + 2) * BK * 2;                                                            \
-    if (req) { HSD_G8_LOAD(ld, 0, kbyte) HSD_G8_LOAD(ld, 1, kbyte) }                                  \
+    if (REQ) { HSD_G8_LOAD(ld, 0, kbyte) HSD_G8_LOAD(ld, 1, kbyte) }                                  \
     HSD_G8_KSTEP(0)                                                                                   \
     __builtin_amdgcn_sched_barrier(0);                                                                \
-    if (req) { HSD_G8_LOAD(ld, 2, kbyte) HSD_G8_LOAD(ld, 3, kbyte) }                                  \
+    if (REQ) { HSD_G8_LOAD(ld, 2, kbyte) HSD_G8_LOAD(ld, 3, kbyte) }                                  \
     HSD_G8_KSTEP(1)                                                                                   \
     __builtin_amdgcn_sched_barrier(0);                                                                \
-    if (put) HSD_G8_STORE(st, ((kt) + 1) & 1, 0, 2)                                                   \
+    if (PUT) HSD_G8_STORE(st, ((kt) + 1) & 1, 0, 2)                                                   \
     HSD_G8_KSTEP(2)                                                                                   \
     __builtin_amdgcn_sched_barrier(0);                                                                \
-    if (put) HSD_G8_STORE(st, ((kt) + 1) & 1, 2, 4)                                                   \
+    if (PUT) HSD_G8_STORE(st, ((kt) + 1) & 1, 2, 4)                                                   \
     HSD_G8_KSTEP(3)                                                                                   \
     __syncthreads();                                                                                  \
   }
 
+#ifdef HSD_GEMM_TRACE
+  const long long tr0 = clock64();
+#endif
   HSD_G8_LOAD(0, 0, 0) HSD_G8_LOAD(0, 1, 0) HSD_G8_LOAD(0, 2, 0) HSD_G8_LOAD(0, 3, 0)
-  if (nk > 1) {
-    HSD_G8_LOAD(1, 0, BK * 2) HSD_G8_LOAD(1, 1, BK * 2) HSD_G8_LOAD(1, 2, BK * 2) HSD_G8_LOAD(1, 3, BK * 2)
-  }
+  HSD_G8_LOAD(1, 0, BK * 2) HSD_G8_LOAD(1, 1, BK * 2) HSD_G8_LOAD(1, 2, BK * 2) HSD_G8_LOAD(1, 3, BK * 2)
   HSD_G8_STORE(0, 0, 0, 4)
   __syncthreads();
   // slice kt+1 lives in set (kt+1) & 1; requests for slice kt+2 reuse set kt & 1 (stored one iteration ago)
+#ifdef HSD_GEMM_TRACE
+  const long long tr1 = clock64();
+#endif
+  // the host only launches this kernel with an even number (>= 4) of K slices: full iterations in pairs, then
+  // the fixed two-iteration tail (keeping the control flow this simple keeps the kernel free of register spills)
   int kt = 0;
-  for (; kt + 1 < nk; kt += 2) {
-    HSD_G8_ITER(kt, 0, 1)
-    HSD_G8_ITER(kt + 1, 1, 0)
+  for (; kt + 3 < nk; kt += 2) {
+    HSD_G8_ITER(kt, 0, 1, true, true)
+    HSD_G8_ITER(kt + 1, 1, 0, true, true)
   }
-  if (kt < nk) HSD_G8_ITER(kt, 0, 1)
+  HSD_G8_ITER(kt, 0, 1, false, true)
+  HSD_G8_ITER(kt + 1, 1, 0, false, false)
+#ifdef HSD_GEMM_TRACE
+  const long long tr2 = clock64();
+#endif
 #undef HSD_G8_LOAD
 #undef HSD_G8_STORE
 #undef HSD_G8_KSTEP
 #undef HSD_G8_ITER
 
-  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(-1, M));
+  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(-1, M),
+                           reinterpret_cast<float *>(smem_raw));
+#ifdef HSD_GEMM_TRACE
+  if ((blockIdx.x % 37) == 0 && t == 0 && MODE == kModeDual) {
+    __builtin_amdgcn_s_waitcnt(0);
+    const long long tr3 = clock64();
+    printf("g8 trace wg=%d tile=(%d,%d) prologue=%lld loop=%lld epi_issue=%lld start=%lld\n", (int)blockIdx.x, m0, n0, tr1 - tr0,
+           tr2 - tr1, tr3 - tr2, tr0);
+  }
+#endif
 }
 
 }  // namespace hsd

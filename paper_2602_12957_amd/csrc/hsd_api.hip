@@ -30,6 +30,7 @@ struct hsd_ctx {
   std::vector<const void *> wqkv, wo, w_gate_up, w_down;
   int n_cu;
   bool force_simple;  // HSD_FORCE_SIMPLE=1: run the plain kernels also for bf16 (cross-check of the MFMA path)
+  int k_chunks[2] = {0, 0};  // experiment override of the O / down K chunking (0 = default)
   int64_t split_rows; // largest row count for which the O / down projections run as split-K
   int gemm_cfg[5];    // tile configuration of the MFMA GEMM per call site (qkv, o, gate_up, down, lm_head)
   // per-kernel timing (hsd_profile_*)
@@ -46,7 +47,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Workspace {
   float *x;
   void *h, *q, *a, *u;
-  int32_t *row_seq, *row_pos, *dump_slot, *tile_cu;
+  int32_t *row_seq, *row_pos, *row_kv, *dump_slot, *tile_cu;
   float2 *rope_cs;
   Top2 *lm_part;
   float *part;  // split-K partial sums of the O / down projections
@@ -59,7 +60,10 @@ inline int64_t split_row_limit(const hsd_model_desc &d) {
   const int64_t tiles_n = d.d_model / 128;
   return (512 / tiles_n) * 128;
 }
-constexpr int kChunksO = 2, kChunksDown = 4;  // fixed per projection: the K-reduction order never depends on the batch
+// K chunking per projection, fixed: the K-reduction order never depends on the batch.  The O projection (K = 1024)
+// runs unsplit; the down projection (K = 4096) in two chunks.  kMaxChunks bounds the HSD_KCHUNKS experiment override
+// and sizes the partial-sum buffer.
+constexpr int kChunksO = 1, kChunksDown = 2, kMaxChunks = 4;
 
 // Carves the workspace; with base == nullptr only the size is computed.
 Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
@@ -79,12 +83,13 @@ Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
   w.u = take(T * d.d_ffn * es);
   w.row_seq = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.row_pos = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
+  w.row_kv = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.dump_slot = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.tile_cu = reinterpret_cast<int32_t *>(take((n_seq + 1) * sizeof(int32_t)));
   w.rope_cs = reinterpret_cast<float2 *>(take(T * 32 * sizeof(float2)));
   w.lm_part = reinterpret_cast<Top2 *>(take(T * (d.vocab / 64) * sizeof(Top2)));
   const int64_t part_rows = T < split_row_limit(d) ? T : split_row_limit(d);
-  w.part = reinterpret_cast<float *>(take(d.dtype == HSD_BF16 ? kChunksDown * part_rows * d.d_model * sizeof(float) : 0));
+  w.part = reinterpret_cast<float *>(take(d.dtype == HSD_BF16 ? kMaxChunks * part_rows * d.d_model * sizeof(float) : 0));
   w.total = off;
   return w;
 }
@@ -197,7 +202,7 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
         case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi, k_chunks, split);
         case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi, k_chunks, split);
         case 8:
-          if (k_chunks == 1) return launch_gemm_mfma8(st, M, N, K, A, W, epi);
+          if (k_chunks == 1 && K % 128 == 0 && K >= 256) return launch_gemm_mfma8(st, M, N, K, A, W, epi);
           [[fallthrough]];
         default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi, k_chunks, split);
       }
@@ -281,11 +286,14 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
                      b->seq_len, b->block_table, b->max_blocks_per_seq, pool->n_blocks, pool->free_list,
                      pool->free_count, b->status);
   HSD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_row_kv, dim3((Tq + 255) / 256), dim3(256), 0, st, Tq, ws.row_seq, ws.row_pos, b->block_table,
+                     b->max_blocks_per_seq, pool->n_blocks, ws.row_kv);
+  HSD_LAUNCH_CHECK();
   hipLaunchKernelGGL((k_embed<T>), dim3(Tq), dim3(256), 0, st, d.d_model, d.vocab, b->tokens, b->embeds,
                      static_cast<const T *>(ctx->tok_embed), ws.x);
   HSD_LAUNCH_CHECK();
 
-  RowMeta meta{ws.row_seq, ws.row_pos, ws.rope_cs};
+  RowMeta meta{ws.row_seq, ws.row_pos, ws.rope_cs, ws.row_kv};
   const bool mfma_path = std::is_same<T, bf16>::value && !ctx->force_simple;
   auto chunks_for = [&](int want, int K) { return (mfma_path && K % (want * 64) == 0) ? want : 1; };
   const bool split_ok = mfma_path && Tq <= ctx->split_rows;
@@ -327,14 +335,15 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
       ProfScope ps(ctx, st, HSD_PROF_ATTENTION);
       if ((rc = launch_attention<T>(ctx, st, b, meta, kv, ws, page_mode))) return rc;
     }
-    if ((rc = residual_proj(kSiteO, HSD_PROF_GEMM_O, ws.a, ctx->wo[l], qdim, kChunksO, &pending))) return rc;
+    if ((rc = residual_proj(kSiteO, HSD_PROF_GEMM_O, ws.a, ctx->wo[l], qdim, ctx->k_chunks[0] ? ctx->k_chunks[0] : kChunksO, &pending))) return rc;
     if ((rc = norm(ctx->ffn_norm[l], pending))) return rc;
     EpiSwiGLU<T> es{static_cast<T *>(ws.u), d.d_ffn};
     {
       ProfScope ps(ctx, st, HSD_PROF_GEMM_GATE_UP);
       if ((rc = launch_gemm<T>(ctx, st, kSiteGateUp, Tq, d.d_ffn, d.d_model, ws.h, ctx->w_gate_up[l], es))) return rc;
     }
-    if ((rc = residual_proj(kSiteDown, HSD_PROF_GEMM_DOWN, ws.u, ctx->w_down[l], d.d_ffn, kChunksDown, &pending)))
+    if ((rc = residual_proj(kSiteDown, HSD_PROF_GEMM_DOWN, ws.u, ctx->w_down[l], d.d_ffn,
+                            ctx->k_chunks[1] ? ctx->k_chunks[1] : kChunksDown, &pending)))
       return rc;
     // the norm that follows: next layer's attention norm, or the final norm before the LM head (none for prefill)
     const float *next_gain = (l + 1 < d.n_layers) ? ctx->attn_norm[l + 1] : (with_head ? ctx->final_norm : nullptr);
@@ -489,6 +498,12 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   if (const char *sr = std::getenv("HSD_SPLIT_ROWS")) {
     const int64_t v = std::atoll(sr);
     if (v >= 0 && v < c->split_rows) c->split_rows = v;
+  }
+  if (const char *kc = std::getenv("HSD_KCHUNKS")) {  // "o,down" (experiments)
+    int v[2] = {0, 0};
+    std::sscanf(kc, "%d,%d", &v[0], &v[1]);
+    for (int i = 0; i < 2; ++i)
+      if (v[i] >= 1 && v[i] <= kMaxChunks) c->k_chunks[i] = v[i];
   }
   // HSD_GEMM_CFG="q,o,g,d,l" (or one number for all) overrides the per-site tile configuration (experiments)
   // 256x256 8-wave tiles for the wide projections (gate/up, LM head), 64x128 tiles for QKV and O (more workgroups),

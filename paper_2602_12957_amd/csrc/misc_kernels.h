@@ -38,6 +38,22 @@ __global__ void k_row_meta(int n_seq, int total_q, const int32_t *__restrict__ c
   rope_cs[static_cast<size_t>(r) * 32 + i] = make_float2(static_cast<float>(cs), static_cast<float>(sn));
 }
 
+// Where each packed row's key and value land in the paged pools: 16 * block id + slot within the block, or -1
+// when the table holds no valid block for the row's position (reservation failed).  Block ids are the same in
+// every layer, so the projection epilogues of all layers read this one array instead of walking
+// row -> sequence -> table themselves.  Runs after the reservation kernel.
+// grid: ceil(T / 256) blocks of 256 threads
+__global__ void k_row_kv(int total_q, const int32_t *__restrict__ row_seq, const int32_t *__restrict__ row_pos,
+                         const int32_t *__restrict__ block_table, int max_blocks_per_seq, int n_blocks,
+                         int32_t *__restrict__ row_kv) {
+  int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= total_q) return;
+  const int pos = row_pos[r], bi = pos / kBlk;
+  int b = -1;
+  if (bi < max_blocks_per_seq) b = block_table[static_cast<size_t>(row_seq[r]) * max_blocks_per_seq + bi];
+  row_kv[r] = (b >= 0 && b < n_blocks) ? b * kBlk + pos % kBlk : -1;
+}
+
 // dump_slot[r] = index into logits_dump for row r, or -1.  Two launches: fill -1, then scatter.
 __global__ void k_fill_i32(int32_t *p, int n, int32_t v) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;

@@ -111,8 +111,16 @@ def _run_config(cfg, mode, max_rounds=None):
             stats["rows"] += int(hi - lo)
             stats["gated_rows"] += int((~ok).sum())
             stats["seq_rounds"] += 1
-            if ok[: rec["alpha"] + 1].all():
-                assert (g_alpha[j], g_bonus[j]) == (rec["alpha"], rec["bonus"]), f"round {r} seq {i}"
+            # acceptance is the closed form of the GPU's own arg-max rows (Eq. 15): leading matches, then the bonus
+            draft_blk = blocks[j][1:]
+            neq = np.nonzero(g_argmax[lo:hi - 1] != draft_blk)[0]
+            a_closed = int(neq[0]) if len(neq) else len(draft_blk)
+            assert (g_alpha[j], g_bonus[j]) == (a_closed, g_argmax[lo + a_closed]), f"round {r} seq {i}: closed form"
+            # ... and equals the oracle's decision unless a row up to the oracle's stopping row is ambiguous
+            # (margin under the gate) AND the GPU really chose the other near-maximal token there
+            a = rec["alpha"]
+            if ok[: a + 1].all() or (g_argmax[lo:lo + a + 1] == u_hat[: a + 1]).all():
+                assert (g_alpha[j], g_bonus[j]) == (a, rec["bonus"]), f"round {r} seq {i}"
             else:
                 stats["gated_rounds"] += 1
             stats["accepted"] += rec["alpha"]
