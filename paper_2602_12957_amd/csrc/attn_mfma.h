@@ -24,10 +24,16 @@
 
 namespace hsd {
 
-constexpr int kAttnKeys = 64;             // keys per LDS tile (4 pages)
 constexpr int kKsStride = kHd + 8;        // bf16 per K row in LDS (16 B pad: conflict-free 128-bit reads)
 constexpr int kVtStride = kBlk + 8;       // bf16 per (page, dim) row of V^T in LDS (48 B)
-constexpr int kAttnStage = kAttnKeys * kKsStride + 4 * kHd * kVtStride;  // bf16 elements per stage
+// One LDS stage holds a tile of 32*KQ keys (2*KQ pages): K rows, then V^T rows.  bf16 elements per stage:
+constexpr int attn_stage_elems(int kq) { return 32 * kq * kKsStride + 2 * kq * kHd * kVtStride; }
+// Dynamic LDS of k_attn_mfma<., KQ>: two stages, reused after the key loop for the merge of the KQ - 1 partial
+// results of each of the QS query sets (34 floats per lane).
+constexpr size_t attn_smem_bytes(int kq, int qs) {
+  const size_t stages = 2 * static_cast<size_t>(attn_stage_elems(kq)) * 2, merge = static_cast<size_t>(kq - 1) * qs * 34 * 64 * 4;
+  return stages > merge ? stages : merge;
+}
 
 // tile_cu[s] = number of query tiles of sequences < s, with q_tile rows per tile.  One block of 1024 threads.
 __global__ void __launch_bounds__(1024) k_attn_tiles(int n_seq, const int32_t *__restrict__ cu_q, int q_tile,
@@ -47,20 +53,26 @@ union Frag8 {
   uint16_t h[8];
 };
 
-// G4 = query heads of one kv head handled per workgroup (1, 2 or 4); 4/G4 row sub-tiles of 32 queries.
-// The workgroup has 8 waves: waves w and w+4 own the same 32 queries and split every 64-key tile between them
-// (keys 0-31 / 32-63), which doubles the waves in flight per query tile; their partial (max, sum, O^T) are merged
-// through LDS at the end, always in the same order, so results do not depend on timing.
-// grid: (upper bound of query tiles, n_kv_heads * ceil(group / G4)), block 512, dynamic LDS 2 * kAttnStage * 2 B.
-template <int G4>
-__global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, const int32_t *__restrict__ cu_q,
+// QS = query sets (waves' worth of 32 queries x one head) per workgroup: 1, 2 or 4.
+// G4 = query heads of one kv head among them (1, 2 or 4, G4 <= QS); QS/G4 row sub-tiles of 32 queries.
+// KQ = key parts per tile (2 or 4).  The workgroup has QS*KQ waves: waves w, w+QS, ... own the same 32 queries
+// and split every tile of 32*KQ keys between them (32 keys each), which multiplies the waves in flight per query
+// tile and divides the number of sequential tile steps; their partial (max, sum, O^T) are merged through LDS at
+// the end, always in the same order, so results do not depend on timing.  Fewer query sets per workgroup mean
+// more, smaller workgroups (finer load balance over the CUs) at the price of staging each K/V tile more often.
+// grid: (upper bound of query tiles, n_kv_heads * ceil(group / G4)), block 64*QS*KQ, dynamic LDS
+// attn_smem_bytes(KQ, QS).
+template <int G4, int KQ, int QS>
+__global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_heads, const int32_t *__restrict__ cu_q,
                                                    const int32_t *__restrict__ seq_slot, int n_slots,
                                                    const int32_t *__restrict__ seq_len,
                                                    const int32_t *__restrict__ tile_cu, PagedKV kv,
                                                    const bf16 *__restrict__ q, bf16 *__restrict__ out) {
+  constexpr int kAttnKeys = 32 * KQ, kAttnStage = attn_stage_elems(KQ);
+  constexpr int NT = 64 * QS * KQ, NS = 4 / QS;   // threads; 16-byte K (and V) pieces staged per thread and tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   uint16_t *smem = reinterpret_cast<uint16_t *>(smem_raw);
-  constexpr int SUB = 4 / G4, QT = 32 * SUB;
+  constexpr int SUB = QS / G4, QT = 32 * SUB;
 
   const int tile = blockIdx.x;
   if (tile >= tile_cu[n_seq]) return;  // uniform for the whole workgroup
@@ -76,7 +88,7 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
   const int group = n_q_heads / kv.n_kv_heads, hb = (group + G4 - 1) / G4;
   const int kvh = blockIdx.y / hb, hgrp = blockIdx.y % hb;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5, qj = lane & 31;
-  const int wq = wave & 3, kh = wave >> 2;                         // query-set index, key half of each tile
+  const int wq = wave % QS, kh = wave / QS;                        // query-set index, key part of each tile
   const int head = kvh * group + hgrp * G4 + (wq % G4);
   const int row0 = tile_in_seq * QT + (wq / G4) * 32;              // first query row (within the block) of this wave
   const bool wave_active = row0 < Lq;
@@ -98,50 +110,62 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
 
   const bf16 *kpool = static_cast<const bf16 *>(kv.k_pool);
   const bf16 *vpool = static_cast<const bf16 *>(kv.v_pool);
-  // Staging: thread t moves one 16-byte piece of K (key t/8, piece t%8) and one of V^T (page t/128, dim
-  // (t%128)/2, half row t%2) per tile; both lie in page t/128 of the tile.  Page ids are fetched one tile ahead
+  // Staging: piece c = t + NT*i (i < NS) is one 16-byte piece of K (key c/8, piece c%8) and one of V^T (page
+  // c/128, dim (c%128)/2, half row c%2); both lie in page c/128 of the tile.  Page ids are fetched one tile ahead
   // of the data they address, so the K/V loads of the next tile never wait behind a dependent block-table read.
-  const int key = t >> 3, ch = t & 7, pg = t >> 7, vd = (t & 127) >> 1, hf = t & 1;
-  uint4 rk, rv;
-  int bid;
-  // fetch_id only ISSUES the block-table read (the index is range-checked, the value is not looked at until the
+  u32x4 rk[NS], rv[NS];
+  int bid[NS];
+  // fetch_id only ISSUES the block-table reads (the index is range-checked, the value is not looked at until the
   // next iteration): examining the id here would stall the wave for a full memory latency every iteration
   auto fetch_id = [&](int kt) {
-    const int p0 = kt * kAttnKeys + pg * kBlk;
-    const int bi = p0 / kBlk;
-    bid = -1;
-    if (p0 < n_valid && bi < kv.max_blocks_per_seq)
-      bid = kv.block_table[static_cast<size_t>(slot) * kv.max_blocks_per_seq + bi];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      const int p0 = kt * kAttnKeys + ((t + NT * i) >> 7) * kBlk;
+      const int bi = p0 / kBlk;
+      bid[i] = -1;
+      if (p0 < n_valid && bi < kv.max_blocks_per_seq)
+        bid[i] = kv.block_table[static_cast<size_t>(slot) * kv.max_blocks_per_seq + bi];
+    }
   };
   // prefetch only ISSUES the loads; nothing here may depend on the loaded values, or the wave would wait for
   // them on the spot and the whole point of requesting a tile ahead would be lost
-  auto prefetch = [&](int kt) {
-    (void)kt;
+  auto prefetch = [&]() {
     // unconditional loads: a page id that is absent (-1, beyond the data of this round) or out of range reads
     // block 0 instead; such a page lies wholly past n_valid, so store_lds zeroes its V and the causal mask
     // discards its scores.  A branch here would make the compiler wait for the loads inside it.
-    const int b = (bid >= 0 && bid < kv.n_blocks) ? bid : 0;
-    const size_t off = kv_block_offset(kv, b, kvh);
-    rk = *reinterpret_cast<const uint4 *>(kpool + off + (key & 15) * kHd + ch * 8);
-    rv = *reinterpret_cast<const uint4 *>(vpool + off + vd * kBlk + hf * 8);
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      const int c = t + NT * i;
+      const int b = (bid[i] >= 0 && bid[i] < kv.n_blocks) ? bid[i] : 0;
+      const size_t off = kv_block_offset(kv, b, kvh);
+      rk[i] = *reinterpret_cast<const u32x4 *>(kpool + off + ((c >> 3) & 15) * kHd + (c & 7) * 8);
+      rv[i] = *reinterpret_cast<const u32x4 *>(vpool + off + ((c & 127) >> 1) * kBlk + (c & 1) * 8);
+    }
   };
   // kt = tile the staged registers belong to
   auto store_lds = [&](int stage, int kt) {
     uint16_t *ks = smem + stage * kAttnStage, *vt = ks + kAttnKeys * kKsStride;
-    *reinterpret_cast<uint4 *>(ks + key * kKsStride + ch * 8) = rk;
-    Frag8 f;
-    f.u = rv;
-    const int p0 = kt * kAttnKeys + pg * kBlk;
-    if (p0 + kBlk > n_valid) {
-      // last, partly filled page: slots of positions that hold no data of this sequence must read as 0
-      // (their probability is 0, but 0 * stale-NaN would poison the product)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        int tok = (e < 4) ? 4 * hf + e : 8 + 4 * hf + (e - 4);
-        if (p0 + tok >= n_valid) f.h[e] = 0;
+    for (int i = 0; i < NS; ++i) {
+      const int c = t + NT * i, pg = c >> 7, vd = (c & 127) >> 1, hf = c & 1;
+      *reinterpret_cast<u32x4 *>(ks + (c >> 3) * kKsStride + (c & 7) * 8) = rk[i];
+      u32x4 f = rv[i];
+      const int p0 = kt * kAttnKeys + pg * kBlk;
+      if (p0 + kBlk > n_valid) {
+        // last, partly filled page: slots of positions that hold no data of this sequence must read as 0
+        // (their probability is 0, but 0 * stale-NaN would poison the product).  Element e of the piece is
+        // token 4*hf + e (e < 4) or 8 + 4*hf + e - 4; two elements per 32-bit word.
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const int tok0 = (w < 2) ? 4 * hf + 2 * w : 8 + 4 * hf + 2 * (w - 2);
+          uint32_t keep = 0;
+          if (p0 + tok0 < n_valid) keep |= 0x0000ffffu;
+          if (p0 + tok0 + 1 < n_valid) keep |= 0xffff0000u;
+          f[w] &= keep;
+        }
       }
+      *reinterpret_cast<u32x4 *>(vt + (pg * kHd + vd) * kVtStride + hf * 8) = f;
     }
-    *reinterpret_cast<uint4 *>(vt + (pg * kHd + vd) * kVtStride + hf * 8) = f.u;
   };
 
   floatx16 o[2];
@@ -153,13 +177,13 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
   const float sc = 0.125f * 1.4426950408889634f;  // 1/sqrt(64) * log2(e): softmax in base 2
 
   fetch_id(0);
-  prefetch(0);
+  prefetch();
   if (n_tiles > 1) fetch_id(1);
   store_lds(0, 0);
   __syncthreads();
   for (int kt = 0; kt < n_tiles; ++kt) {
     if (kt + 1 < n_tiles) {
-      prefetch(kt + 1);
+      prefetch();
       if (kt + 2 < n_tiles) fetch_id(kt + 2);
     }
     const int kb = kt * kAttnKeys + kh * 32;   // first key of this wave's half tile
@@ -232,11 +256,12 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
     __syncthreads();
   }
 
-  // ---- merge the two key halves of each query set through LDS (stage memory is free after the last barrier)
-  float *mrg = reinterpret_cast<float *>(smem_raw);   // [4 query sets][34][64 lanes]
+  // ---- merge the KQ key parts of each query set through LDS (stage memory is free after the last barrier):
+  // part 0 folds in parts 1, 2, ... in that order
+  float *mrg = reinterpret_cast<float *>(smem_raw);   // [KQ - 1][QS query sets][34][64 lanes]
   l_run += __shfl_xor(l_run, 32, kWave);
-  if (kh == 1) {
-    float *dst = mrg + wq * 34 * 64 + lane;
+  if (kh > 0) {
+    float *dst = mrg + ((kh - 1) * QS + wq) * 34 * 64 + lane;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -246,12 +271,21 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
   }
   __syncthreads();
   if (kh == 0 && wave_active && row0 + qj < Lq) {
-    const float *src = mrg + wq * 34 * 64 + lane;
-    const float m_b = src[32 * 64], l_b = src[33 * 64];
-    const float m_tot = fmaxf(m_run, m_b);            // finite: key 0 belongs to half 0 of the first tile
-    const float ca = ldexpf(1.0f, static_cast<int>(m_run - m_tot));   // integer exponents: exact powers of two
-    const float cb = (m_b > -INFINITY) ? ldexpf(1.0f, static_cast<int>(m_b - m_tot)) : 0.f;
-    const float inv = 1.0f / (l_run * ca + l_b * cb);
+#pragma unroll
+    for (int part = 1; part < KQ; ++part) {
+      const float *src = mrg + ((part - 1) * QS + wq) * 34 * 64 + lane;
+      const float m_b = src[32 * 64], l_b = src[33 * 64];
+      const float m_tot = fmaxf(m_run, m_b);            // finite: key 0 belongs to part 0 of the first tile
+      const float ca = ldexpf(1.0f, static_cast<int>(m_run - m_tot));   // integer exponents: exact powers of two
+      const float cb = (m_b > -INFINITY) ? ldexpf(1.0f, static_cast<int>(m_b - m_tot)) : 0.f;
+      l_run = l_run * ca + l_b * cb;
+      m_run = m_tot;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[i][v] = o[i][v] * ca + src[(i * 16 + v) * 64] * cb;
+    }
+    const float inv = 1.0f / l_run;
     bf16 *op = out + static_cast<size_t>(base + row0 + qj) * qdim + head * kHd;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -259,7 +293,7 @@ __global__ void __launch_bounds__(512) k_attn_mfma(int n_seq, int n_q_heads, con
       for (int g = 0; g < 4; ++g) {
         floatx4 ov;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) ov[e] = (o[i][4 * g + e] * ca + src[(i * 16 + 4 * g + e) * 64] * cb) * inv;
+        for (int e = 0; e < 4; ++e) ov[e] = o[i][4 * g + e] * inv;
         *reinterpret_cast<bf16x4 *>(op + i * 32 + 8 * g + 4 * half) = __builtin_convertvector(ov, bf16x4);
       }
   }

@@ -98,16 +98,16 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, const b
       *reinterpret_cast<u32x4 *>(sd + BP * LS + lds_dst + i * 64 * LS) = regQ[set][i];                \
     }                                                                                                 \
   }
-#define HSD_G8_KSTEP(kk)                                                                              \
-  {                                                                                                   \
-    bf16x8 a[TM], b[TN];                                                                              \
-    _Pragma("unroll") for (int i = 0; i < TM; ++i) a[i] =                                             \
-        *reinterpret_cast<const bf16x8 *>(sp + frag_p + i * 32 * LS + (kk) * 16);                     \
-    _Pragma("unroll") for (int j = 0; j < TN; ++j) b[j] =                                             \
-        *reinterpret_cast<const bf16x8 *>(sp + frag_q + j * 32 * LS + (kk) * 16);                     \
-    _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)     \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);           \
-  }
+  // Operand fragments are double buffered in registers: the LDS reads of k-step kk+1 are issued before the MFMAs
+  // of k-step kk, so their latency hides behind the matrix pipe instead of opening every k-step.
+#define HSD_G8_FRAG(buf, kk)                                                                          \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i) fa[buf][i] =                                         \
+      *reinterpret_cast<const bf16x8 *>(sp + frag_p + i * 32 * LS + (kk) * 16);                       \
+  _Pragma("unroll") for (int j = 0; j < TN; ++j) fb[buf][j] =                                         \
+      *reinterpret_cast<const bf16x8 *>(sp + frag_q + j * 32 * LS + (kk) * 16);
+#define HSD_G8_MMA(buf)                                                                               \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)       \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
   // one iteration: multiply slice kt (LDS stage kt & 1); request slice kt+2 into set `ld`; store set `st` (kt+1)
   // REQ / PUT are compile-time so that the compiler can count the loads in flight exactly (a run-time condition
   // around the requests would force a wait for ALL loads before every LDS store)
@@ -115,23 +115,25 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, const b
   {                                                                                                   \
     const uint16_t *sp = smem + ((kt) & 1) * Cfg::kStage;                                             \
     const int kbyte = ((kt) + 2) * BK * 2;                                                            \
+    bf16x8 fa[2][TM], fb[2][TN];                                                                      \
+    HSD_G8_FRAG(0, 0)                                                                                 \
     if (REQ) { HSD_G8_LOAD(ld, 0, kbyte) HSD_G8_LOAD(ld, 1, kbyte) }                                  \
-    HSD_G8_KSTEP(0)                                                                                   \
+    HSD_G8_FRAG(1, 1)                                                                                 \
+    HSD_G8_MMA(0)                                                                                     \
     __builtin_amdgcn_sched_barrier(0);                                                                \
     if (REQ) { HSD_G8_LOAD(ld, 2, kbyte) HSD_G8_LOAD(ld, 3, kbyte) }                                  \
-    HSD_G8_KSTEP(1)                                                                                   \
+    HSD_G8_FRAG(0, 2)                                                                                 \
+    HSD_G8_MMA(1)                                                                                     \
     __builtin_amdgcn_sched_barrier(0);                                                                \
     if (PUT) HSD_G8_STORE(st, ((kt) + 1) & 1, 0, 2)                                                   \
-    HSD_G8_KSTEP(2)                                                                                   \
+    HSD_G8_FRAG(1, 3)                                                                                 \
+    HSD_G8_MMA(0)                                                                                     \
     __builtin_amdgcn_sched_barrier(0);                                                                \
     if (PUT) HSD_G8_STORE(st, ((kt) + 1) & 1, 2, 4)                                                   \
-    HSD_G8_KSTEP(3)                                                                                   \
+    HSD_G8_MMA(1)                                                                                     \
     __syncthreads();                                                                                  \
   }
 
-#ifdef HSD_GEMM_TRACE
-  const long long tr0 = clock64();
-#endif
   HSD_G8_LOAD(0, 0, 0) HSD_G8_LOAD(0, 1, 0) HSD_G8_LOAD(0, 2, 0) HSD_G8_LOAD(0, 3, 0)
   HSD_G8_LOAD(1, 0, BK * 2) HSD_G8_LOAD(1, 1, BK * 2) HSD_G8_LOAD(1, 2, BK * 2) HSD_G8_LOAD(1, 3, BK * 2)
   HSD_G8_STORE(0, 0, 0, 4)
@@ -154,7 +156,8 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, const b
 #endif
 #undef HSD_G8_LOAD
 #undef HSD_G8_STORE
-#undef HSD_G8_KSTEP
+#undef HSD_G8_FRAG
+#undef HSD_G8_MMA
 #undef HSD_G8_ITER
 
   gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(-1, M),

@@ -30,6 +30,7 @@ struct hsd_ctx {
   std::vector<const void *> wqkv, wo, w_gate_up, w_down;
   int n_cu;
   bool force_simple;  // HSD_FORCE_SIMPLE=1: run the plain kernels also for bf16 (cross-check of the MFMA path)
+  int attn_cfg[2] = {4, 2};  // attention work split for GQA groups of 4: query sets (= heads) per workgroup, key parts
   int k_chunks[2] = {0, 0};  // experiment override of the O / down K chunking (0 = default)
   int64_t split_rows; // largest row count for which the O / down projections run as split-K
   int gemm_cfg[5];    // tile configuration of the MFMA GEMM per call site (qkv, o, gate_up, down, lm_head)
@@ -240,8 +241,15 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
   const int group = d.n_q_heads / d.n_kv_heads;
   if constexpr (std::is_same<T, bf16>::value) {
     if (!ctx->force_simple && (group == 1 || group == 2 || group % 4 == 0)) {
-      const int g4 = group >= 4 ? 4 : group;
-      const int q_tile = 32 * (4 / g4);
+      // Work split, fixed per model (never chosen from the batch, so results stay bitwise batch-invariant):
+      // g4 query heads of a kv head and qs query sets per workgroup, kq key parts per tile.
+      int g4 = group >= 4 ? 4 : group, qs = 4, kq = 2;
+      if (group % 4 == 0) {
+        g4 = ctx->attn_cfg[0];
+        qs = ctx->attn_cfg[0];
+        kq = ctx->attn_cfg[1];
+      }
+      const int q_tile = 32 * (qs / g4);
       const int max_tiles = b->total_q / q_tile + b->n_seq;
       const dim3 grid(max_tiles, d.n_kv_heads * ((group + g4 - 1) / g4));
       const bf16 *q = static_cast<const bf16 *>(ws.q);
@@ -250,16 +258,28 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
         hipLaunchKernelGGL(k_attn_tiles, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, q_tile, ws.tile_cu);
         HSD_LAUNCH_CHECK();
       }
-      const size_t smem = 2 * kAttnStage * sizeof(uint16_t);
-      if (g4 == 4)
-        hipLaunchKernelGGL((k_attn_mfma<4>), grid, dim3(512), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
-                           b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);
-      else if (g4 == 2)
-        hipLaunchKernelGGL((k_attn_mfma<2>), grid, dim3(512), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
-                           b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);
-      else
-        hipLaunchKernelGGL((k_attn_mfma<1>), grid, dim3(512), smem, st, b->n_seq, d.n_q_heads, b->cu_q, b->seq_slot,
-                           b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);
+#define HSD_ATTN_LAUNCH(G4, KQ, QS)                                                                              \
+  {                                                                                                              \
+    constexpr size_t smem = attn_smem_bytes(KQ, QS);                                                             \
+    static bool attr_done = false;                                                                               \
+    if (!attr_done) {                                                                                            \
+      if (smem > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void *>(k_attn_mfma<G4, KQ, QS>),       \
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) \
+        return HSD_EHIP;                                                                                         \
+      attr_done = true;                                                                                          \
+    }                                                                                                            \
+    hipLaunchKernelGGL((k_attn_mfma<G4, KQ, QS>), grid, dim3(64 * QS * KQ), smem, st, b->n_seq, d.n_q_heads,     \
+                       b->cu_q, b->seq_slot, b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);                      \
+  }
+      if (g4 == 4 && kq == 4) HSD_ATTN_LAUNCH(4, 4, 4)
+      else if (g4 == 4) HSD_ATTN_LAUNCH(4, 2, 4)
+      else if (g4 == 2 && qs == 2 && kq == 4) HSD_ATTN_LAUNCH(2, 4, 2)
+      else if (g4 == 2 && qs == 2) HSD_ATTN_LAUNCH(2, 2, 2)
+      else if (g4 == 1 && qs == 1 && kq == 4) HSD_ATTN_LAUNCH(1, 4, 1)
+      else if (g4 == 1 && qs == 1) HSD_ATTN_LAUNCH(1, 2, 1)
+      else if (g4 == 2) HSD_ATTN_LAUNCH(2, 2, 4)
+      else HSD_ATTN_LAUNCH(1, 2, 4)
+#undef HSD_ATTN_LAUNCH
       HSD_LAUNCH_CHECK();
       return HSD_OK;
     }
@@ -498,6 +518,11 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   if (const char *sr = std::getenv("HSD_SPLIT_ROWS")) {
     const int64_t v = std::atoll(sr);
     if (v >= 0 && v < c->split_rows) c->split_rows = v;
+  }
+  if (const char *ac = std::getenv("HSD_ATTN_CFG")) {  // "query sets,key parts" (experiments)
+    int v[2] = {0, 0};
+    std::sscanf(ac, "%d,%d", &v[0], &v[1]);
+    if ((v[0] == 1 || v[0] == 2 || v[0] == 4) && (v[1] == 2 || v[1] == 4)) c->attn_cfg[0] = v[0], c->attn_cfg[1] = v[1];
   }
   if (const char *kc = std::getenv("HSD_KCHUNKS")) {  // "o,down" (experiments)
     int v[2] = {0, 0};

@@ -92,33 +92,58 @@ __global__ void k_embed(int d, int vocab, const int32_t *__restrict__ tokens, co
 
 // ------------------------------------------------------------------------------------------------
 // RMSNorm: h[r,:] = x[r,:] * rsqrt(mean(x^2) + eps) * gain, fp32 math, output in the GEMM operand type.
-// One wave per row, 4 rows per 256-thread block; d is a multiple of 128 so every lane reads float4s.
+// One wave per row, 4 rows per 256-thread block; d is a multiple of 128 so every lane reads float4s.  The
+// first kNormCache float4 of a lane (rows up to 2048 wide) stay in registers between the two passes.
+// Both norm kernels share the helpers below, so they round identically.
 // ------------------------------------------------------------------------------------------------
+constexpr int kNormCache = 8;
+
+__device__ __forceinline__ float sumsq4(const floatx4 &v) { return v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3]; }
+
+__device__ __forceinline__ void norm_store4(float *dst, const floatx4 &v, float rstd, const floatx4 &g) {
+  floatx4 o = {v[0] * rstd * g[0], v[1] * rstd * g[1], v[2] * rstd * g[2], v[3] * rstd * g[3]};
+  *reinterpret_cast<floatx4 *>(dst) = o;
+}
+__device__ __forceinline__ void norm_store4(bf16 *dst, const floatx4 &v, float rstd, const floatx4 &g) {
+  floatx4 o = {v[0] * rstd * g[0], v[1] * rstd * g[1], v[2] * rstd * g[2], v[3] * rstd * g[3]};
+  *reinterpret_cast<bf16x4 *>(dst) = __builtin_convertvector(o, bf16x4);   // round-to-nearest-even, 8-byte store
+}
+
+// second pass of both kernels: scale the row (cached part from registers, the rest re-read) and store it
+template <typename T>
+__device__ __forceinline__ void norm_write_row(const floatx4 *xr, const floatx4 (&cache)[kNormCache], int n4, int lane,
+                                               float ss, int d, float eps, const float *gain, T *hr) {
+  ss = wave_sum(ss);
+  const float rstd = 1.0f / sqrtf(ss / static_cast<float>(d) + eps);
+  const floatx4 *g4 = reinterpret_cast<const floatx4 *>(gain);
+#pragma unroll
+  for (int i = 0; i < kNormCache; ++i) {
+    const int c = lane + kWave * i;
+    if (c < n4) norm_store4(hr + 4 * c, cache[i], rstd, g4[c]);
+  }
+  for (int c = lane + kWave * kNormCache; c < n4; c += kWave) norm_store4(hr + 4 * c, xr[c], rstd, g4[c]);
+}
+
 template <typename T>
 __global__ void k_rmsnorm(int n_rows, int d, float eps, const float *__restrict__ x, const float *__restrict__ gain,
                           T *__restrict__ h) {
-  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int r = blockIdx.x * 4 + wave;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + wave;
   if (r >= n_rows) return;
-  const float4 *xr = reinterpret_cast<const float4 *>(x + static_cast<size_t>(r) * d);
-  const float4 *g4 = reinterpret_cast<const float4 *>(gain);
-  int n4 = d >> 2;
+  const floatx4 *xr = reinterpret_cast<const floatx4 *>(x + static_cast<size_t>(r) * d);
+  const int n4 = d >> 2;
+  floatx4 cache[kNormCache];
   float ss = 0.f;
-  for (int c = lane; c < n4; c += kWave) {
-    float4 v = xr[c];
-    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+#pragma unroll
+  for (int i = 0; i < kNormCache; ++i) {
+    const int c = lane + kWave * i;
+    if (c < n4) {
+      cache[i] = xr[c];
+      ss += sumsq4(cache[i]);
+    }
   }
-  ss = wave_sum(ss);
-  float rstd = 1.0f / sqrtf(ss / static_cast<float>(d) + eps);
-  T *hr = h + static_cast<size_t>(r) * d;
-  for (int c = lane; c < n4; c += kWave) {
-    float4 v = xr[c];
-    float4 g = g4[c];
-    hr[4 * c + 0] = from_f32<T>(v.x * rstd * g.x);
-    hr[4 * c + 1] = from_f32<T>(v.y * rstd * g.y);
-    hr[4 * c + 2] = from_f32<T>(v.z * rstd * g.z);
-    hr[4 * c + 3] = from_f32<T>(v.w * rstd * g.w);
-  }
+  for (int c = lane + kWave * kNormCache; c < n4; c += kWave) ss += sumsq4(xr[c]);
+  norm_write_row<T>(xr, cache, n4, lane, ss, d, eps, gain, h + static_cast<size_t>(r) * d);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -130,38 +155,34 @@ __global__ void k_rmsnorm(int n_rows, int d, float eps, const float *__restrict_
 template <typename T>
 __global__ void k_reduce_rmsnorm(int n_rows, int d, float eps, float *__restrict__ x, const float *__restrict__ part,
                                  int n_splits, const float *__restrict__ gain, T *__restrict__ h) {
-  int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int r = blockIdx.x * 4 + wave;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + wave;
   if (r >= n_rows) return;
-  float4 *xr = reinterpret_cast<float4 *>(x + static_cast<size_t>(r) * d);
+  floatx4 *xr = reinterpret_cast<floatx4 *>(x + static_cast<size_t>(r) * d);
   const size_t split_stride = static_cast<size_t>(n_rows) * d / 4;
-  const float4 *pr = reinterpret_cast<const float4 *>(part) + static_cast<size_t>(r) * d / 4;
-  int n4 = d >> 2;
-  float ss = 0.f;
-  for (int c = lane; c < n4; c += kWave) {
-    float4 s = pr[c];
-    for (int k = 1; k < n_splits; ++k) {
-      float4 p = pr[k * split_stride + c];
-      s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
-    }
-    float4 v = xr[c];
-    v.x += s.x; v.y += s.y; v.z += s.z; v.w += s.w;
+  const floatx4 *pr = reinterpret_cast<const floatx4 *>(part) + static_cast<size_t>(r) * d / 4;
+  const int n4 = d >> 2;
+  auto reduce_at = [&](int c) {
+    floatx4 s = pr[c];
+    for (int k = 1; k < n_splits; ++k) s += pr[k * split_stride + c];
+    floatx4 v = xr[c];
+    v += s;
     xr[c] = v;
-    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    return v;
+  };
+  floatx4 cache[kNormCache];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < kNormCache; ++i) {
+    const int c = lane + kWave * i;
+    if (c < n4) {
+      cache[i] = reduce_at(c);
+      ss += sumsq4(cache[i]);
+    }
   }
+  for (int c = lane + kWave * kNormCache; c < n4; c += kWave) ss += sumsq4(reduce_at(c));
   if (gain == nullptr) return;
-  ss = wave_sum(ss);
-  float rstd = 1.0f / sqrtf(ss / static_cast<float>(d) + eps);
-  const float4 *g4 = reinterpret_cast<const float4 *>(gain);
-  T *hr = h + static_cast<size_t>(r) * d;
-  for (int c = lane; c < n4; c += kWave) {
-    float4 v = xr[c];
-    float4 g = g4[c];
-    hr[4 * c + 0] = from_f32<T>(v.x * rstd * g.x);
-    hr[4 * c + 1] = from_f32<T>(v.y * rstd * g.y);
-    hr[4 * c + 2] = from_f32<T>(v.z * rstd * g.z);
-    hr[4 * c + 3] = from_f32<T>(v.w * rstd * g.w);
-  }
+  norm_write_row<T>(xr, cache, n4, lane, ss, d, eps, gain, h + static_cast<size_t>(r) * d);
 }
 
 // ------------------------------------------------------------------------------------------------
