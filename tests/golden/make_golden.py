@@ -12,9 +12,14 @@ For every sequence of a configuration it stores, as JSON:
   * for a few rows of round 1, the logits at a seeded sample of vocabulary columns plus each row's top-8
     (value, index) pairs, for the element-wise logit comparison.
 
-Usage:  python tests/golden/make_golden.py --config 1 [--procs 4] [--max-rounds N]
+Usage:  python tests/golden/make_golden.py --config 1 [--procs 4] [--max-rounds N] [--gzip]
+        python tests/golden/make_golden.py --config 4 --trim cfg4_full.json --max-rounds 16 --gzip
+The second form cuts a file this script wrote earlier down to its first N rounds per sequence (rounds are
+computed one after the other, so the result equals a fresh run with --max-rounds N) without repeating hours of
+CPU work.
 """
 import argparse
+import gzip
 import json
 import os
 import sys
@@ -122,7 +127,21 @@ def main():
     ap.add_argument("--max-rounds", type=int, default=None)
     ap.add_argument("--seqs", type=str, default=None, help="a:b slice of the configuration's sequences")
     ap.add_argument("--out", type=str, default=None)
+    ap.add_argument("--gzip", action="store_true", help="write cfgN.json.gz")
+    ap.add_argument("--trim", type=str, default=None, help="existing output of this script to cut to --max-rounds")
     args = ap.parse_args()
+    here = os.path.dirname(os.path.abspath(__file__))
+    path = args.out or os.path.join(here, f"cfg{args.config}.json" + (".gz" if args.gzip else ""))
+    if args.trim:
+        with (gzip.open if args.trim.endswith(".gz") else open)(args.trim, "rt") as f:
+            out = json.load(f)
+        assert out["config"] == args.config and args.max_rounds
+        for sq in out["sequences"]:
+            if len(sq["rounds"]) > args.max_rounds:
+                sq["rounds"] = sq["rounds"][: args.max_rounds]
+                sq["complete"] = False
+        write_out(out, path)
+        return
     seed = W.SEED_BASE
     desc = W.CONFIGS[args.config].model
     specs = W.draw_sequences(args.config, seed)
@@ -145,10 +164,14 @@ def main():
     out = {"config": args.config, "seed": seed, "oracle_dtype": "float64",
            "oracle_act_dtype": "bf16" if desc.dtype == "bf16" else None, "generator": "tests/golden/make_golden.py",
            "noise_floor": noise, "sequences": seqs}
-    path = args.out or os.path.join(os.path.dirname(os.path.abspath(__file__)), f"cfg{args.config}.json")
-    with open(path, "w") as f:
+    write_out(out, path)
+    print(f"done in {time.time() - t0:.0f}s")
+
+
+def write_out(out, path):
+    with (gzip.open(path, "wt", compresslevel=9) if path.endswith(".gz") else open(path, "w")) as f:
         json.dump(out, f, separators=(",", ":"))
-    print(f"wrote {path} ({os.path.getsize(path) / 1e6:.2f} MB) in {time.time() - t0:.0f}s")
+    print(f"wrote {path} ({os.path.getsize(path) / 1e6:.2f} MB)")
 
 
 if __name__ == "__main__":

