@@ -176,15 +176,26 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = 0.125f * 1.4426950408889634f;  // 1/sqrt(64) * log2(e): softmax in base 2
 
+  // Pipeline: K/V of tile kt+2 and the page ids of tile kt+3 are requested at the top of iteration kt, right after
+  // the staging registers (tile kt+1, requested one whole iteration earlier, so long since arrived) were written to
+  // the LDS stage that iteration kt-1 finished reading.  No wave ever waits for a load it has just issued, and the
+  // LDS stores run ahead of the tile's arithmetic instead of between it and the barrier.
   fetch_id(0);
   prefetch();
   if (n_tiles > 1) fetch_id(1);
   store_lds(0, 0);
+  if (n_tiles > 1) {
+    prefetch();
+    if (n_tiles > 2) fetch_id(2);
+  }
   __syncthreads();
   for (int kt = 0; kt < n_tiles; ++kt) {
     if (kt + 1 < n_tiles) {
-      prefetch();
-      if (kt + 2 < n_tiles) fetch_id(kt + 2);
+      store_lds((kt + 1) & 1, kt + 1);
+      if (kt + 2 < n_tiles) {
+        prefetch();
+        if (kt + 3 < n_tiles) fetch_id(kt + 3);
+      }
     }
     const int kb = kt * kAttnKeys + kh * 32;   // first key of this wave's half tile
     if (wave_active && kb < wave_keys) {
@@ -252,7 +263,6 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
         }
       }
     }
-    if (kt + 1 < n_tiles) store_lds((kt + 1) & 1, kt + 1);
     __syncthreads();
   }
 

@@ -29,6 +29,8 @@ struct hsd_ctx {
   std::vector<const float *> attn_norm, ffn_norm;
   std::vector<const void *> wqkv, wo, w_gate_up, w_down;
   int n_cu;
+  bool sync_layers = false;  // HSD_SYNC_LAYERS=1: wait for the stream after every layer (bounds the launches in flight
+                             // for tools that track each dispatch; never set in timed runs)
   bool force_simple;  // HSD_FORCE_SIMPLE=1: run the plain kernels also for bf16 (cross-check of the MFMA path)
   int attn_cfg[2] = {4, 2};  // attention work split for GQA groups of 4: query sets (= heads) per workgroup, key parts
   int k_chunks[2] = {0, 0};  // experiment override of the O / down K chunking (0 = default)
@@ -187,6 +189,7 @@ using GemmCfg4 = GemmCfg<128, 256, 64, 2, 2>;
 using GemmCfg6 = GemmCfg<256, 128, 64, 4, 2>;   // 8 waves, wave tile 64x64
 using GemmCfg2 = GemmCfg<64, 128, 64, 2, 2>;    // small tiles for narrow projections (more workgroups)
 using GemmCfg3 = GemmCfg<128, 64, 64, 2, 1>;
+using GemmCfg5 = GemmCfg<128, 128, 64, 4, 2>;   // 8 waves, wave tile 32x64
 
 
 template <typename T, typename Epi>
@@ -195,12 +198,13 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
   if constexpr (std::is_same<T, bf16>::value) {
     if (!ctx->force_simple && K % 64 == 0) {
       int cfg = ctx->gemm_cfg[site];
-      if (site == kSiteLM && (cfg == 2 || cfg == 3)) cfg = 0;  // the LM-head partial buffer assumes >= 64 rows per wave
+      if (site == kSiteLM && (cfg == 2 || cfg == 3 || cfg == 5)) cfg = 0;  // the LM-head partial buffer assumes >= 64 rows per wave
       switch (cfg) {
         case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi, k_chunks, split);
         case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi, k_chunks, split);
         case 3: return launch_gemm_mfma<GemmCfg3>(st, M, N, K, A, W, epi, k_chunks, split);
         case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi, k_chunks, split);
+        case 5: return launch_gemm_mfma<GemmCfg5>(st, M, N, K, A, W, epi, k_chunks, split);
         case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi, k_chunks, split);
         case 8:
           if (k_chunks == 1 && K % 128 == 0 && K >= 256) return launch_gemm_mfma8(st, M, N, K, A, W, epi);
@@ -369,6 +373,7 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
     const float *next_gain = (l + 1 < d.n_layers) ? ctx->attn_norm[l + 1] : (with_head ? ctx->final_norm : nullptr);
     if (next_gain != nullptr || pending > 0)
       if ((rc = norm(next_gain, pending))) return rc;
+    if (ctx->sync_layers && hipStreamSynchronize(st) != hipSuccess) return HSD_EHIP;
   }
   if (!with_head) return HSD_OK;
 
@@ -513,6 +518,7 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   c->n_cu = prop.multiProcessorCount;
   const char *fs = std::getenv("HSD_FORCE_SIMPLE");
   c->force_simple = fs != nullptr && fs[0] == '1';
+  if (const char *sl = std::getenv("HSD_SYNC_LAYERS")) c->sync_layers = sl[0] == '1';
   // HSD_SPLIT_ROWS (tests): lower the row count up to which split-K is used, to exercise the chunk-walking GEMM
   c->split_rows = split_row_limit(*desc);
   if (const char *sr = std::getenv("HSD_SPLIT_ROWS")) {
@@ -533,7 +539,7 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   // HSD_GEMM_CFG="q,o,g,d,l" (or one number for all) overrides the per-site tile configuration (experiments)
   // 256x256 8-wave tiles for the wide projections (gate/up, LM head), 64x128 tiles for QKV and O (more workgroups),
   // 128x128 for the split-K down projection
-  const int defaults[5] = {2, 2, 8, 0, 8};
+  const int defaults[5] = {5, 2, 8, 0, 8};
   for (int i = 0; i < 5; ++i) c->gemm_cfg[i] = defaults[i];
   if (const char *gc = std::getenv("HSD_GEMM_CFG")) {
     int vals[5], n = std::sscanf(gc, "%d,%d,%d,%d,%d", &vals[0], &vals[1], &vals[2], &vals[3], &vals[4]);
