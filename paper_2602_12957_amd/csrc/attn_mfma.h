@@ -53,7 +53,7 @@ union Frag8 {
   uint16_t h[8];
 };
 
-// QS = query sets (waves' worth of 32 queries x one head) per workgroup: 1, 2 or 4.
+// QS = query sets (waves' worth of 32 queries x one head) per workgroup: 1, 2, 4 or 8.
 // G4 = query heads of one kv head among them (1, 2 or 4, G4 <= QS); QS/G4 row sub-tiles of 32 queries.
 // KQ = key parts per tile (2 or 4).  The workgroup has QS*KQ waves: waves w, w+QS, ... own the same 32 queries
 // and split every tile of 32*KQ keys between them (32 keys each), which multiplies the waves in flight per query
@@ -69,7 +69,9 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
                                                    const int32_t *__restrict__ tile_cu, PagedKV kv,
                                                    const bf16 *__restrict__ q, bf16 *__restrict__ out) {
   constexpr int kAttnKeys = 32 * KQ, kAttnStage = attn_stage_elems(KQ);
-  constexpr int NT = 64 * QS * KQ, NS = 4 / QS;   // threads; 16-byte K (and V) pieces staged per thread and tile
+  // threads; 16-byte K (and V) pieces staged per thread and tile (with 8 query sets only the first 256*KQ threads stage)
+  constexpr int NT = 64 * QS * KQ, NS = QS >= 4 ? 1 : 4 / QS;
+  const bool stager = QS <= 4 || threadIdx.x < 256 * KQ;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   uint16_t *smem = reinterpret_cast<uint16_t *>(smem_raw);
   constexpr int SUB = QS / G4, QT = 32 * SUB;
@@ -118,6 +120,7 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
   // fetch_id only ISSUES the block-table reads (the index is range-checked, the value is not looked at until the
   // next iteration): examining the id here would stall the wave for a full memory latency every iteration
   auto fetch_id = [&](int kt) {
+    if (!stager) return;
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
       const int p0 = kt * kAttnKeys + ((t + NT * i) >> 7) * kBlk;
@@ -130,6 +133,7 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
   // prefetch only ISSUES the loads; nothing here may depend on the loaded values, or the wave would wait for
   // them on the spot and the whole point of requesting a tile ahead would be lost
   auto prefetch = [&]() {
+    if (!stager) return;
     // unconditional loads: a page id that is absent (-1, beyond the data of this round) or out of range reads
     // block 0 instead; such a page lies wholly past n_valid, so store_lds zeroes its V and the causal mask
     // discards its scores.  A branch here would make the compiler wait for the loads inside it.
@@ -144,6 +148,7 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
   };
   // kt = tile the staged registers belong to
   auto store_lds = [&](int stage, int kt) {
+    if (!stager) return;
     uint16_t *ks = smem + stage * kAttnStage, *vt = ks + kAttnKeys * kKsStride;
 #pragma unroll
     for (int i = 0; i < NS; ++i) {

@@ -32,7 +32,6 @@ struct hsd_ctx {
   bool sync_layers = false;  // HSD_SYNC_LAYERS=1: wait for the stream after every layer (bounds the launches in flight
                              // for tools that track each dispatch; never set in timed runs)
   bool force_simple;  // HSD_FORCE_SIMPLE=1: run the plain kernels also for bf16 (cross-check of the MFMA path)
-  int attn_cfg[2] = {4, 2};  // attention work split for GQA groups of 4: query sets (= heads) per workgroup, key parts
   int k_chunks[2] = {0, 0};  // experiment override of the O / down K chunking (0 = default)
   int64_t split_rows; // largest row count for which the O / down projections run as split-K
   int gemm_cfg[5];    // tile configuration of the MFMA GEMM per call site (qkv, o, gate_up, down, lm_head)
@@ -246,13 +245,9 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
   if constexpr (std::is_same<T, bf16>::value) {
     if (!ctx->force_simple && (group == 1 || group == 2 || group % 4 == 0)) {
       // Work split, fixed per model (never chosen from the batch, so results stay bitwise batch-invariant):
-      // g4 query heads of a kv head and qs query sets per workgroup, kq key parts per tile.
-      int g4 = group >= 4 ? 4 : group, qs = 4, kq = 2;
-      if (group % 4 == 0) {
-        g4 = ctx->attn_cfg[0];
-        qs = ctx->attn_cfg[0];
-        kq = ctx->attn_cfg[1];
-      }
+      // g4 query heads of a kv head among the 4 query sets of a workgroup, 2 key parts per 64-key tile.  Measured
+      // alternatives on the 16-region workload (all slower): 4 key parts of 128-key tiles, 1 / 2 / 8 query sets.
+      const int g4 = group >= 4 ? 4 : group, qs = 4;
       const int q_tile = 32 * (qs / g4);
       const int max_tiles = b->total_q / q_tile + b->n_seq;
       const dim3 grid(max_tiles, d.n_kv_heads * ((group + g4 - 1) / g4));
@@ -275,12 +270,7 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
     hipLaunchKernelGGL((k_attn_mfma<G4, KQ, QS>), grid, dim3(64 * QS * KQ), smem, st, b->n_seq, d.n_q_heads,     \
                        b->cu_q, b->seq_slot, b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);                      \
   }
-      if (g4 == 4 && kq == 4) HSD_ATTN_LAUNCH(4, 4, 4)
-      else if (g4 == 4) HSD_ATTN_LAUNCH(4, 2, 4)
-      else if (g4 == 2 && qs == 2 && kq == 4) HSD_ATTN_LAUNCH(2, 4, 2)
-      else if (g4 == 2 && qs == 2) HSD_ATTN_LAUNCH(2, 2, 2)
-      else if (g4 == 1 && qs == 1 && kq == 4) HSD_ATTN_LAUNCH(1, 4, 1)
-      else if (g4 == 1 && qs == 1) HSD_ATTN_LAUNCH(1, 2, 1)
+      if (g4 == 4) HSD_ATTN_LAUNCH(4, 2, 4)
       else if (g4 == 2) HSD_ATTN_LAUNCH(2, 2, 4)
       else HSD_ATTN_LAUNCH(1, 2, 4)
 #undef HSD_ATTN_LAUNCH
@@ -524,11 +514,6 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   if (const char *sr = std::getenv("HSD_SPLIT_ROWS")) {
     const int64_t v = std::atoll(sr);
     if (v >= 0 && v < c->split_rows) c->split_rows = v;
-  }
-  if (const char *ac = std::getenv("HSD_ATTN_CFG")) {  // "query sets,key parts" (experiments)
-    int v[2] = {0, 0};
-    std::sscanf(ac, "%d,%d", &v[0], &v[1]);
-    if ((v[0] == 1 || v[0] == 2 || v[0] == 4) && (v[1] == 2 || v[1] == 4)) c->attn_cfg[0] = v[0], c->attn_cfg[1] = v[1];
   }
   if (const char *kc = std::getenv("HSD_KCHUNKS")) {  // "o,down" (experiments)
     int v[2] = {0, 0};
