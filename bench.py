@@ -21,6 +21,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+# Bytes that crossed the L2 <-> fabric boundary per launch of the kernel on THIS workload (fetch + write), taken
+# from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE) scaled by what the same counters read for a plain
+# 2 GiB device copy; the runs and the scaling are recorded in profiles/bench_cfg1_region_verify_hbm_traffic.md.
+# The counters cannot be read from inside this script; None for kernels not profiled that way.
+MEASURED_TRAFFIC_BYTES = {"gate_up": 62_541_824}
 
 
 def build_workload(cfg_index, seed):
@@ -70,7 +75,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--seed", type=int, default=None)
-    ap.add_argument("--cpu-sample", type=int, default=4, help="sequences of the workload the oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=16, help="sequences of the workload the oracle is timed on (0 = skip)")
     ap.add_argument("--profile-kernel", type=str, default="gate_up",
                     choices=["gate_up", "qkv", "attention", "o", "down", "lm_head", "rmsnorm", "none"])
     ap.add_argument("--random-target", action="store_true",
@@ -159,7 +164,8 @@ def main():
         ach = flops_per_launch[args.profile_kernel] / (avg_ms * 1e-3) / 1e12
         roofline = {"kernel": f"k_gemm_mfma ({args.profile_kernel})", "bound": "mfma", "achieved": round(ach, 1),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                    "traffic": None, "avg_launch_ms": round(avg_ms, 5), "launches_timed": n_launch,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.profile_kernel), "avg_launch_ms": round(avg_ms, 5),
+                    "launches_timed": n_launch,
                     "flops_per_launch": flops_per_launch[args.profile_kernel]}
     gemm_flops_step = 2.0 * desc.gemm_params * total_q
     out = {
