@@ -191,25 +191,38 @@ using GemmCfg3 = GemmCfg<128, 64, 64, 2, 1>;
 using GemmCfg5 = GemmCfg<128, 128, 64, 4, 2>;   // 8 waves, wave tile 32x64
 
 
+// Tile configuration actually used at a call site for a given problem (the launch and everything sized from the
+// tile shape, like the LM-head partial records, must agree on it).  -1 = plain kernels.
+template <typename T>
+int effective_gemm_cfg(const hsd_ctx *ctx, int site, int N, int K, int k_chunks) {
+  if (!std::is_same<T, bf16>::value || ctx->force_simple || K % 64 != 0) return -1;
+  int cfg = ctx->gemm_cfg[site];
+  if (cfg < 0 || cfg > 8 || cfg == 7) cfg = 0;
+  // the 8-wave kernel takes unchunked K in an even number (>= 4) of 64-wide slices
+  if (cfg == 8 && !(k_chunks == 1 && K % 128 == 0 && K >= 256)) cfg = 0;
+  if (site == kSiteLM) {
+    // the partial-record buffer holds vocab/64 records per row: at least 64 vocabulary rows per wave, and the
+    // vocabulary must be a whole number of tiles (it is a multiple of 128 by validation)
+    if (cfg == 2 || cfg == 3 || cfg == 5) cfg = 0;
+    if ((cfg == 1 || cfg == 6 || cfg == 8) && N % 256 != 0) cfg = 0;
+  }
+  return cfg;
+}
+
 template <typename T, typename Epi>
 int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int K, const void *A, const void *W,
                 const Epi &epi, int k_chunks = 1, bool split = false) {
   if constexpr (std::is_same<T, bf16>::value) {
-    if (!ctx->force_simple && K % 64 == 0) {
-      int cfg = ctx->gemm_cfg[site];
-      if (site == kSiteLM && (cfg == 2 || cfg == 3 || cfg == 5)) cfg = 0;  // the LM-head partial buffer assumes >= 64 rows per wave
-      switch (cfg) {
-        case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi, k_chunks, split);
-        case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi, k_chunks, split);
-        case 3: return launch_gemm_mfma<GemmCfg3>(st, M, N, K, A, W, epi, k_chunks, split);
-        case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi, k_chunks, split);
-        case 5: return launch_gemm_mfma<GemmCfg5>(st, M, N, K, A, W, epi, k_chunks, split);
-        case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi, k_chunks, split);
-        case 8:
-          if (k_chunks == 1 && K % 128 == 0 && K >= 256) return launch_gemm_mfma8(st, M, N, K, A, W, epi);
-          [[fallthrough]];
-        default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi, k_chunks, split);
-      }
+    switch (effective_gemm_cfg<T>(ctx, site, N, K, k_chunks)) {
+      case -1: break;
+      case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi, k_chunks, split);
+      case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi, k_chunks, split);
+      case 3: return launch_gemm_mfma<GemmCfg3>(st, M, N, K, A, W, epi, k_chunks, split);
+      case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi, k_chunks, split);
+      case 5: return launch_gemm_mfma<GemmCfg5>(st, M, N, K, A, W, epi, k_chunks, split);
+      case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi, k_chunks, split);
+      case 8: return launch_gemm_mfma8(st, M, N, K, A, W, epi);
+      default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi, k_chunks, split);
     }
   }
   dim3 grid(N / 64, (M + 63) / 64);
@@ -223,16 +236,14 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
 template <typename T>
 int lm_head_tiles(const hsd_ctx *ctx) {
   const int V = ctx->desc.vocab;
-  if (std::is_same<T, bf16>::value && !ctx->force_simple && ctx->desc.d_model % 64 == 0) {
-    switch (ctx->gemm_cfg[kSiteLM]) {
-      case 1: return V / GemmCfg1::BP * GemmCfg1::WM;
-      case 4: return V / GemmCfg4::BP * GemmCfg4::WM;
-      case 6: return V / GemmCfg6::BP * GemmCfg6::WM;
-      case 8: return V / GemmCfg8::BP * GemmCfg8::WM;
-      default: return V / GemmCfg0::BP * GemmCfg0::WM;
-    }
+  switch (effective_gemm_cfg<T>(ctx, kSiteLM, V, ctx->desc.d_model, 1)) {
+    case -1: return V / 64;
+    case 1: return V / GemmCfg1::BP * GemmCfg1::WM;
+    case 4: return V / GemmCfg4::BP * GemmCfg4::WM;
+    case 6: return V / GemmCfg6::BP * GemmCfg6::WM;
+    case 8: return V / GemmCfg8::BP * GemmCfg8::WM;
+    default: return V / GemmCfg0::BP * GemmCfg0::WM;
   }
-  return V / 64;
 }
 
 // Verification attention: bf16 goes to the MFMA kernel when the GQA group size fits its wave mapping.

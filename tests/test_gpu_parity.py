@@ -123,9 +123,11 @@ def test_config0_tiny_fp32_full_rounds():
 
 SMALL_BF16 = W.ModelDesc(n_layers=3, d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, d_ffn=512, vocab=1024, dtype="bf16")
 SMALL_FP32 = W.ModelDesc(n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=1, head_dim=64, d_ffn=256, vocab=512, dtype="fp32")
+# two 64-wide K slices per projection: the shortest GEMM pipeline, and every large-tile configuration falls back
+NARROW_BF16 = W.ModelDesc(n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ffn=256, vocab=640, dtype="bf16")
 
 
-@pytest.mark.parametrize("desc", [SMALL_FP32, SMALL_BF16], ids=["fp32", "bf16"])
+@pytest.mark.parametrize("desc", [SMALL_FP32, SMALL_BF16, NARROW_BF16], ids=["fp32", "bf16", "bf16-narrow"])
 @pytest.mark.parametrize("mode", ["region", "page"])
 def test_ragged_batch_rounds(desc, mode):
     """Ragged prefixes and drafts spanning several tiles with ragged tails, GQA, both entry points.
