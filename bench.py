@@ -188,6 +188,58 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    # --- attention against both of its roofs (extra steps after the timed region; event-timed like the GEMM above)
+    if args.profile_kernel != "none":
+        eng.profile(B.HSD_PROF_ATTENTION, desc.n_layers * 3 + 8)
+        for _ in range(3):
+            step()
+        cnt, ms = eng.profile_read()
+        eng.profile(B.HSD_PROF_NONE, 0)
+        if cnt > 0:
+            S = [sp.n_visual + sp.n_prompt - 1 for sp in specs]
+            Lq = [sp.draft_len + 1 for sp in specs]
+            flops = sum(4.0 * desc.n_q_heads * desc.head_dim * (l * s_ + l * (l + 1) / 2) for s_, l in zip(S, Lq))
+            kv_bytes = sum((s_ + l) * desc.n_kv_heads * desc.head_dim * 2 * 2 for s_, l in zip(S, Lq))
+            qo_bytes = 2 * total_q * desc.q_dim * 2
+            t_s = ms / cnt * 1e-3
+            out["attention"] = {"avg_launch_ms": round(ms / cnt, 5), "algorithmic_bytes": kv_bytes + qo_bytes,
+                                "achieved_GBps": round((kv_bytes + qo_bytes) / t_s / 1e9, 1),
+                                "frac_hbm_8TBps": round((kv_bytes + qo_bytes) / t_s / 8e12, 4),
+                                "algorithmic_flops": flops, "achieved_TFLOPs": round(flops / t_s / 1e12, 1),
+                                "frac_mfma": round(flops / t_s / 1e12 / PEAK_BF16_TFLOPS, 4)}
+    # --- the same workload to completion: verify -> commit -> read (alpha, bonus) -> slice the next blocks on the
+    # host -> upload them, until every draft is consumed (not part of `value`)
+    if not args.random_target:
+        def to_completion():
+            eng.restore()
+            pending, offset = list(pend), [0] * n
+            rounds = rows = acc = 0
+            while True:
+                active = [i for i in range(n) if offset[i] < len(drafts[i])]
+                if not active:
+                    break
+                blks = [np.concatenate([[pending[i]], drafts[i][offset[i]:]]).astype(np.int32) for i in active]
+                eng.verify(active, blks, "region")
+                eng.commit()
+                a, b, st_ = eng.read_acceptance(len(active))
+                assert st_ == 0
+                for j, i in enumerate(active):
+                    rows += len(blks[j]) - 1
+                    acc += int(a[j])
+                    offset[i] += int(a[j]) + 1
+                    pending[i] = int(b[j])
+                rounds += 1
+            return rounds, rows, acc
+        to_completion()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rounds, rows, acc = to_completion()
+        torch.cuda.synchronize()
+        dtc = time.perf_counter() - t0
+        out["to_completion"] = {"rounds": rounds, "ms_total": round(dtc * 1e3, 3), "draft_rows_scored": rows,
+                                "accepted_tokens": acc, "verified_tokens_per_s": round(rows / dtc, 1),
+                                "committed_tokens_per_s": round(sum(len(d_) for d_ in drafts) / dtc, 1),
+                                "note": "includes host slicing and the upload of each round's batch"}
     if args.breakdown:
         bd = {}
         for name, cls in prof_map.items():
