@@ -83,3 +83,20 @@ def test_lossless_config1_model_m():
     specs = W.draw_sequences(1, W.SEED_BASE)
     rounds = _lossless(W.MODEL_M, specs, W.SEED_BASE, "region")
     print("cfg1 lossless rounds", rounds)
+
+
+def test_lossless_config2_page_level():
+    """configs[2] shape: one page, 4127 cached tokens, a 2048-token draft, first mismatch Geometric(0.002)."""
+    specs = W.draw_sequences(2, W.SEED_BASE)
+    rounds = _lossless(W.MODEL_M, specs, W.SEED_BASE, "page")
+    print("cfg2 lossless rounds", rounds)
+
+
+def test_lossless_config3_long_documents():
+    """configs[3] shape at full size: 4 pages of 8192 cached tokens with 8192-token drafts at 1 % corruption
+    (about 80 rounds, 32,772 rows in the first).  The CPU oracle needs hours per page here; this property needs
+    no oracle and is exact."""
+    specs = W.draw_sequences(3, W.SEED_BASE)
+    rounds = _lossless(W.MODEL_M, specs, W.SEED_BASE, "page")
+    print("cfg3 lossless rounds", rounds)
+    assert rounds >= 40
