@@ -11,7 +11,8 @@ tree is a chain and the tree-ancestry mask is the causal mask):
     pass over [pending token, d_1 .. d_k] on top of the already accepted context (Eq. 8);
   * the model's own top-1 token u_hat at every position (Eq. 10);
   * exact greedy acceptance: descend while the draft token equals u_hat (Eq. 9 and Eq. 11 in the
-    limit tau -> 1, where log p(u*) - log p(u_hat) >= 0 holds only for u* = u_hat);
+    limit tau -> 1, where log p(u*) - log p(u_hat) >= 0 holds only for u* = u_hat); with log_tau < 0 the
+    relaxed rule of Eq. 11 itself (accept while log p(u*) - log p(u_hat) >= log tau);
   * the accepted-sequence update  y <- y + accepted path + u_hat at the stop node (Eq. 12);
   * alpha = number of consecutive draft tokens accepted before the first mismatch, the quantity
     averaged by the AAL metric (Eq. 15, Section 4.2).
@@ -34,7 +35,9 @@ Pins (tests/test_oracle_pins.py, tests/test_oracle_invariants.py): Transformers'
 logits and greedy generation; torch's scaled_dot_product_attention, rms_norm and silu; complex-number
 form of the rotary embedding; pure-Python brute-force attention; the lossless invariant (verification
 rounds reproduce token-by-token greedy decoding exactly); closed-form alpha from the corruption
-positions.  No function here is "parity unpinned".
+positions; for the relaxed rule (tests/test_oracle_relaxed.py) the probability-ratio form of Eq. 11, the
+tau -> 1 and tau -> 0 limits, monotonicity in tau, a closed form on near-miss drafts and the replay invariant
+(every committed token passes the rule in its own context).  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -45,8 +48,8 @@ import numpy as np
 
 __all__ = [
     "round_bf16", "rmsnorm", "rope_rotate_half", "causal_gqa_attention", "swiglu", "KVCache", "decoder_forward",
-    "argmax_lowest_index", "top2_margin", "accept_longest_prefix", "verify_block", "greedy_decode",
-    "prefill", "spec_decode", "RoundRecord",
+    "argmax_lowest_index", "top2_margin", "accept_longest_prefix", "draft_gap", "accept_relaxed", "verify_block",
+    "greedy_decode", "prefill", "spec_decode", "RoundRecord", "embed_tokens",
 ]
 
 
@@ -249,18 +252,45 @@ def accept_longest_prefix(u_hat: np.ndarray, draft: np.ndarray) -> Tuple[int, in
     return alpha, int(u_hat[alpha])
 
 
-def verify_block(desc, weights, cache: KVCache, pending: int, draft: np.ndarray, dtype=np.float64, act_dtype=None):
+def draft_gap(logits: np.ndarray, draft: np.ndarray) -> np.ndarray:
+    """gap[i] = logit of the draft token d_{i+1} at row i minus the row's largest logit (<= 0), i = 0..k-1.
+
+    The two log-probabilities of the relaxed acceptance test (Eq. 11) share their normaliser, so their
+    difference is this difference of logits."""
+    k = len(draft)
+    rows = np.arange(k)
+    return logits[rows, np.asarray(draft, dtype=np.int64)] - logits[:k].max(axis=1)
+
+
+def accept_relaxed(logits: np.ndarray, draft: np.ndarray, log_tau: float) -> Tuple[int, int]:
+    """Relaxed walk down the chain (Eq. 9-12 with a single candidate per node): the draft token d_{i+1} is the
+    only candidate u* at node i; it is accepted iff log p(u*) - log p(u_hat) >= log tau.  Returns (alpha, bonus):
+    the number of accepted draft tokens and the model's own top-1 token at the stop node (Eq. 12)."""
+    gap = draft_gap(logits, draft)
+    k = len(draft)
+    alpha = 0
+    while alpha < k and gap[alpha] >= log_tau:
+        alpha += 1
+    return alpha, int(argmax_lowest_index(logits[alpha:alpha + 1])[0])
+
+
+def verify_block(desc, weights, cache: KVCache, pending: int, draft: np.ndarray, dtype=np.float64, act_dtype=None,
+                 log_tau: float = 0.0):
     """One verification pass for one sequence.
 
     cache holds the accepted context except its last token `pending` (whose keys/values are not
     cached yet).  Feeds [pending, d_1..d_k] in one causal pass (Eq. 8), takes u_hat at every row
-    (Eq. 10), walks the chain (Eq. 9, 11) and returns (alpha, bonus, u_hat[k+1], logits[k+1,V]).
+    (Eq. 10), walks the chain (Eq. 9, 11; log_tau = 0 is the exact-match rule, log_tau < 0 the relaxed one) and
+    returns (alpha, bonus, u_hat[k+1], logits[k+1,V]).
     All k+1 rows are appended to the cache; the caller commits by truncating to
     len_before + 1 + alpha."""
     block = np.concatenate([[pending], np.asarray(draft, dtype=np.int64)]).astype(np.int64)
     logits = decoder_forward(desc, weights, embed_tokens(weights, block, dtype), cache, dtype, act_dtype=act_dtype)
     u_hat = argmax_lowest_index(logits)
-    alpha, bonus = accept_longest_prefix(u_hat, draft)
+    if log_tau < 0.0:    # relaxed acceptance (the paper's operating point is tau = 0.75)
+        alpha, bonus = accept_relaxed(logits, draft, log_tau)
+    else:                # tau -> 1: exact greedy match, ties resolved to the lowest token id
+        alpha, bonus = accept_longest_prefix(u_hat, draft)
     return alpha, bonus, u_hat, logits
 
 
@@ -307,7 +337,7 @@ class RoundRecord:
 
 
 def spec_decode(desc, weights, cache: KVCache, pending: int, draft: np.ndarray, n_commit: int,
-                dtype=np.float64, max_block: Optional[int] = None, act_dtype=None):
+                dtype=np.float64, max_block: Optional[int] = None, act_dtype=None, log_tau: float = 0.0):
     """SpecDecode (Eq. 1) for one sequence with a single fixed, index-aligned draft.
 
     Repeats verification passes until n_commit tokens are committed.  The draft stays fixed (it
@@ -324,7 +354,7 @@ def spec_decode(desc, weights, cache: KVCache, pending: int, draft: np.ndarray, 
         if max_block is not None:
             rest = rest[: max_block]
         base = len(cache)
-        alpha, bonus, u_hat, logits = verify_block(desc, weights, cache, pending, rest, dtype, act_dtype)
+        alpha, bonus, u_hat, logits = verify_block(desc, weights, cache, pending, rest, dtype, act_dtype, log_tau)
         cache.truncate(base + 1 + alpha)                      # commit accepted rows, roll back the rest
         committed.extend(int(t) for t in rest[:alpha])
         committed.append(bonus)
