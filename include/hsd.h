@@ -115,6 +115,12 @@ typedef struct hsd_batch {
   float *logits_dump;         /* dev out [n_dump, vocab] fp32 logits of selected rows (debug) or NULL */
   const int32_t *dump_rows;   /* dev [n_dump] packed row indices                                      */
   int32_t n_dump;
+  /* Relaxed acceptance (paper Section 3.2, Eq. 11): the draft token d_{i+1} is accepted at row i iff          */
+  /* log p(d_{i+1}) - log p(u_hat) >= log_tau, i.e. iff its logit is within -log_tau of the row's largest.      */
+  /* log_tau = 0 (tau = 1) selects the exact-match rule (d_{i+1} == arg-max, lowest id among equal maxima).     */
+  float log_tau;              /* <= 0, finite                                                         */
+  float *draft_gap;           /* dev out [total_q] or NULL: logit of the NEXT row's token minus the row's max  */
+                              /*   logit (<= 0; -inf on the last row of a sequence); required if log_tau < 0   */
 } hsd_batch;
 
 typedef struct hsd_ctx hsd_ctx; /* opaque; host memory only (descriptor + copied pointer tables) */

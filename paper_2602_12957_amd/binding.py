@@ -44,7 +44,8 @@ class hsd_batch(C.Structure):
     _fields_ = [("n_seq", i32), ("total_q", i32), ("max_blocks_per_seq", i32), ("n_slots", i32),
                 ("cu_q", vp), ("seq_slot", vp), ("tokens", vp), ("embeds", vp), ("seq_len", vp),
                 ("block_table", vp), ("argmax", vp), ("top2_margin", vp), ("accept_len", vp), ("bonus", vp),
-                ("status", vp), ("logits_dump", vp), ("dump_rows", vp), ("n_dump", i32)]
+                ("status", vp), ("logits_dump", vp), ("dump_rows", vp), ("n_dump", i32),
+                ("log_tau", f32), ("draft_gap", vp)]
 
 
 _P = C.POINTER

@@ -193,6 +193,12 @@ struct EpiLMHead {
   int vocab;
   const int32_t *dump_slot;  // [T] or nullptr
   float *logits_dump;        // [n_dump][vocab]
+  const int32_t *row_want;   // [T] vocabulary id whose logit row m must record (relaxed acceptance), -1 = none;
+  float *want_logit;         //   nullptr when the exact-match rule is in force.  [T], pre-filled with -inf
+  // called for every (row, vocabulary id) the kernel computes: exactly one thread of the launch holds the wanted id
+  __device__ __forceinline__ void capture(int m, int n, float v, int want) const {
+    if (n == want) want_logit[m] = v;
+  }
   __device__ __forceinline__ void dump(int m, int n, float lo, float hi) const {
     if (dump_slot != nullptr) {
       int sl = dump_slot[m];

@@ -86,6 +86,16 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[Cfg::TM][Cfg::TN],
           int n = n0 + wi * (BP / Cfg::WM) + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
           top2_push(tp, acc[i][j][v], n);
         }
+      if (epi.want_logit != nullptr && m < M) {
+        const int want = epi.row_want[m];
+        if (want >= 0) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              epi.capture(m, n0 + wi * (BP / Cfg::WM) + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3), acc[i][j][v], want);
+        }
+      }
       if (epi.dump_slot != nullptr && m < M) {
         int sl = epi.dump_slot[m];
         if (sl >= 0) {

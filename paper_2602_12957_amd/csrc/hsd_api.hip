@@ -2,6 +2,7 @@
 // All device work is enqueued on the caller's stream; nothing here synchronises or allocates device memory.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -49,7 +50,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Workspace {
   float *x;
   void *h, *q, *a, *u;
-  int32_t *row_seq, *row_pos, *row_kv, *dump_slot, *tile_cu;
+  int32_t *row_seq, *row_pos, *row_kv, *row_want, *dump_slot, *tile_cu;
+  float *want_logit;
   float2 *rope_cs;
   Top2 *lm_part;
   float *part;  // split-K partial sums of the O / down projections
@@ -86,6 +88,8 @@ Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
   w.row_seq = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.row_pos = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.row_kv = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
+  w.row_want = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
+  w.want_logit = reinterpret_cast<float *>(take(T * sizeof(float)));
   w.dump_slot = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.tile_cu = reinterpret_cast<int32_t *>(take((n_seq + 1) * sizeof(int32_t)));
   w.rope_cs = reinterpret_cast<float2 *>(take(T * 32 * sizeof(float2)));
@@ -302,10 +306,12 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
   const int Tq = b->total_q;
   Workspace ws = carve(d, Tq, b->n_seq, ws_base);
   const int qdim = d.n_q_heads * d.head_dim, kvdim = d.n_kv_heads * d.head_dim;
+  const bool relaxed = with_head && b->log_tau < 0.f;   // Eq. 11 with tau < 1: needs the draft tokens' own logits
   int rc;
 
   hipLaunchKernelGGL(k_row_meta, dim3((Tq * 32 + 255) / 256), dim3(256), 0, st, b->n_seq, Tq, b->cu_q, b->seq_slot,
-                     b->n_slots, b->seq_len, d.rope_theta, ws.row_seq, ws.row_pos, ws.rope_cs);
+                     b->n_slots, b->seq_len, d.rope_theta, ws.row_seq, ws.row_pos, ws.rope_cs, b->tokens,
+                     relaxed ? ws.row_want : nullptr, ws.want_logit);
   HSD_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_kv_reserve, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, b->seq_slot, b->n_slots,
                      b->seq_len, b->block_table, b->max_blocks_per_seq, pool->n_blocks, pool->free_list,
@@ -388,16 +394,16 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
     dump_slot = ws.dump_slot;
   }
   const int n_tiles = lm_head_tiles<T>(ctx);
-  EpiLMHead el{ws.lm_part, n_tiles, d.vocab, dump_slot, b->logits_dump};
+  EpiLMHead el{ws.lm_part, n_tiles, d.vocab, dump_slot, b->logits_dump, ws.row_want, relaxed ? ws.want_logit : nullptr};
   {
     ProfScope ps(ctx, st, HSD_PROF_GEMM_LM_HEAD);
     if ((rc = launch_gemm<T>(ctx, st, kSiteLM, Tq, d.vocab, d.d_model, ws.h, ctx->lm_head, el))) return rc;
   }
   hipLaunchKernelGGL(k_lm_reduce, dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, n_tiles, ws.lm_part, b->argmax,
-                     b->top2_margin);
+                     b->top2_margin, ws.want_logit, relaxed ? b->draft_gap : nullptr);
   HSD_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_accept, dim3((b->n_seq + 3) / 4), dim3(256), 0, st, b->n_seq, b->cu_q, b->tokens, b->argmax,
-                     b->accept_len, b->bonus);
+                     relaxed ? b->draft_gap : nullptr, b->log_tau, b->accept_len, b->bonus);
   HSD_LAUNCH_CHECK();
   return HSD_OK;
 }
@@ -473,6 +479,10 @@ int hsd_validate_batch(const hsd_model_desc *desc, const hsd_kv_pool *pool, cons
       b->status == nullptr)
     return HSD_EINVAL;
   if (b->n_dump < 0 || (b->n_dump > 0 && (b->logits_dump == nullptr || b->dump_rows == nullptr))) return HSD_EINVAL;
+  // log_tau is log(tau) of a threshold in (0, 1]: finite and <= 0 (the comparison also rejects NaN); the relaxed
+  // rule needs somewhere to put the per-row gaps
+  if (!(b->log_tau <= 0.f) || std::isinf(b->log_tau)) return HSD_EINVAL;
+  if (b->log_tau < 0.f && b->argmax != nullptr && b->draft_gap == nullptr) return HSD_EINVAL;
   if (pool != nullptr) {
     if (pool->k_pool == nullptr || pool->v_pool == nullptr || pool->free_list == nullptr ||
         pool->free_count == nullptr || pool->n_blocks < 1)

@@ -15,7 +15,9 @@ namespace hsd {
 __global__ void k_row_meta(int n_seq, int total_q, const int32_t *__restrict__ cu_q,
                            const int32_t *__restrict__ seq_slot, int n_slots,
                            const int32_t *__restrict__ seq_len, float rope_theta, int32_t *__restrict__ row_seq,
-                           int32_t *__restrict__ row_pos, float2 *__restrict__ rope_cs) {
+                           int32_t *__restrict__ row_pos, float2 *__restrict__ rope_cs,
+                           const int32_t *__restrict__ tokens, int32_t *__restrict__ row_want,
+                           float *__restrict__ want_logit) {
   int gid = blockIdx.x * blockDim.x + threadIdx.x;
   int r = gid >> 5, i = gid & 31;
   if (r >= total_q) return;
@@ -30,6 +32,13 @@ __global__ void k_row_meta(int n_seq, int total_q, const int32_t *__restrict__ c
   if (i == 0) {
     row_seq[r] = slot;
     row_pos[r] = pos;
+    if (row_want != nullptr) {
+      // the token the draft proposes AFTER row r (relaxed acceptance needs its logit at row r); -1 on the last
+      // row of a sequence and for rows followed by an embedding row
+      int w = (r + 1 < cu_q[lo + 1]) ? tokens[r + 1] : -1;
+      row_want[r] = w < 0 ? -1 : w;
+      want_logit[r] = -INFINITY;
+    }
   }
   double inv_freq = pow(static_cast<double>(rope_theta), -2.0 * i / static_cast<double>(kHd));
   double ang = static_cast<double>(pos) * inv_freq;
@@ -368,7 +377,8 @@ __global__ void k_pool_init(int n_blocks, int32_t *__restrict__ free_list, int32
 // arg-max of probabilities) and the top-1/top-2 logit margin.
 // ------------------------------------------------------------------------------------------------
 __global__ void k_lm_reduce(int n_rows, int n_tiles, const Top2 *__restrict__ part, int32_t *__restrict__ argmax,
-                            float *__restrict__ margin) {
+                            float *__restrict__ margin, const float *__restrict__ want_logit,
+                            float *__restrict__ draft_gap) {
   int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int r = blockIdx.x * 4 + wave;
   if (r >= n_rows) return;
@@ -385,28 +395,33 @@ __global__ void k_lm_reduce(int n_rows, int n_tiles, const Top2 *__restrict__ pa
   if (lane == 0) {
     argmax[r] = t.i1;
     if (margin != nullptr) margin[r] = t.m1 - t.m2;
+    // Eq. 11 in logits: log p(u*) - log p(u_hat) = logit(u*) - max logit (same normaliser)
+    if (draft_gap != nullptr) draft_gap[r] = want_logit[r] - t.m1;
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Draft compare + longest-prefix acceptance (Eq. 9, 11 at exact match; Eq. 12 bonus; alpha of Eq. 15).
-// One wave per sequence: lanes compare 64 draft positions at a time, a ballot finds the first
-// mismatch.  match_i = (tokens[base+i] == argmax[base+i-1]) for i = 1..k.
+// Draft compare + longest-prefix acceptance (Eq. 9, 11; Eq. 12 bonus; alpha of Eq. 15).
+// One wave per sequence: lanes test 64 draft positions at a time, a ballot finds the first rejection.
+// Exact rule (log_tau == 0): reject_i = (tokens[base+i] != argmax[base+i-1]) for i = 1..k.
+// Relaxed rule (log_tau < 0): reject_i = !(draft_gap[base+i-1] >= log_tau).
 // ------------------------------------------------------------------------------------------------
 __global__ void k_accept(int n_seq, const int32_t *__restrict__ cu_q, const int32_t *__restrict__ tokens,
-                         const int32_t *__restrict__ argmax, int32_t *__restrict__ accept_len,
-                         int32_t *__restrict__ bonus) {
+                         const int32_t *__restrict__ argmax, const float *__restrict__ draft_gap, float log_tau,
+                         int32_t *__restrict__ accept_len, int32_t *__restrict__ bonus) {
   int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int s = blockIdx.x * 4 + wave;
   if (s >= n_seq) return;
   int base = cu_q[s], k = cu_q[s + 1] - base - 1;
+  const bool relaxed = log_tau < 0.f && draft_gap != nullptr;
   int alpha = k;
   for (int i0 = 1; i0 <= k; i0 += kWave) {
     int i = i0 + lane;
-    bool mismatch = (i <= k) && (tokens[base + i] != argmax[base + i - 1]);
-    unsigned long long m = __ballot(mismatch);
+    bool reject = false;
+    if (i <= k) reject = relaxed ? !(draft_gap[base + i - 1] >= log_tau) : (tokens[base + i] != argmax[base + i - 1]);
+    unsigned long long m = __ballot(reject);
     if (m != 0ull) {
-      alpha = i0 + (__ffsll(static_cast<long long>(m)) - 1) - 1;  // accepted = index of first mismatch - 1
+      alpha = i0 + (__ffsll(static_cast<long long>(m)) - 1) - 1;  // accepted = index of first rejection - 1
       break;
     }
   }

@@ -39,6 +39,7 @@ class VerifyOutput:
     accept_len: torch.Tensor  # device int32 [n_seq]
     bonus: torch.Tensor       # device int32 [n_seq]
     logits: Optional[torch.Tensor] = None  # device fp32 [n_dump, vocab]
+    gap: Optional[torch.Tensor] = None     # device fp32 [total_q]: draft token's logit minus the row maximum
 
 
 class Engine:
@@ -104,6 +105,7 @@ class Engine:
         self._d_meta = torch.empty(n_meta, dtype=torch.int32, device=self.dev)
         self.argmax = torch.zeros(max_total_q, dtype=torch.int32, device=self.dev)
         self.margin = torch.zeros(max_total_q, dtype=torch.float32, device=self.dev)
+        self.gap = torch.zeros(max_total_q, dtype=torch.float32, device=self.dev)
         self.accept_len = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
         self.bonus = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
         self.pending = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
@@ -165,7 +167,8 @@ class Engine:
         return B.hsd_profile_read(self.ctx)
 
     def _make_batch(self, slots: Sequence[int], blocks: Sequence[np.ndarray], dump_rows=None,
-                    with_outputs: bool = True, embeds: Optional[torch.Tensor] = None) -> B.hsd_batch:
+                    with_outputs: bool = True, embeds: Optional[torch.Tensor] = None,
+                    log_tau: float = 0.0) -> B.hsd_batch:
         n = len(slots)
         lens = [len(b) for b in blocks]
         total = int(sum(lens))
@@ -201,6 +204,9 @@ class Engine:
         if with_outputs:
             b.argmax, b.top2_margin = _ptr(self.argmax), _ptr(self.margin)
             b.accept_len, b.bonus = _ptr(self.accept_len), _ptr(self.bonus)
+            b.log_tau = float(log_tau)
+            if log_tau < 0:
+                b.draft_gap = _ptr(self.gap)
         if nd:
             b.logits_dump, b.dump_rows, b.n_dump = _ptr(self.logits_dump), base + 4 * o_dump, nd
         self._cu = cu
@@ -235,19 +241,21 @@ class Engine:
                 torch.cuda.current_stream(self.dev).synchronize()   # dev_emb must outlive the pass
 
     def verify(self, slots: Sequence[int], blocks: Sequence[np.ndarray], mode: str = "region",
-               dump_rows=None) -> VerifyOutput:
-        """One verification pass; blocks[i] = [pending token, d_1..d_k] of sequence slots[i].  Asynchronous."""
-        b = self._make_batch(slots, blocks, dump_rows)
+               dump_rows=None, log_tau: float = 0.0) -> VerifyOutput:
+        """One verification pass; blocks[i] = [pending token, d_1..d_k] of sequence slots[i].  Asynchronous.
+        log_tau = 0 is the exact-match rule; log_tau < 0 the relaxed acceptance test with threshold tau."""
+        b = self._make_batch(slots, blocks, dump_rows, log_tau=log_tau)
         fn = B.hsd_verify_region_batch if mode == "region" else B.hsd_verify_page
         fn(self.ctx, self.stream, self.cpool, b, _ptr(self.ws), self.ws_bytes)
         self._batch = b
         n, T = b.n_seq, b.total_q
         return VerifyOutput(n, T, self._cu.copy(), self.argmax[:T], self.margin[:T], self.accept_len[:n],
-                            self.bonus[:n], self.logits_dump[:b.n_dump] if b.n_dump else None)
+                            self.bonus[:n], self.logits_dump[:b.n_dump] if b.n_dump else None,
+                            self.gap[:T] if log_tau < 0 else None)
 
-    def prepare(self, slots: Sequence[int], blocks: Sequence[np.ndarray]) -> B.hsd_batch:
+    def prepare(self, slots: Sequence[int], blocks: Sequence[np.ndarray], log_tau: float = 0.0) -> B.hsd_batch:
         """Uploads a batch description once; verify_prepared/commit can then be replayed on it."""
-        b = self._make_batch(slots, blocks)
+        b = self._make_batch(slots, blocks, log_tau=log_tau)
         self._batch = b
         return b
 

@@ -76,6 +76,12 @@ def test_validate_batch():
     assert B.hsd_validate_batch(d, _pool(), _batch(n_slots=2), need) == B.HSD_EINVAL          # identity slots need n_slots >= n_seq
     assert B.hsd_validate_batch(d, _pool(), _batch(n_slots=2, seq_slot=0x1000), need) == B.HSD_OK
     assert B.hsd_validate_batch(d, _pool(), _batch(n_dump=2), need) == B.HSD_EINVAL           # dump without buffers
+    # acceptance threshold: log(tau) of a tau in (0, 1]; the relaxed rule needs its output buffer
+    assert B.hsd_validate_batch(d, _pool(), _batch(log_tau=0.1), need) == B.HSD_EINVAL
+    assert B.hsd_validate_batch(d, _pool(), _batch(log_tau=float("nan")), need) == B.HSD_EINVAL
+    assert B.hsd_validate_batch(d, _pool(), _batch(log_tau=float("-inf"), draft_gap=0x1000), need) == B.HSD_EINVAL
+    assert B.hsd_validate_batch(d, _pool(), _batch(log_tau=-0.3), need) == B.HSD_EINVAL
+    assert B.hsd_validate_batch(d, _pool(), _batch(log_tau=-0.3, draft_gap=0x1000), need) == B.HSD_OK
     assert B.hsd_validate_batch(d, _pool(n_blocks=0), _batch(), need) == B.HSD_EINVAL
     assert B.hsd_validate_batch(d, _pool(k_pool=None), _batch(), need) == B.HSD_EINVAL
     assert B.hsd_workspace_bytes(_desc(head_dim=32), 10, 1) == 0
