@@ -245,6 +245,22 @@ def main():
                                 "accepted_tokens": acc, "verified_tokens_per_s": round(rows / dtc, 1),
                                 "committed_tokens_per_s": round(sum(len(d_) for d_ in drafts) / dtc, 1),
                                 "note": "includes host slicing and the upload of each round's batch"}
+    # --- the same model decoding the same sequences one token per pass (Lq = 1 for every region): the
+    # autoregressive baseline of the paper's decode-time speedup ratio (Section 4.2), on this GPU and this library
+    if not args.random_target:
+        eng.restore()
+        n_ar = 32
+        eng.greedy_decode(slots, pend, 4)
+        eng.restore()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        eng.greedy_decode(slots, pend, n_ar)
+        torch.cuda.synchronize()
+        dar = time.perf_counter() - t0
+        ar_rate = n * n_ar / dar
+        out["ar_decode_baseline"] = {"tokens_per_s": round(ar_rate, 1), "ms_per_token_step": round(dar / n_ar * 1e3, 4),
+                                     "steps_timed": n_ar, "batch": n,
+                                     "speedup_to_completion": round(out["to_completion"]["committed_tokens_per_s"] / ar_rate, 2)}
     if args.breakdown:
         bd = {}
         for name, cls in prof_map.items():

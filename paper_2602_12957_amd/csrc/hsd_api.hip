@@ -35,6 +35,7 @@ struct hsd_ctx {
   bool force_simple;  // HSD_FORCE_SIMPLE=1: run the plain kernels also for bf16 (cross-check of the MFMA path)
   int k_chunks[2] = {0, 0};  // experiment override of the O / down K chunking (0 = default)
   int64_t split_rows; // largest row count for which the O / down projections run as split-K
+  bool gemm_cfg_forced = false;  // HSD_GEMM_CFG given: use it for every row count
   int gemm_cfg[5];    // tile configuration of the MFMA GEMM per call site (qkv, o, gate_up, down, lm_head)
   // per-kernel timing (hsd_profile_*)
   int prof_which = HSD_PROF_NONE;
@@ -198,10 +199,14 @@ using GemmCfg5 = GemmCfg<128, 128, 64, 4, 2>;   // 8 waves, wave tile 32x64
 // Tile configuration actually used at a call site for a given problem (the launch and everything sized from the
 // tile shape, like the LM-head partial records, must agree on it).  -1 = plain kernels.
 template <typename T>
-int effective_gemm_cfg(const hsd_ctx *ctx, int site, int N, int K, int k_chunks) {
+int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_chunks) {
   if (!std::is_same<T, bf16>::value || ctx->force_simple || K % 64 != 0) return -1;
   int cfg = ctx->gemm_cfg[site];
   if (cfg < 0 || cfg > 8 || cfg == 7) cfg = 0;
+  // A pass over a few rows (token-by-token decoding) has a single row tile: small tiles give it more workgroups.
+  // The tile shape never changes a result bit (every output element sums its K slices in the same order), so
+  // choosing it from the row count keeps the path batch-invariant.
+  if (M <= 64 && !ctx->gemm_cfg_forced) cfg = 2;
   // the 8-wave kernel takes unchunked K in an even number (>= 4) of 64-wide slices
   if (cfg == 8 && !(k_chunks == 1 && K % 128 == 0 && K >= 256)) cfg = 0;
   if (site == kSiteLM) {
@@ -217,7 +222,7 @@ template <typename T, typename Epi>
 int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int K, const void *A, const void *W,
                 const Epi &epi, int k_chunks = 1, bool split = false) {
   if constexpr (std::is_same<T, bf16>::value) {
-    switch (effective_gemm_cfg<T>(ctx, site, N, K, k_chunks)) {
+    switch (effective_gemm_cfg<T>(ctx, site, M, N, K, k_chunks)) {
       case -1: break;
       case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi, k_chunks, split);
       case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi, k_chunks, split);
@@ -238,9 +243,9 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
 
 // Number of (row, column-tile) partial records the LM-head GEMM writes per row.
 template <typename T>
-int lm_head_tiles(const hsd_ctx *ctx) {
+int lm_head_tiles(const hsd_ctx *ctx, int M) {
   const int V = ctx->desc.vocab;
-  switch (effective_gemm_cfg<T>(ctx, kSiteLM, V, ctx->desc.d_model, 1)) {
+  switch (effective_gemm_cfg<T>(ctx, kSiteLM, M, V, ctx->desc.d_model, 1)) {
     case -1: return V / 64;
     case 1: return V / GemmCfg1::BP * GemmCfg1::WM;
     case 4: return V / GemmCfg4::BP * GemmCfg4::WM;
@@ -393,7 +398,7 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
     HSD_LAUNCH_CHECK();
     dump_slot = ws.dump_slot;
   }
-  const int n_tiles = lm_head_tiles<T>(ctx);
+  const int n_tiles = lm_head_tiles<T>(ctx, Tq);
   EpiLMHead el{ws.lm_part, n_tiles, d.vocab, dump_slot, b->logits_dump, ws.row_want, relaxed ? ws.want_logit : nullptr};
   {
     ProfScope ps(ctx, st, HSD_PROF_GEMM_LM_HEAD);
@@ -548,6 +553,7 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   const int defaults[5] = {5, 2, 8, 0, 8};
   for (int i = 0; i < 5; ++i) c->gemm_cfg[i] = defaults[i];
   if (const char *gc = std::getenv("HSD_GEMM_CFG")) {
+    c->gemm_cfg_forced = true;
     int vals[5], n = std::sscanf(gc, "%d,%d,%d,%d,%d", &vals[0], &vals[1], &vals[2], &vals[3], &vals[4]);
     for (int i = 0; i < 5; ++i)
       if (n == 1) c->gemm_cfg[i] = vals[0]; else if (i < n) c->gemm_cfg[i] = vals[i];
