@@ -37,7 +37,10 @@ form of the rotary embedding; pure-Python brute-force attention; the lossless in
 rounds reproduce token-by-token greedy decoding exactly); closed-form alpha from the corruption
 positions; for the relaxed rule (tests/test_oracle_relaxed.py) the probability-ratio form of Eq. 11, the
 tau -> 1 and tau -> 0 limits, monotonicity in tau, a closed form on near-miss drafts and the replay invariant
-(every committed token passes the rule in its own context).  No function here is "parity unpinned".
+(every committed token passes the rule in its own context); for prefix-tree batching (tests/test_oracle_tree.py)
+the worked example's tree, subtree intervals = ancestry, every node's logits against an independent chain
+evaluation of its root-to-node path, reduction to the chain for one candidate, lossless tree rounds whose
+compacted cache equals a token-by-token one.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -50,6 +53,7 @@ __all__ = [
     "round_bf16", "rmsnorm", "rope_rotate_half", "causal_gqa_attention", "swiglu", "KVCache", "decoder_forward",
     "argmax_lowest_index", "top2_margin", "accept_longest_prefix", "draft_gap", "accept_relaxed", "verify_block",
     "greedy_decode", "prefill", "spec_decode", "RoundRecord", "embed_tokens",
+    "build_prefix_tree", "ancestry_mask", "walk_prefix_tree", "verify_tree",
 ]
 
 
@@ -94,7 +98,8 @@ def rope_rotate_half(x: np.ndarray, positions: np.ndarray, theta: float) -> np.n
     return np.concatenate([lo * cos - hi * sin, hi * cos + lo * sin], axis=-1)
 
 
-def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_pos0: int, act_dtype=None) -> np.ndarray:
+def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_pos0: int, act_dtype=None,
+                         block_mask: Optional[np.ndarray] = None) -> np.ndarray:
     """Softmax attention of a block of queries over a key/value history.
 
     q: [Lq, Hq, hd] queries at absolute positions q_pos0 .. q_pos0+Lq-1.
@@ -114,6 +119,10 @@ def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_pos0: in
     key_pos = np.arange(n_keys)[None, :]
     qry_pos = (q_pos0 + np.arange(Lq))[:, None]
     allowed = key_pos <= qry_pos                                           # [Lq, n_keys]
+    if block_mask is not None:
+        # tree-ancestry mask (Section 3.2): every key before the block is visible, key q_pos0 + j of the block is
+        # visible to query row i iff block_mask[i, j]
+        allowed = np.concatenate([np.ones((Lq, q_pos0), dtype=bool), np.asarray(block_mask, dtype=bool)], axis=1)
     for h in range(Hq):
         kh = k[:, h // group, :]
         vh = v[:, h // group, :]
@@ -170,6 +179,14 @@ class KVCache:
     def advance(self, n_new: int) -> None:
         self._n += n_new
 
+    def compact(self, base: int, slots: Sequence[int]) -> None:
+        """Moves the keys/values stored at positions `slots` (increasing, each >= its target) to the contiguous
+        positions base, base+1, ...: the accepted root-to-node path of a packed tree becomes ordinary context."""
+        for layer in range(len(self._kbuf)):
+            for d, src in enumerate(slots):
+                self._kbuf[layer][base + d] = self._kbuf[layer][src]
+                self._vbuf[layer][base + d] = self._vbuf[layer][src]
+
     def truncate(self, n: int) -> None:
         """Rollback: forget every position >= n."""
         assert n <= self._n
@@ -187,18 +204,23 @@ def _cast_weights(weights: Dict, dtype) -> Dict:
 
 
 def decoder_forward(desc, weights: Dict, x_rows: np.ndarray, cache: KVCache, dtype=np.float64,
-                    want_logits: bool = True, act_dtype=None) -> Optional[np.ndarray]:
+                    want_logits: bool = True, act_dtype=None, depth: Optional[np.ndarray] = None,
+                    block_mask: Optional[np.ndarray] = None) -> Optional[np.ndarray]:
     """Causal forward of the decoder over a block of new rows of one sequence.
 
     x_rows: [n, d_model] input embeddings of the new rows (token rows already looked up).  The rows
     sit at absolute positions len(cache) .. len(cache)+n-1.  Their keys/values are appended to
-    `cache`.  Returns logits [n, vocab] (or None when want_logits is False)."""
+    `cache`.  Returns logits [n, vocab] (or None when want_logits is False).
+
+    Packed prefix tree (Section 3.2): with `depth` [n] and `block_mask` [n, n] given, row i sits at position
+    len(cache) + depth[i] (its position on its own root-to-node path) and sees, inside the block, exactly the rows
+    j with block_mask[i, j]; its keys/values are still stored at cache slot len(cache) + i."""
     w = _cast_weights(weights, dtype)
     rnd = _act_round(act_dtype)
     x = np.asarray(x_rows, dtype=dtype).copy()
     n = x.shape[0]
     pos0 = len(cache)
-    positions = pos0 + np.arange(n)
+    positions = pos0 + (np.arange(n) if depth is None else np.asarray(depth, dtype=np.int64))
     Hq, Hkv, hd = desc.n_q_heads, desc.n_kv_heads, desc.head_dim
     for l, lay in enumerate(w["layers"]):
         h = rnd(rmsnorm(x, lay["attn_norm"], desc.rms_eps))
@@ -209,7 +231,8 @@ def decoder_forward(desc, weights: Dict, x_rows: np.ndarray, cache: KVCache, dty
         q = rnd(rope_rotate_half(q, positions, desc.rope_theta))
         k = rnd(rope_rotate_half(k, positions, desc.rope_theta))
         cache.write(l, pos0, k, rnd(v))
-        a = rnd(causal_gqa_attention(q, cache.keys(l, pos0 + n), cache.values(l, pos0 + n), pos0, act_dtype))
+        a = rnd(causal_gqa_attention(q, cache.keys(l, pos0 + n), cache.values(l, pos0 + n), pos0, act_dtype,
+                                     block_mask))
         x = x + a.reshape(n, Hq * hd) @ lay["wo"].T
         h = rnd(rmsnorm(x, lay["ffn_norm"], desc.rms_eps))
         gu = h @ lay["w_gate_up"].T
@@ -292,6 +315,98 @@ def verify_block(desc, weights, cache: KVCache, pending: int, draft: np.ndarray,
     else:                # tau -> 1: exact greedy match, ties resolved to the lowest token id
         alpha, bonus = accept_longest_prefix(u_hat, draft)
     return alpha, bonus, u_hat, logits
+
+
+# ----------------------------------------------------------------------------------------------
+# Prefix-tree batching (Section 3.2, Eq. 7 and the tree-ancestry mask; acceptance Eq. 9-12 over Next(s))
+# ----------------------------------------------------------------------------------------------
+
+def build_prefix_tree(pending: int, candidates: Sequence[Sequence[int]]):
+    """Merges the candidate continuations into a prefix tree and linearises it in depth-first pre-order.
+
+    Row 0 is the root (empty prefix): it carries the pending token, whose row produces the distribution the
+    root's children are tested against.  Children of a node keep the order in which their tokens first appear
+    in `candidates`.  Returns int arrays over the packed rows: tokens, parent (-1 for the root), depth (0 for the
+    root) and end (row index one past the node's subtree, so j is an ancestor-or-self of i iff j <= i < end[j])."""
+    children: List[Dict[int, int]] = [{}]          # per node: token -> node id (creation order)
+    tok, par = [int(pending)], [-1]
+    for c in candidates:
+        v = 0
+        for t in c:
+            t = int(t)
+            if t not in children[v]:
+                children[v][t] = len(tok)
+                tok.append(t)
+                par.append(v)
+                children.append({})
+            v = children[v][t]
+    order, new_id = [], {}
+    stack = [0]
+    while stack:                                   # pre-order, children in creation order
+        v = stack.pop()
+        new_id[v] = len(order)
+        order.append(v)
+        stack.extend(reversed(list(children[v].values())))
+    n = len(order)
+    tokens = np.array([tok[v] for v in order], dtype=np.int64)
+    parent = np.array([-1 if par[v] < 0 else new_id[par[v]] for v in order], dtype=np.int64)
+    depth = np.zeros(n, dtype=np.int64)
+    end = np.arange(1, n + 1, dtype=np.int64)
+    for i in range(1, n):
+        depth[i] = depth[parent[i]] + 1
+    for i in range(n - 1, 0, -1):                  # a node's subtree ends where its last descendant's does
+        end[parent[i]] = max(end[parent[i]], end[i])
+    return tokens, parent, depth, end
+
+
+def ancestry_mask(parent: np.ndarray) -> np.ndarray:
+    """mask[i, j] = row j is row i itself or one of its ancestors (the tree-ancestry attention mask)."""
+    n = len(parent)
+    mask = np.zeros((n, n), dtype=bool)
+    for i in range(n):
+        v = i
+        while v >= 0:
+            mask[i, v] = True
+            v = int(parent[v])
+    return mask
+
+
+def walk_prefix_tree(logits: np.ndarray, tokens: np.ndarray, parent: np.ndarray, log_tau: float = 0.0):
+    """Greedy traversal (Eq. 9-12).  At node s the candidate u* is the child whose token has the highest logit at
+    row s (lowest row index among equals); it is entered iff logit(u*) - max logit >= log_tau (log_tau = 0: iff u*
+    is the arg-max token itself, lowest id among equal maxima).  Returns (path rows excluding the root, bonus =
+    arg-max token at the stop node)."""
+    n = len(tokens)
+    kids: List[List[int]] = [[] for _ in range(n)]
+    for i in range(1, n):
+        kids[int(parent[i])].append(i)
+    s, path = 0, []
+    while kids[s]:
+        row = logits[s]
+        best = max(kids[s], key=lambda c: (row[tokens[c]], -c))
+        u_hat = int(argmax_lowest_index(row[None, :])[0])
+        ok = (row[tokens[best]] - row.max() >= log_tau) if log_tau < 0.0 else (int(tokens[best]) == u_hat)
+        if not ok:
+            break
+        path.append(best)
+        s = best
+    return path, int(argmax_lowest_index(logits[s:s + 1])[0])
+
+
+def verify_tree(desc, weights, cache: KVCache, pending: int, candidates: Sequence[Sequence[int]], dtype=np.float64,
+                act_dtype=None, log_tau: float = 0.0):
+    """One verification pass over the prefix tree of `candidates` (all of them continuations of the accepted
+    context + pending token).  Returns (accepted tokens, bonus, logits [n, V], (tokens, parent, depth, end)).
+    On return the cache holds the accepted context extended by the pending token and the accepted path
+    (the path's keys/values are moved to contiguous positions, everything else of the block is rolled back)."""
+    tokens, parent, depth, end = build_prefix_tree(pending, candidates)
+    base = len(cache)
+    logits = decoder_forward(desc, weights, embed_tokens(weights, tokens, dtype), cache, dtype, act_dtype=act_dtype,
+                             depth=depth, block_mask=ancestry_mask(parent))
+    path, bonus = walk_prefix_tree(logits, tokens, parent, log_tau)
+    cache.compact(base + 1, [base + r for r in path])
+    cache.truncate(base + 1 + len(path))
+    return [int(tokens[r]) for r in path], bonus, logits, (tokens, parent, depth, end)
 
 
 def prefill(desc, weights, visual: np.ndarray, prompt: Sequence[int], dtype=np.float64, act_dtype=None):
