@@ -48,7 +48,8 @@ enum { HSD_FP32 = 0, HSD_BF16 = 1 };
 enum {
   HSD_STATUS_POOL_EXHAUSTED = 1, /* not enough free KV blocks for the speculative append */
   HSD_STATUS_TABLE_OVERFLOW = 2, /* seq_len + q_len exceeds max_blocks_per_seq * 16       */
-  HSD_STATUS_BAD_SLOT = 4        /* a seq_slot entry lies outside [0, n_slots)           */
+  HSD_STATUS_BAD_SLOT = 4,       /* a seq_slot entry lies outside [0, n_slots)           */
+  HSD_STATUS_BAD_TREE = 8        /* a tree_end / tree_depth entry was not a valid packed tree */
 };
 
 enum { HSD_KV_BLOCK_TOKENS = 16, HSD_HEAD_DIM = 64, HSD_MAX_SEQ = 4096 };
@@ -119,8 +120,21 @@ typedef struct hsd_batch {
   /* log p(d_{i+1}) - log p(u_hat) >= log_tau, i.e. iff its logit is within -log_tau of the row's largest.      */
   /* log_tau = 0 (tau = 1) selects the exact-match rule (d_{i+1} == arg-max, lowest id among equal maxima).     */
   float log_tau;              /* <= 0, finite                                                         */
-  float *draft_gap;           /* dev out [total_q] or NULL: logit of the NEXT row's token minus the row's max  */
-                              /*   logit (<= 0; -inf on the last row of a sequence); required if log_tau < 0   */
+  float *draft_gap;           /* dev out [total_q] or NULL: logit of the row's OWN token under its parent row    */
+                              /*   (the previous row of a chain) minus that row's max logit (<= 0; -inf on the  */
+                              /*   first row of a sequence); required if log_tau < 0                            */
+  /* Prefix-tree batching (paper Section 3.2, Eq. 7 and the tree-ancestry mask).  NULL tree_end = every block    */
+  /* is a chain.  Otherwise each sequence's block is a prefix tree packed in depth-first pre-order: local row 0   */
+  /* is the root (it carries the pending token), and the subtree of local row i is local rows                    */
+  /* i .. tree_end[cu_q[s]+i]-1.  A row sits at position seq_len + tree_depth (its place on its own root-to-node */
+  /* path), sees the accepted context plus its ancestors and itself, and its K/V go to cache slot seq_len + i.   */
+  /* Acceptance walks the tree from the root (Eq. 9-12); commit moves the accepted path's K/V to the contiguous  */
+  /* slots seq_len+1 .. seq_len+alpha and rolls the rest back.  Malformed entries are clamped to a valid tree    */
+  /* and reported as HSD_STATUS_BAD_TREE.                                                                        */
+  const int32_t *tree_end;    /* dev [total_q] or NULL                                                */
+  const int32_t *tree_depth;  /* dev [total_q]; required with tree_end; root = 0, child = parent + 1  */
+  int32_t *stop_row;          /* dev out [n_seq]: local row of the stop node; required with tree_end  */
+                              /*   when argmax is given; input of commit                              */
 } hsd_batch;
 
 typedef struct hsd_ctx hsd_ctx; /* opaque; host memory only (descriptor + copied pointer tables) */

@@ -19,7 +19,7 @@ lib = C.CDLL(LIB_PATH)
 
 HSD_OK, HSD_EINVAL, HSD_ENOSPC, HSD_ERANGE, HSD_EARCH, HSD_ENODEV, HSD_EHIP = 0, -1, -2, -3, -4, -5, -6
 HSD_FP32, HSD_BF16 = 0, 1
-HSD_STATUS_POOL_EXHAUSTED, HSD_STATUS_TABLE_OVERFLOW, HSD_STATUS_BAD_SLOT = 1, 2, 4
+HSD_STATUS_POOL_EXHAUSTED, HSD_STATUS_TABLE_OVERFLOW, HSD_STATUS_BAD_SLOT, HSD_STATUS_BAD_TREE = 1, 2, 4, 8
 HSD_KV_BLOCK_TOKENS, HSD_HEAD_DIM, HSD_MAX_SEQ = 16, 64, 4096
 
 i32, f32, vp = C.c_int32, C.c_float, C.c_void_p
@@ -45,7 +45,7 @@ class hsd_batch(C.Structure):
                 ("cu_q", vp), ("seq_slot", vp), ("tokens", vp), ("embeds", vp), ("seq_len", vp),
                 ("block_table", vp), ("argmax", vp), ("top2_margin", vp), ("accept_len", vp), ("bonus", vp),
                 ("status", vp), ("logits_dump", vp), ("dump_rows", vp), ("n_dump", i32),
-                ("log_tau", f32), ("draft_gap", vp)]
+                ("log_tau", f32), ("draft_gap", vp), ("tree_end", vp), ("tree_depth", vp), ("stop_row", vp)]
 
 
 _P = C.POINTER

@@ -67,7 +67,8 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
                                                    const int32_t *__restrict__ seq_slot, int n_slots,
                                                    const int32_t *__restrict__ seq_len,
                                                    const int32_t *__restrict__ tile_cu, PagedKV kv,
-                                                   const bf16 *__restrict__ q, bf16 *__restrict__ out) {
+                                                   const bf16 *__restrict__ q, bf16 *__restrict__ out,
+                                                   const int32_t *__restrict__ row_end) {
   constexpr int kAttnKeys = 32 * KQ, kAttnStage = attn_stage_elems(KQ);
   // threads; 16-byte K (and V) pieces staged per thread and tile (with 8 query sets only the first 256*KQ threads stage)
   constexpr int NT = 64 * QS * KQ, NS = QS >= 4 ? 1 : 4 / QS;
@@ -214,7 +215,19 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
         st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk].v, st, 0, 0, 0);
       }
       // scores stay unscaled; the softmax scale rides in the exponent's fused multiply-add
-      if (kb + 31 > S + row0) {  // half tile reaches past the wave's first query: causal mask (wave-uniform)
+      if (row_end != nullptr) {
+        // packed prefix tree (tree-ancestry mask): inside the block, the key in slot S + p is visible to local
+        // row r iff p is r itself or an ancestor of r, i.e. p <= r < end of p's subtree (rows are in pre-order)
+        if (kb + 31 >= S) {  // half tile reaches into the block (wave-uniform)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int kpos = kb + 8 * (v >> 2) + 4 * half + (v & 3);
+            bool vis = kpos <= pos_j;
+            if (vis && kpos >= S) vis = row_end[base + kpos - S] > base + my_row;
+            if (!vis) st[v] = -INFINITY;
+          }
+        }
+      } else if (kb + 31 > S + row0) {  // half tile reaches past the wave's first query: causal mask (wave-uniform)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int kpos = kb + 8 * (v >> 2) + 4 * half + (v & 3);

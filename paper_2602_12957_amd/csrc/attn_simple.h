@@ -1,7 +1,8 @@
 // Verification attention, plain version (fp32 debug path and cross-check of the MFMA kernel).
 // Row r of sequence s at absolute position p attends to cached positions 0..p of s: the accepted prefix
 // plus the draft rows before it in the same block, which the QKV epilogue has already appended to the
-// pages (the chain case of the tree-ancestry mask, paper Section 3.2).  Query head h reads kv head h/group.
+// pages (the chain case of the tree-ancestry mask, paper Section 3.2; with row_end given, the packed prefix tree
+// itself).  Query head h reads kv head h/group.
 // One wave per (row, query head): lanes own one key each for the scores and one head dimension each for
 // the weighted sum of values; online softmax in fp32.
 #pragma once
@@ -19,7 +20,10 @@ __global__ void __launch_bounds__(256) k_attn_simple(int n_q_heads, RowMeta meta
   const int r = blockIdx.x, head = blockIdx.y * 4 + wave;
   if (head >= n_q_heads) return;
   const int group = n_q_heads / kv.n_kv_heads, kvh = head / group;
-  const int s = meta.row_seq[r], p = meta.row_pos[r], n_keys = p + 1;
+  // keys live in cache slots 0 .. slot(r); slots before the block hold the accepted context (all visible), slot
+  // S + i holds row i of the block: visible iff i is r's own row or (packed prefix tree) one of its ancestors
+  const int s = meta.row_seq[r], n_keys = meta.row_slot[r] + 1;
+  const int row0 = meta.row_base[r], S = meta.row_slot[r] - (r - row0);
   const T *kpool = static_cast<const T *>(kv.k_pool);
   const T *vpool = static_cast<const T *>(kv.v_pool);
 
@@ -33,6 +37,7 @@ __global__ void __launch_bounds__(256) k_attn_simple(int n_q_heads, RowMeta meta
   for (int j0 = 0; j0 < n_keys; j0 += kWave) {
     int j = j0 + lane;
     int blk = (j < n_keys) ? kv_lookup_block(kv, s, j) : -1;
+    if (meta.row_end != nullptr && j >= S && j < n_keys && meta.row_end[row0 + j - S] <= r) blk = -1;  // not an ancestor
     float score = -INFINITY;
     if (blk >= 0) {
       const T *kp = kpool + kv_block_offset(kv, blk, kvh) + (j % kBlk) * kHd;

@@ -127,9 +127,12 @@ __device__ __forceinline__ int slot_of(const int32_t *seq_slot, int s, int n_slo
 // Per-row metadata built once per pass.
 struct RowMeta {
   const int32_t *row_seq;  // [T] state row (slot) of the row's sequence
-  const int32_t *row_pos;  // [T] absolute position of the row in its sequence
+  const int32_t *row_pos;  // [T] absolute position of the row in its sequence (what the rotary embedding sees)
   const float2 *rope_cs;   // [T][32] (cos, sin) of pos * theta^(-2i/64)
-  const int32_t *row_kv;   // [T] 16 * (block id holding the row's position) + position % 16, or -1 if no valid block
+  const int32_t *row_kv;   // [T] 16 * (block id holding the row's cache slot) + slot % 16, or -1 if no valid block
+  const int32_t *row_slot; // [T] cache slot of the row's K/V: committed length + index of the row in its block
+  const int32_t *row_base; // [T] packed index of the first row of the row's block
+  const int32_t *row_end;  // [T] packed index one past the row's subtree (packed prefix tree), or nullptr: chains
 };
 
 // Everything a kernel needs to find a (sequence, position) slot in the paged pools.

@@ -193,11 +193,20 @@ struct EpiLMHead {
   int vocab;
   const int32_t *dump_slot;  // [T] or nullptr
   float *logits_dump;        // [n_dump][vocab]
-  const int32_t *row_want;   // [T] vocabulary id whose logit row m must record (relaxed acceptance), -1 = none;
-  float *want_logit;         //   nullptr when the exact-match rule is in force.  [T], pre-filled with -inf
-  // called for every (row, vocabulary id) the kernel computes: exactly one thread of the launch holds the wanted id
-  __device__ __forceinline__ void capture(int m, int n, float v, int want) const {
-    if (n == want) want_logit[m] = v;
+  // Relaxed acceptance needs, for every candidate row c, the logit of c's own token at its PARENT row m.  The
+  // children of row m in the packed pre-order tree are m+1, row_end[m+1], ... while < row_end[m] (a chain: just m+1).
+  const int32_t *tokens;     // [T] packed token ids
+  const int32_t *row_end;    // [T] packed index one past each row's subtree
+  float *want_logit;         // [T] out, indexed by the CANDIDATE row, pre-filled with -inf; nullptr = exact rule
+  // called with the logits v[0..count) of row m at vocabulary ids n[e]: every (row, id) pair is computed by exactly
+  // one thread of the launch, so each wanted logit is written once, from the accumulator that feeds the arg-max
+  template <typename F>
+  __device__ __forceinline__ void capture(int m, F &&match) const {
+    for (int c = m + 1; c < row_end[m]; c = row_end[c]) {
+      const int want = tokens[c];
+      float v;
+      if (want >= 0 && match(want, v)) want_logit[c] = v;
+    }
   }
   __device__ __forceinline__ void dump(int m, int n, float lo, float hi) const {
     if (dump_slot != nullptr) {

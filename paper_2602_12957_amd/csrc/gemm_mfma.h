@@ -87,14 +87,20 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[Cfg::TM][Cfg::TN],
           top2_push(tp, acc[i][j][v], n);
         }
       if (epi.want_logit != nullptr && m < M) {
-        const int want = epi.row_want[m];
-        if (want >= 0) {
+        // this lane holds row m's logits at ids nb + 32*i + 8*(v/4) + 4*half + v%4, i < TM, v < 16
+        const int nb = n0 + wi * (BP / Cfg::WM);
+        epi.capture(m, [&](int want, float &out) {
+          const int rel = want - nb;
+          if (rel < 0 || rel >= TM * 32 || ((rel >> 2) & 1) != half) return false;
+          const int i = rel >> 5, vv = ((rel & 31) >> 3) * 4 + (rel & 3);
+          bool hit = false;
 #pragma unroll
-          for (int i = 0; i < TM; ++i)
+          for (int ii = 0; ii < TM; ++ii)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-              epi.capture(m, n0 + wi * (BP / Cfg::WM) + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3), acc[i][j][v], want);
-        }
+              if (ii == i && v == vv) out = acc[ii][j][v], hit = true;
+          return hit;
+        });
       }
       if (epi.dump_slot != nullptr && m < M) {
         int sl = epi.dump_slot[m];

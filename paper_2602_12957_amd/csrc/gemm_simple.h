@@ -89,9 +89,12 @@ __global__ void __launch_bounds__(256) k_gemm_simple(int M, int N, int K, const 
       top2_push(tp, acc[i][1], n0 + tx + 32);
       if (m < M) epi.dump(m, n0 + tx, acc[i][0], acc[i][1]);
       if (m < M && epi.want_logit != nullptr) {
-        const int want = epi.row_want[m];
-        epi.capture(m, n0 + tx, acc[i][0], want);
-        epi.capture(m, n0 + tx + 32, acc[i][1], want);
+        const float v0 = acc[i][0], v1 = acc[i][1];
+        epi.capture(m, [&](int want, float &out) {
+          if (want == n0 + tx) { out = v0; return true; }
+          if (want == n0 + tx + 32) { out = v1; return true; }
+          return false;
+        });
       }
 #pragma unroll
       for (int o = 16; o > 0; o >>= 1) {  // stays inside the 32 lanes that share this row

@@ -51,8 +51,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Workspace {
   float *x;
   void *h, *q, *a, *u;
-  int32_t *row_seq, *row_pos, *row_kv, *row_want, *dump_slot, *tile_cu;
-  float *want_logit;
+  int32_t *row_seq, *row_pos, *row_kv, *row_slot, *row_base, *row_end, *row_par, *dump_slot, *tile_cu;
+  float *want_logit, *row_max;
   float2 *rope_cs;
   Top2 *lm_part;
   float *part;  // split-K partial sums of the O / down projections
@@ -89,8 +89,12 @@ Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
   w.row_seq = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.row_pos = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.row_kv = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
-  w.row_want = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
+  w.row_slot = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
+  w.row_base = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
+  w.row_end = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
+  w.row_par = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.want_logit = reinterpret_cast<float *>(take(T * sizeof(float)));
+  w.row_max = reinterpret_cast<float *>(take(T * sizeof(float)));
   w.dump_slot = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
   w.tile_cu = reinterpret_cast<int32_t *>(take((n_seq + 1) * sizeof(int32_t)));
   w.rope_cs = reinterpret_cast<float2 *>(take(T * 32 * sizeof(float2)));
@@ -288,7 +292,7 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
       attr_done = true;                                                                                          \
     }                                                                                                            \
     hipLaunchKernelGGL((k_attn_mfma<G4, KQ, QS>), grid, dim3(64 * QS * KQ), smem, st, b->n_seq, d.n_q_heads,     \
-                       b->cu_q, b->seq_slot, b->n_slots, b->seq_len, ws.tile_cu, kv, q, o);                      \
+                       b->cu_q, b->seq_slot, b->n_slots, b->seq_len, ws.tile_cu, kv, q, o, meta.row_end);        \
   }
       if (g4 == 4) HSD_ATTN_LAUNCH(4, 2, 4)
       else if (g4 == 2) HSD_ATTN_LAUNCH(2, 2, 4)
@@ -315,21 +319,22 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
   int rc;
 
   hipLaunchKernelGGL(k_row_meta, dim3((Tq * 32 + 255) / 256), dim3(256), 0, st, b->n_seq, Tq, b->cu_q, b->seq_slot,
-                     b->n_slots, b->seq_len, d.rope_theta, ws.row_seq, ws.row_pos, ws.rope_cs, b->tokens,
-                     relaxed ? ws.row_want : nullptr, ws.want_logit);
+                     b->n_slots, b->seq_len, d.rope_theta, ws.row_seq, ws.row_pos, ws.row_slot, ws.row_base, ws.rope_cs,
+                     b->tree_end, b->tree_depth, ws.row_end, relaxed ? ws.row_par : nullptr, ws.want_logit, b->status);
   HSD_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_kv_reserve, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, b->seq_slot, b->n_slots,
                      b->seq_len, b->block_table, b->max_blocks_per_seq, pool->n_blocks, pool->free_list,
                      pool->free_count, b->status);
   HSD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_row_kv, dim3((Tq + 255) / 256), dim3(256), 0, st, Tq, ws.row_seq, ws.row_pos, b->block_table,
+  hipLaunchKernelGGL(k_row_kv, dim3((Tq + 255) / 256), dim3(256), 0, st, Tq, ws.row_seq, ws.row_slot, b->block_table,
                      b->max_blocks_per_seq, pool->n_blocks, ws.row_kv);
   HSD_LAUNCH_CHECK();
   hipLaunchKernelGGL((k_embed<T>), dim3(Tq), dim3(256), 0, st, d.d_model, d.vocab, b->tokens, b->embeds,
                      static_cast<const T *>(ctx->tok_embed), ws.x);
   HSD_LAUNCH_CHECK();
 
-  RowMeta meta{ws.row_seq, ws.row_pos, ws.rope_cs, ws.row_kv};
+  const bool tree = b->tree_end != nullptr;
+  RowMeta meta{ws.row_seq, ws.row_pos, ws.rope_cs, ws.row_kv, ws.row_slot, ws.row_base, tree ? ws.row_end : nullptr};
   const bool mfma_path = std::is_same<T, bf16>::value && !ctx->force_simple;
   auto chunks_for = [&](int want, int K) { return (mfma_path && K % (want * 64) == 0) ? want : 1; };
   const bool split_ok = mfma_path && Tq <= ctx->split_rows;
@@ -399,16 +404,27 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
     dump_slot = ws.dump_slot;
   }
   const int n_tiles = lm_head_tiles<T>(ctx, Tq);
-  EpiLMHead el{ws.lm_part, n_tiles, d.vocab, dump_slot, b->logits_dump, ws.row_want, relaxed ? ws.want_logit : nullptr};
+  EpiLMHead el{ws.lm_part, n_tiles, d.vocab, dump_slot, b->logits_dump, b->tokens, ws.row_end,
+               relaxed ? ws.want_logit : nullptr};
   {
     ProfScope ps(ctx, st, HSD_PROF_GEMM_LM_HEAD);
     if ((rc = launch_gemm<T>(ctx, st, kSiteLM, Tq, d.vocab, d.d_model, ws.h, ctx->lm_head, el))) return rc;
   }
   hipLaunchKernelGGL(k_lm_reduce, dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, n_tiles, ws.lm_part, b->argmax,
-                     b->top2_margin, ws.want_logit, relaxed ? b->draft_gap : nullptr);
+                     b->top2_margin, relaxed ? ws.row_max : nullptr);
   HSD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_accept, dim3((b->n_seq + 3) / 4), dim3(256), 0, st, b->n_seq, b->cu_q, b->tokens, b->argmax,
-                     relaxed ? b->draft_gap : nullptr, b->log_tau, b->accept_len, b->bonus);
+  if (relaxed) {
+    hipLaunchKernelGGL(k_draft_gap, dim3((Tq + 255) / 256), dim3(256), 0, st, Tq, ws.row_par, ws.want_logit,
+                       ws.row_max, b->draft_gap);
+    HSD_LAUNCH_CHECK();
+  }
+  if (tree)
+    hipLaunchKernelGGL(k_accept_tree, dim3((b->n_seq + 63) / 64), dim3(64), 0, st, b->n_seq, b->cu_q, b->tokens,
+                       b->argmax, ws.row_end, ws.want_logit, relaxed ? b->draft_gap : nullptr, b->log_tau,
+                       b->accept_len, b->bonus, b->stop_row);
+  else
+    hipLaunchKernelGGL(k_accept, dim3((b->n_seq + 3) / 4), dim3(256), 0, st, b->n_seq, b->cu_q, b->tokens, b->argmax,
+                       relaxed ? b->draft_gap : nullptr, b->log_tau, b->accept_len, b->bonus);
   HSD_LAUNCH_CHECK();
   return HSD_OK;
 }
@@ -488,6 +504,8 @@ int hsd_validate_batch(const hsd_model_desc *desc, const hsd_kv_pool *pool, cons
   // rule needs somewhere to put the per-row gaps
   if (!(b->log_tau <= 0.f) || std::isinf(b->log_tau)) return HSD_EINVAL;
   if (b->log_tau < 0.f && b->argmax != nullptr && b->draft_gap == nullptr) return HSD_EINVAL;
+  if (b->tree_end != nullptr && (b->tree_depth == nullptr || (b->argmax != nullptr && b->stop_row == nullptr)))
+    return HSD_EINVAL;
   if (pool != nullptr) {
     if (pool->k_pool == nullptr || pool->v_pool == nullptr || pool->free_list == nullptr ||
         pool->free_count == nullptr || pool->n_blocks < 1)
@@ -630,6 +648,23 @@ int hsd_kv_commit_rollback(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, 
   int rc = hsd_validate_batch(&ctx->desc, pool, b, static_cast<size_t>(-1));
   if (rc != HSD_OK) return rc;
   if (b->accept_len == nullptr || b->bonus == nullptr) return HSD_EINVAL;
+  if (b->tree_end != nullptr) {
+    // packed prefix tree: move the accepted path's K/V to contiguous slots before the lengths change
+    if (b->stop_row == nullptr) return HSD_EINVAL;
+    const hsd_model_desc &d = ctx->desc;
+    const dim3 grid(b->n_seq, d.n_layers * d.n_kv_heads);
+    if (d.dtype == HSD_BF16)
+      hipLaunchKernelGGL((k_kv_compact<bf16>), grid, dim3(64), 0, static_cast<hipStream_t>(stream), b->cu_q, b->seq_slot,
+                         b->n_slots, b->seq_len, b->block_table, b->max_blocks_per_seq, pool->n_blocks, d.n_kv_heads,
+                         b->tree_end, b->accept_len, b->stop_row, static_cast<bf16 *>(pool->k_pool),
+                         static_cast<bf16 *>(pool->v_pool));
+    else
+      hipLaunchKernelGGL((k_kv_compact<float>), grid, dim3(64), 0, static_cast<hipStream_t>(stream), b->cu_q, b->seq_slot,
+                         b->n_slots, b->seq_len, b->block_table, b->max_blocks_per_seq, pool->n_blocks, d.n_kv_heads,
+                         b->tree_end, b->accept_len, b->stop_row, static_cast<float *>(pool->k_pool),
+                         static_cast<float *>(pool->v_pool));
+    HSD_LAUNCH_CHECK();
+  }
   hipLaunchKernelGGL(k_kv_commit, dim3(1), dim3(1024), 0, static_cast<hipStream_t>(stream), b->n_seq, b->cu_q,
                      b->seq_slot, b->n_slots, b->seq_len, b->block_table, b->max_blocks_per_seq, pool->n_blocks, pool->free_list,
                      pool->free_count, b->accept_len, b->bonus, pending_out, 0);

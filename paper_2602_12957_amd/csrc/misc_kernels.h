@@ -7,7 +7,12 @@
 namespace hsd {
 
 // ------------------------------------------------------------------------------------------------
-// Row metadata: sequence id, absolute position and rotary (cos, sin) table of every packed row.
+// Row metadata of every packed row: sequence, rotary position and (cos, sin) table, cache slot, and the packed
+// tree it belongs to.  A chain block is the tree in which every row's subtree is the rest of the block.
+//   row_pos  = seq_len + depth   (position on the row's own root-to-node path: what the rotary embedding sees)
+//   row_slot = seq_len + local index (where its K/V are stored until commit)
+//   row_end  = GLOBAL row index one past the row's subtree, clamped into (row, end of the sequence's block]
+//   row_par  = GLOBAL row index of the parent (nearest earlier row whose subtree contains this one), -1 for a root
 // The angle is formed in fp64 (position * theta^(-2i/64)) so that positions of many thousands lose
 // nothing before the fp32 rounding of cos/sin themselves.
 // grid: ceil(T*32 / 256) blocks of 256 threads; thread -> (row, frequency index i)
@@ -15,9 +20,12 @@ namespace hsd {
 __global__ void k_row_meta(int n_seq, int total_q, const int32_t *__restrict__ cu_q,
                            const int32_t *__restrict__ seq_slot, int n_slots,
                            const int32_t *__restrict__ seq_len, float rope_theta, int32_t *__restrict__ row_seq,
-                           int32_t *__restrict__ row_pos, float2 *__restrict__ rope_cs,
-                           const int32_t *__restrict__ tokens, int32_t *__restrict__ row_want,
-                           float *__restrict__ want_logit) {
+                           int32_t *__restrict__ row_pos, int32_t *__restrict__ row_slot,
+                           int32_t *__restrict__ row_base, float2 *__restrict__ rope_cs,
+                           const int32_t *__restrict__ tree_end,
+                           const int32_t *__restrict__ tree_depth, int32_t *__restrict__ row_end,
+                           int32_t *__restrict__ row_par, float *__restrict__ want_logit,
+                           int32_t *__restrict__ status) {
   int gid = blockIdx.x * blockDim.x + threadIdx.x;
   int r = gid >> 5, i = gid & 31;
   if (r >= total_q) return;
@@ -27,16 +35,46 @@ __global__ void k_row_meta(int n_seq, int total_q, const int32_t *__restrict__ c
     int mid = (lo + hi + 1) >> 1;
     if (cu_q[mid] <= r) lo = mid; else hi = mid - 1;
   }
+  const int base = cu_q[lo], stop = cu_q[lo + 1], local = r - base;
   int slot = slot_of(seq_slot, lo, n_slots);
-  int pos = seq_len[slot] + (r - cu_q[lo]);
+  int depth = local;
+  if (tree_depth != nullptr) {
+    depth = tree_depth[r];
+    if (depth < 0 || depth > local || (local > 0 && depth == 0)) {
+      depth = local > 0 ? 1 : 0;
+      if (i == 0) atomicOr(status, HSD_STATUS_BAD_TREE);
+    }
+  }
+  int pos = seq_len[slot] + depth;
   if (i == 0) {
     row_seq[r] = slot;
     row_pos[r] = pos;
-    if (row_want != nullptr) {
-      // the token the draft proposes AFTER row r (relaxed acceptance needs its logit at row r); -1 on the last
-      // row of a sequence and for rows followed by an embedding row
-      int w = (r + 1 < cu_q[lo + 1]) ? tokens[r + 1] : -1;
-      row_want[r] = w < 0 ? -1 : w;
+    row_slot[r] = seq_len[slot] + local;
+    row_base[r] = base;
+    int e = stop;
+    if (tree_end != nullptr) {
+      e = base + tree_end[r];
+      if (e <= r || e > stop || (local == 0 && e != stop)) {
+        e = local == 0 ? stop : r + 1;
+        atomicOr(status, HSD_STATUS_BAD_TREE);
+      }
+    }
+    row_end[r] = e;
+    if (row_par != nullptr) {
+      // nearest earlier row whose (clamped) subtree reaches past r; row `base` (the root) always qualifies
+      int p = -1;
+      if (local > 0) {
+        p = base;
+        if (tree_end == nullptr) {
+          p = r - 1;
+        } else {
+          for (int j = r - 1; j > base; --j) {
+            int ej = base + tree_end[j];
+            if (ej > r && ej <= stop) { p = j; break; }
+          }
+        }
+      }
+      row_par[r] = p;
       want_logit[r] = -INFINITY;
     }
   }
@@ -52,12 +90,12 @@ __global__ void k_row_meta(int n_seq, int total_q, const int32_t *__restrict__ c
 // every layer, so the projection epilogues of all layers read this one array instead of walking
 // row -> sequence -> table themselves.  Runs after the reservation kernel.
 // grid: ceil(T / 256) blocks of 256 threads
-__global__ void k_row_kv(int total_q, const int32_t *__restrict__ row_seq, const int32_t *__restrict__ row_pos,
+__global__ void k_row_kv(int total_q, const int32_t *__restrict__ row_seq, const int32_t *__restrict__ row_slot,
                          const int32_t *__restrict__ block_table, int max_blocks_per_seq, int n_blocks,
                          int32_t *__restrict__ row_kv) {
   int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= total_q) return;
-  const int pos = row_pos[r], bi = pos / kBlk;
+  const int pos = row_slot[r], bi = pos / kBlk;
   int b = -1;
   if (bi < max_blocks_per_seq) b = block_table[static_cast<size_t>(row_seq[r]) * max_blocks_per_seq + bi];
   row_kv[r] = (b >= 0 && b < n_blocks) ? b * kBlk + pos % kBlk : -1;
@@ -377,8 +415,7 @@ __global__ void k_pool_init(int n_blocks, int32_t *__restrict__ free_list, int32
 // arg-max of probabilities) and the top-1/top-2 logit margin.
 // ------------------------------------------------------------------------------------------------
 __global__ void k_lm_reduce(int n_rows, int n_tiles, const Top2 *__restrict__ part, int32_t *__restrict__ argmax,
-                            float *__restrict__ margin, const float *__restrict__ want_logit,
-                            float *__restrict__ draft_gap) {
+                            float *__restrict__ margin, float *__restrict__ row_max) {
   int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int r = blockIdx.x * 4 + wave;
   if (r >= n_rows) return;
@@ -395,16 +432,26 @@ __global__ void k_lm_reduce(int n_rows, int n_tiles, const Top2 *__restrict__ pa
   if (lane == 0) {
     argmax[r] = t.i1;
     if (margin != nullptr) margin[r] = t.m1 - t.m2;
-    // Eq. 11 in logits: log p(u*) - log p(u_hat) = logit(u*) - max logit (same normaliser)
-    if (draft_gap != nullptr) draft_gap[r] = want_logit[r] - t.m1;
+    if (row_max != nullptr) row_max[r] = t.m1;
   }
 }
 
+// Relaxed acceptance (Eq. 11) in logits: log p(u*) - log p(u_hat) = logit(u*) - max logit, both taken at the PARENT
+// row of the candidate.  draft_gap[r] = (logit of row r's own token at its parent's row) - (parent's row maximum);
+// -inf for root rows.  One thread per row.
+__global__ void k_draft_gap(int n_rows, const int32_t *__restrict__ row_par, const float *__restrict__ want_logit,
+                            const float *__restrict__ row_max, float *__restrict__ draft_gap) {
+  int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_rows) return;
+  const int p = row_par[r];
+  draft_gap[r] = p < 0 ? -INFINITY : want_logit[r] - row_max[p];
+}
+
 // ------------------------------------------------------------------------------------------------
-// Draft compare + longest-prefix acceptance (Eq. 9, 11; Eq. 12 bonus; alpha of Eq. 15).
+// Draft compare + longest-prefix acceptance on chain blocks (Eq. 9, 11; Eq. 12 bonus; alpha of Eq. 15).
 // One wave per sequence: lanes test 64 draft positions at a time, a ballot finds the first rejection.
 // Exact rule (log_tau == 0): reject_i = (tokens[base+i] != argmax[base+i-1]) for i = 1..k.
-// Relaxed rule (log_tau < 0): reject_i = !(draft_gap[base+i-1] >= log_tau).
+// Relaxed rule (log_tau < 0): reject_i = !(draft_gap[base+i] >= log_tau).
 // ------------------------------------------------------------------------------------------------
 __global__ void k_accept(int n_seq, const int32_t *__restrict__ cu_q, const int32_t *__restrict__ tokens,
                          const int32_t *__restrict__ argmax, const float *__restrict__ draft_gap, float log_tau,
@@ -418,7 +465,7 @@ __global__ void k_accept(int n_seq, const int32_t *__restrict__ cu_q, const int3
   for (int i0 = 1; i0 <= k; i0 += kWave) {
     int i = i0 + lane;
     bool reject = false;
-    if (i <= k) reject = relaxed ? !(draft_gap[base + i - 1] >= log_tau) : (tokens[base + i] != argmax[base + i - 1]);
+    if (i <= k) reject = relaxed ? !(draft_gap[base + i] >= log_tau) : (tokens[base + i] != argmax[base + i - 1]);
     unsigned long long m = __ballot(reject);
     if (m != 0ull) {
       alpha = i0 + (__ffsll(static_cast<long long>(m)) - 1) - 1;  // accepted = index of first rejection - 1
@@ -428,6 +475,88 @@ __global__ void k_accept(int n_seq, const int32_t *__restrict__ cu_q, const int3
   if (lane == 0) {
     accept_len[s] = alpha;
     bonus[s] = argmax[base + alpha];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Greedy traversal of a packed prefix tree (Eq. 9-12).  One thread per sequence (trees are small: the candidate
+// continuations of one matching step).  At node s the children are s+1, row_end[s+1], ... while < row_end[s].
+// Exact rule: enter the child whose token is the row's arg-max token, if there is one (then u* = u_hat).
+// Relaxed rule: u* = the child with the largest logit at row s (lowest row among equals); enter it iff
+// draft_gap[u*] >= log_tau.  Outputs alpha = depth reached, the bonus token (arg-max at the stop node) and the
+// stop node's local row.
+// ------------------------------------------------------------------------------------------------
+__global__ void k_accept_tree(int n_seq, const int32_t *__restrict__ cu_q, const int32_t *__restrict__ tokens,
+                              const int32_t *__restrict__ argmax, const int32_t *__restrict__ row_end,
+                              const float *__restrict__ want_logit, const float *__restrict__ draft_gap,
+                              float log_tau, int32_t *__restrict__ accept_len, int32_t *__restrict__ bonus,
+                              int32_t *__restrict__ stop_row) {
+  int sq = blockIdx.x * blockDim.x + threadIdx.x;
+  if (sq >= n_seq) return;
+  const int base = cu_q[sq];
+  const bool relaxed = log_tau < 0.f && draft_gap != nullptr;
+  int s = base, alpha = 0;
+  for (;;) {
+    int best = -1;
+    float best_v = -INFINITY;
+    for (int c = s + 1; c < row_end[s]; c = row_end[c]) {
+      if (relaxed) {
+        float v = want_logit[c];
+        if (best < 0 || v > best_v) best = c, best_v = v;
+      } else if (tokens[c] == argmax[s]) {
+        best = c;
+        break;
+      }
+    }
+    if (best < 0) break;
+    if (relaxed && !(draft_gap[best] >= log_tau)) break;
+    s = best;
+    ++alpha;
+  }
+  accept_len[sq] = alpha;
+  bonus[sq] = argmax[s];
+  stop_row[sq] = s - base;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Commit of a packed tree: the accepted root-to-stop path becomes ordinary context.  Its node at depth d was stored
+// at cache slot S + (local row) and moves to slot S + d, d = 1..alpha (a node's pre-order row is never smaller
+// than its depth, and no target slot is the source of a later move, so the moves are independent).
+// grid: (n_seq, n_layers * n_kv_heads), block 64: lane = head dimension.  Runs BEFORE the length update.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_kv_compact(const int32_t *__restrict__ cu_q, const int32_t *__restrict__ seq_slot, int n_slots,
+                             const int32_t *__restrict__ seq_len, const int32_t *__restrict__ block_table, int maxb,
+                             int n_blocks, int n_kv_heads, const int32_t *__restrict__ tree_end,
+                             const int32_t *__restrict__ accept_len, const int32_t *__restrict__ stop_row,
+                             T *__restrict__ k_pool, T *__restrict__ v_pool) {
+  const int sq = blockIdx.x, layer = blockIdx.y / n_kv_heads, kvh = blockIdx.y % n_kv_heads, dim = threadIdx.x;
+  const int base = cu_q[sq], Lq = cu_q[sq + 1] - base;
+  const int sl = slot_of(seq_slot, sq, n_slots);
+  const int S = seq_len[sl];
+  int alpha = accept_len[sq], stop = stop_row[sq];
+  if (alpha < 1 || stop < 1 || stop >= Lq) return;
+  auto end_of = [&](int i) {   // same clamping as the row metadata kernel
+    int e = tree_end[base + i];
+    return (e <= i || e > Lq) ? i + 1 : e;
+  };
+  int s = 0;
+  for (int d = 1; d <= alpha; ++d) {
+    // the child of s whose subtree contains the stop node
+    int c = s + 1;
+    while (c < Lq && !(c <= stop && stop < end_of(c))) c = end_of(c);
+    if (c >= Lq) return;   // malformed tree: nothing sensible to move
+    s = c;
+    if (c == d) continue;  // already in place
+    const int src = S + c, dst = S + d;
+    if (src / kBlk >= maxb) return;
+    const int bs = block_table[static_cast<size_t>(sl) * maxb + src / kBlk];
+    const int bd = block_table[static_cast<size_t>(sl) * maxb + dst / kBlk];
+    if (bs < 0 || bs >= n_blocks || bd < 0 || bd >= n_blocks) return;
+    const size_t os = ((static_cast<size_t>(layer) * n_blocks + bs) * n_kv_heads + kvh) * (kBlk * kHd);
+    const size_t od = ((static_cast<size_t>(layer) * n_blocks + bd) * n_kv_heads + kvh) * (kBlk * kHd);
+    k_pool[od + (dst % kBlk) * kHd + dim] = k_pool[os + (src % kBlk) * kHd + dim];
+    v_pool[od + kv_v_elem(dst % kBlk, dim)] = v_pool[os + kv_v_elem(src % kBlk, dim)];
   }
 }
 

@@ -29,6 +29,45 @@ def _ptr(t: Optional[torch.Tensor]):
     return C.c_void_p(t.data_ptr()) if t is not None else None
 
 
+def pack_prefix_tree(pending: int, candidates: Sequence[Sequence[int]]):
+    """Host-side batching of candidate continuations into one packed prefix tree (depth-first pre-order; row 0 is
+    the root and carries the pending token; children keep the order in which their tokens first appear).
+    Returns (tokens, tree_end, tree_depth) int32 arrays as the C ABI expects them."""
+    nodes = [{}]                   # per trie node: token -> child node
+    toks, depth_of = [int(pending)], [0]
+    for cand in candidates:
+        v = 0
+        for t in cand:
+            t = int(t)
+            nxt = nodes[v].get(t)
+            if nxt is None:
+                nxt = len(nodes)
+                nodes[v][t] = nxt
+                nodes.append({})
+                toks.append(t)
+                depth_of.append(depth_of[v] + 1)
+            v = nxt
+    tokens, end, depth = [], [], []
+
+    def emit(v):                   # pre-order; recursion depth = longest candidate
+        i = len(tokens)
+        tokens.append(toks[v]), depth.append(depth_of[v]), end.append(0)
+        for c in nodes[v].values():
+            emit(c)
+        end[i] = len(tokens)
+
+    import sys
+    limit = sys.getrecursionlimit()
+    need = max((len(c) for c in candidates), default=0) + 50
+    if need > limit:
+        sys.setrecursionlimit(need)
+    try:
+        emit(0)
+    finally:
+        sys.setrecursionlimit(limit)
+    return (np.asarray(tokens, dtype=np.int32), np.asarray(end, dtype=np.int32), np.asarray(depth, dtype=np.int32))
+
+
 @dataclass
 class VerifyOutput:
     n_seq: int
@@ -39,7 +78,9 @@ class VerifyOutput:
     accept_len: torch.Tensor  # device int32 [n_seq]
     bonus: torch.Tensor       # device int32 [n_seq]
     logits: Optional[torch.Tensor] = None  # device fp32 [n_dump, vocab]
-    gap: Optional[torch.Tensor] = None     # device fp32 [total_q]: draft token's logit minus the row maximum
+    gap: Optional[torch.Tensor] = None     # device fp32 [total_q]: row's own token under its parent row, minus that
+                                           #   row's maximum logit (relaxed acceptance only)
+    stop_row: Optional[torch.Tensor] = None  # device int32 [n_seq]: local row of the stop node (tree blocks only)
 
 
 class Engine:
@@ -100,7 +141,7 @@ class Engine:
         # ---- workspace and batch staging
         self.ws_bytes = B.hsd_workspace_bytes(self.cdesc, max_total_q, n_slots)
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
-        n_meta = (n_slots + 1) + n_slots + max_total_q + max(max_dump, 1)
+        n_meta = (n_slots + 1) + n_slots + 3 * max_total_q + max(max_dump, 1)
         self._h_meta = torch.empty(n_meta, dtype=torch.int32).pin_memory()
         self._d_meta = torch.empty(n_meta, dtype=torch.int32, device=self.dev)
         self.argmax = torch.zeros(max_total_q, dtype=torch.int32, device=self.dev)
@@ -108,6 +149,7 @@ class Engine:
         self.gap = torch.zeros(max_total_q, dtype=torch.float32, device=self.dev)
         self.accept_len = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
         self.bonus = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
+        self.stop_row = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
         self.pending = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
         self._h_out = torch.empty(2 * n_slots + 1, dtype=torch.int32).pin_memory()
         self._d_out = torch.empty(2 * n_slots + 1, dtype=torch.int32, device=self.dev)
@@ -168,7 +210,7 @@ class Engine:
 
     def _make_batch(self, slots: Sequence[int], blocks: Sequence[np.ndarray], dump_rows=None,
                     with_outputs: bool = True, embeds: Optional[torch.Tensor] = None,
-                    log_tau: float = 0.0) -> B.hsd_batch:
+                    log_tau: float = 0.0, trees=None) -> B.hsd_batch:
         n = len(slots)
         lens = [len(b) for b in blocks]
         total = int(sum(lens))
@@ -189,6 +231,12 @@ class Engine:
         if nd:
             h[o_dump:o_dump + nd] = np.asarray(dump_rows, dtype=np.int32)
         used = o_dump + nd
+        o_end = o_dep = None
+        if trees is not None:      # per sequence (tree_end, tree_depth) of its packed prefix tree
+            o_end, o_dep = used, used + total
+            h[o_end:o_end + total] = np.concatenate([np.asarray(t[0], dtype=np.int32) for t in trees])
+            h[o_dep:o_dep + total] = np.concatenate([np.asarray(t[1], dtype=np.int32) for t in trees])
+            used = o_dep + total
         self._d_meta[:used].copy_(self._h_meta[:used], non_blocking=True)
         self._meta_event = torch.cuda.Event()
         self._meta_event.record(torch.cuda.current_stream(self.dev))
@@ -207,6 +255,9 @@ class Engine:
             b.log_tau = float(log_tau)
             if log_tau < 0:
                 b.draft_gap = _ptr(self.gap)
+            if trees is not None:
+                b.tree_end, b.tree_depth = base + 4 * o_end, base + 4 * o_dep
+                b.stop_row = _ptr(self.stop_row)
         if nd:
             b.logits_dump, b.dump_rows, b.n_dump = _ptr(self.logits_dump), base + 4 * o_dump, nd
         self._cu = cu
@@ -241,17 +292,19 @@ class Engine:
                 torch.cuda.current_stream(self.dev).synchronize()   # dev_emb must outlive the pass
 
     def verify(self, slots: Sequence[int], blocks: Sequence[np.ndarray], mode: str = "region",
-               dump_rows=None, log_tau: float = 0.0) -> VerifyOutput:
+               dump_rows=None, log_tau: float = 0.0, trees=None) -> VerifyOutput:
         """One verification pass; blocks[i] = [pending token, d_1..d_k] of sequence slots[i].  Asynchronous.
-        log_tau = 0 is the exact-match rule; log_tau < 0 the relaxed acceptance test with threshold tau."""
-        b = self._make_batch(slots, blocks, dump_rows, log_tau=log_tau)
+        log_tau = 0 is the exact-match rule; log_tau < 0 the relaxed acceptance test with threshold tau.
+        With trees[i] = (tree_end, tree_depth), blocks[i] holds the tokens of a packed prefix tree
+        (see pack_prefix_tree) instead of a chain."""
+        b = self._make_batch(slots, blocks, dump_rows, log_tau=log_tau, trees=trees)
         fn = B.hsd_verify_region_batch if mode == "region" else B.hsd_verify_page
         fn(self.ctx, self.stream, self.cpool, b, _ptr(self.ws), self.ws_bytes)
         self._batch = b
         n, T = b.n_seq, b.total_q
         return VerifyOutput(n, T, self._cu.copy(), self.argmax[:T], self.margin[:T], self.accept_len[:n],
                             self.bonus[:n], self.logits_dump[:b.n_dump] if b.n_dump else None,
-                            self.gap[:T] if log_tau < 0 else None)
+                            self.gap[:T] if log_tau < 0 else None, self.stop_row[:n] if trees is not None else None)
 
     def prepare(self, slots: Sequence[int], blocks: Sequence[np.ndarray], log_tau: float = 0.0) -> B.hsd_batch:
         """Uploads a batch description once; verify_prepared/commit can then be replayed on it."""
@@ -264,11 +317,14 @@ class Engine:
         fn(self.ctx, self.stream, self.cpool, b, _ptr(self.ws), self.ws_bytes)
         self._batch = b
 
-    def override_acceptance(self, accept_len: np.ndarray, bonus: np.ndarray):
-        """Test hook: replaces the device-side alpha/bonus of the last verify before commit."""
+    def override_acceptance(self, accept_len: np.ndarray, bonus: np.ndarray, stop_row: Optional[np.ndarray] = None):
+        """Test hook: replaces the device-side alpha/bonus (and, for tree blocks, the stop node) of the last verify
+        before commit."""
         n = len(accept_len)
         self.accept_len[:n].copy_(torch.from_numpy(np.asarray(accept_len, dtype=np.int32)))
         self.bonus[:n].copy_(torch.from_numpy(np.asarray(bonus, dtype=np.int32)))
+        if stop_row is not None:
+            self.stop_row[:n].copy_(torch.from_numpy(np.asarray(stop_row, dtype=np.int32)))
 
     def commit(self, pending_out: Optional[torch.Tensor] = None):
         """Commit/rollback for the batch of the last verify (alpha < 0 entries roll back)."""

@@ -86,12 +86,13 @@ def test_relaxed_acceptance_rounds(desc, tau, mode):
             cache.truncate(base + 1 + alpha)
             lo, hi = out.cu_q[j], out.cu_q[j + 1]
             ref_gap = O.draft_gap(logits, rest)
-            err = float(np.abs(g_gap[lo:hi - 1] - ref_gap).max()) if len(rest) else 0.0
+            # the device array is indexed by the candidate's own row: entry lo+1+i belongs to draft token i
+            err = float(np.abs(g_gap[lo + 1:hi] - ref_gap).max()) if len(rest) else 0.0
             stats["max_gap_err"] = max(stats["max_gap_err"], err)
             assert err <= 2 * TOL[desc.dtype], (i, err)        # a gap is a difference of two logits
-            assert g_gap[hi - 1] == -np.inf                    # no draft token follows the last row
+            assert g_gap[lo] == -np.inf                        # the pending token's row is nobody's candidate
             # the GPU's decision is the closed form of its own gaps and arg-max rows (no tolerance)
-            rej = np.nonzero(~(g_gap[lo:hi - 1] >= np.float32(lt)))[0]
+            rej = np.nonzero(~(g_gap[lo + 1:hi] >= np.float32(lt)))[0]
             a_closed = int(rej[0]) if len(rej) else len(rest)
             assert (g_alpha[j], g_bonus[j]) == (a_closed, g_arg[lo + a_closed])
             # ... and equals the oracle's wherever no deciding row is within the gate of the threshold
