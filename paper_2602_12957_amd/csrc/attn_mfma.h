@@ -60,9 +60,10 @@ union Frag8 {
 // tile and divides the number of sequential tile steps; their partial (max, sum, O^T) are merged through LDS at
 // the end, always in the same order, so results do not depend on timing.  Fewer query sets per workgroup mean
 // more, smaller workgroups (finer load balance over the CUs) at the price of staging each K/V tile more often.
+// TREE selects the tree-ancestry mask (row_end = packed index one past each row's subtree) instead of the causal one.
 // grid: (upper bound of query tiles, n_kv_heads * ceil(group / G4)), block 64*QS*KQ, dynamic LDS
 // attn_smem_bytes(KQ, QS).
-template <int G4, int KQ, int QS>
+template <int G4, int KQ, int QS, bool TREE>
 __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_heads, const int32_t *__restrict__ cu_q,
                                                    const int32_t *__restrict__ seq_slot, int n_slots,
                                                    const int32_t *__restrict__ seq_len,
@@ -215,7 +216,7 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
         st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk].v, st, 0, 0, 0);
       }
       // scores stay unscaled; the softmax scale rides in the exponent's fused multiply-add
-      if (row_end != nullptr) {
+      if constexpr (TREE) {
         // packed prefix tree (tree-ancestry mask): inside the block, the key in slot S + p is visible to local
         // row r iff p is r itself or an ancestor of r, i.e. p <= r < end of p's subtree (rows are in pre-order)
         if (kb + 31 >= S) {  // half tile reaches into the block (wave-uniform)

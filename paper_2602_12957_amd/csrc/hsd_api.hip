@@ -281,22 +281,27 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
         hipLaunchKernelGGL(k_attn_tiles, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, q_tile, ws.tile_cu);
         HSD_LAUNCH_CHECK();
       }
-#define HSD_ATTN_LAUNCH(G4, KQ, QS)                                                                              \
+#define HSD_ATTN_LAUNCH(G4, KQ, QS, TREE)                                                                        \
   {                                                                                                              \
     constexpr size_t smem = attn_smem_bytes(KQ, QS);                                                             \
     static bool attr_done = false;                                                                               \
     if (!attr_done) {                                                                                            \
-      if (smem > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void *>(k_attn_mfma<G4, KQ, QS>),       \
+      if (smem > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void *>(k_attn_mfma<G4, KQ, QS, TREE>), \
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) \
         return HSD_EHIP;                                                                                         \
       attr_done = true;                                                                                          \
     }                                                                                                            \
-    hipLaunchKernelGGL((k_attn_mfma<G4, KQ, QS>), grid, dim3(64 * QS * KQ), smem, st, b->n_seq, d.n_q_heads,     \
-                       b->cu_q, b->seq_slot, b->n_slots, b->seq_len, ws.tile_cu, kv, q, o, meta.row_end);        \
+    hipLaunchKernelGGL((k_attn_mfma<G4, KQ, QS, TREE>), grid, dim3(64 * QS * KQ), smem, st, b->n_seq,            \
+                       d.n_q_heads, b->cu_q, b->seq_slot, b->n_slots, b->seq_len, ws.tile_cu, kv, q, o,          \
+                       meta.row_end);                                                                            \
   }
-      if (g4 == 4) HSD_ATTN_LAUNCH(4, 2, 4)
-      else if (g4 == 2) HSD_ATTN_LAUNCH(2, 2, 4)
-      else HSD_ATTN_LAUNCH(1, 2, 4)
+      const bool tree = meta.row_end != nullptr;
+      if (g4 == 4 && tree) HSD_ATTN_LAUNCH(4, 2, 4, true)
+      else if (g4 == 4) HSD_ATTN_LAUNCH(4, 2, 4, false)
+      else if (g4 == 2 && tree) HSD_ATTN_LAUNCH(2, 2, 4, true)
+      else if (g4 == 2) HSD_ATTN_LAUNCH(2, 2, 4, false)
+      else if (tree) HSD_ATTN_LAUNCH(1, 2, 4, true)
+      else HSD_ATTN_LAUNCH(1, 2, 4, false)
 #undef HSD_ATTN_LAUNCH
       HSD_LAUNCH_CHECK();
       return HSD_OK;
