@@ -54,6 +54,7 @@ __all__ = [
     "argmax_lowest_index", "top2_margin", "accept_longest_prefix", "draft_gap", "accept_relaxed", "verify_block",
     "greedy_decode", "prefill", "spec_decode", "RoundRecord", "embed_tokens",
     "build_prefix_tree", "ancestry_mask", "walk_prefix_tree", "verify_tree",
+    "match_candidates", "cap_candidates", "spec_decode_matching",
 ]
 
 
@@ -407,6 +408,81 @@ def verify_tree(desc, weights, cache: KVCache, pending: int, candidates: Sequenc
     cache.compact(base + 1, [base + r for r in path])
     cache.truncate(base + 1 + len(path))
     return [int(tokens[r]) for r in path], bonus, logits, (tokens, parent, depth, end)
+
+
+# ----------------------------------------------------------------------------------------------
+# Decoupled speculative verification driver: draft-target matching (Eq. 5-6), candidate cap, rounds
+# ----------------------------------------------------------------------------------------------
+
+def match_candidates(accepted: Sequence[int], drafts: Sequence[Sequence[int]], n: int) -> List[List[int]]:
+    """Candidate continuations C (Eq. 5-6): slide the reference window w = the last n accepted tokens over every
+    draft; each occurrence that is followed by at least one token contributes the suffix after it.
+    While fewer than n tokens are accepted the window is the whole accepted sequence; with nothing accepted yet
+    every draft is a candidate from its first token (the paper leaves the start-up unspecified).
+    Duplicates are kept out (C is a set); order: by draft, then by match position."""
+    accepted = [int(t) for t in accepted]
+    w = accepted[-n:] if n > 0 else []
+    out: List[List[int]] = []
+    seen = set()
+    for d in drafts:
+        d = [int(t) for t in d]
+        starts = [0] if not w else [j for j in range(len(d) - len(w) + 1) if d[j:j + len(w)] == w]
+        for j in starts:
+            suf = d[j + len(w):]
+            if suf and tuple(suf) not in seen:
+                seen.add(tuple(suf))
+                out.append(suf)
+    return out
+
+
+def cap_candidates(candidates: Sequence[Sequence[int]], max_packed: int) -> List[List[int]]:
+    """Cuts all candidates to one common length L, the largest for which the packed prefix tree (root included)
+    has at most max_packed rows (the paper caps the packed sequence at 128 tokens but not how; cutting every
+    candidate at the same depth keeps all alternatives alive).  At least one token per candidate is kept if
+    max_packed allows a root and one child per distinct first token."""
+    cands = [list(c) for c in candidates if len(c)]
+    if not cands:
+        return []
+
+    def size(L):
+        return 1 + len({tuple(c[:k]) for c in cands for k in range(1, min(L, len(c)) + 1)})
+
+    lo, hi = 1, max(len(c) for c in cands)
+    if size(hi) <= max_packed:
+        lo = hi
+    else:
+        while lo < hi:                       # size is non-decreasing in L
+            mid = (lo + hi + 1) // 2
+            if size(mid) <= max_packed:
+                lo = mid
+            else:
+                hi = mid - 1
+    out, seen = [], set()
+    for c in cands:
+        t = tuple(c[:lo])
+        if t not in seen:
+            seen.add(t)
+            out.append(list(t))
+    return out
+
+
+def spec_decode_matching(desc, weights, cache: KVCache, pending: int, drafts: Sequence[Sequence[int]],
+                         n_commit: int, n_window: int = 3, max_packed: int = 128, dtype=np.float64,
+                         act_dtype=None, log_tau: float = 0.0):
+    """SpecDecode (Eq. 1) with a fixed draft SET and decoupled verification: every round matches the reference
+    window against all drafts, packs the candidate continuations into one prefix tree and verifies it in one
+    pass; a round without candidates is a plain decoding step (the tree is its root alone).
+    Returns (committed tokens [n_commit], list of (tree rows, accepted) per round)."""
+    committed: List[int] = []
+    rounds = []
+    while len(committed) < n_commit:
+        cands = cap_candidates(match_candidates(committed, drafts, n_window), max_packed)
+        acc, bonus, _, (tokens, _, _, _) = verify_tree(desc, weights, cache, pending, cands, dtype, act_dtype, log_tau)
+        committed.extend(acc)
+        committed.append(bonus)
+        rounds.append((len(tokens), len(acc)))
+        pending = bonus
+    return np.asarray(committed[:n_commit], dtype=np.int32), rounds
 
 
 def prefill(desc, weights, visual: np.ndarray, prompt: Sequence[int], dtype=np.float64, act_dtype=None):
