@@ -42,30 +42,23 @@ def match_candidates(accepted: Sequence[int], drafts: Sequence[Sequence[int]], n
 
 def cap_candidates(candidates: Sequence[Sequence[int]], max_packed: int) -> List[List[int]]:
     """Cuts every candidate at one common depth, the largest whose packed tree (root included) has at most
-    max_packed rows."""
-    cands = [list(c) for c in candidates if len(c)]
+    max_packed rows.  The tree has one row per distinct candidate prefix, so its size at cut depth L is
+    1 + sum over depths k <= L of the number of distinct length-k prefixes: one pass over the depths."""
+    cands = [tuple(int(t) for t in c) for c in candidates if len(c)]
     if not cands:
         return []
-
-    def size(L):
-        return 1 + len({tuple(c[:k]) for c in cands for k in range(1, min(L, len(c)) + 1)})
-
-    lo, hi = 1, max(len(c) for c in cands)
-    if size(hi) <= max_packed:
-        lo = hi
-    else:
-        while lo < hi:
-            mid = (lo + hi + 1) // 2
-            if size(mid) <= max_packed:
-                lo = mid
-            else:
-                hi = mid - 1
+    rows, depth = 1, 0
+    for k in range(1, max(len(c) for c in cands) + 1):
+        level = len({c[:k] for c in cands if len(c) >= k})
+        if rows + level > max_packed and k > 1:
+            break
+        rows, depth = rows + level, k
     out, seen = [], set()
     for c in cands:
-        t = tuple(c[:lo])
-        if t not in seen:
-            seen.add(t)
-            out.append(list(t))
+        head = c[:depth]
+        if head not in seen:
+            seen.add(head)
+            out.append(list(head))
     return out
 
 
