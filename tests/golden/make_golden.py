@@ -63,10 +63,17 @@ def one_sequence(args):
     vis, prompt = W.make_prefix(desc, seed, sp.seq_id, sp.n_visual, sp.n_prompt)
     cache, pending = O.prefill(desc, weights, vis, prompt, act_dtype=act)
     base_len = len(cache)
-    target, tmargin = O.greedy_decode(desc, weights, cache, pending, sp.draft_len, return_margins=True, act_dtype=act)
+    if RANDOM_DRAFT:
+        # long-document shapes: the token-by-token greedy target costs hours of oracle time per page; a seeded
+        # random draft still exercises every row of the full-size pass (arg-max, margins, logits) in round 1
+        target = np.random.default_rng([seed, cfg_index, sp.seq_id, 7]).integers(0, desc.vocab, size=sp.draft_len)
+        target, tmargin = target.astype(np.int32), np.zeros(sp.draft_len)
+        draft = target
+    else:
+        target, tmargin = O.greedy_decode(desc, weights, cache, pending, sp.draft_len, return_margins=True, act_dtype=act)
+        cache.truncate(base_len)
+        draft = draft_for(cfg_index, desc, seed, sp, target)
     t1 = time.time()
-    cache.truncate(base_len)
-    draft = draft_for(cfg_index, desc, seed, sp, target)
     rounds, committed = [], 0
     pend = pending
     samples = None
@@ -97,7 +104,7 @@ def one_sequence(args):
     return {"seq_id": sp.seq_id, "n_visual": sp.n_visual, "n_prompt": sp.n_prompt, "draft_len": sp.draft_len,
             "cached_len": base_len, "pending": int(pending), "target": target.tolist(),
             "target_margin": [float(f"{m:.6g}") for m in tmargin], "rounds": rounds,
-            "complete": committed >= sp.draft_len, "logit_samples": samples}
+            "complete": committed >= sp.draft_len, "logit_samples": samples, "draft_is_target": bool(RANDOM_DRAFT)}
 
 
 def noise_probe(cfg_index, seed):
@@ -117,10 +124,11 @@ def noise_probe(cfg_index, seed):
 
 
 _WEIGHTS = None
+RANDOM_DRAFT = False
 
 
 def main():
-    global _WEIGHTS
+    global _WEIGHTS, RANDOM_DRAFT
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, required=True)
     ap.add_argument("--procs", type=int, default=1)
@@ -128,6 +136,8 @@ def main():
     ap.add_argument("--seqs", type=str, default=None, help="a:b slice of the configuration's sequences")
     ap.add_argument("--out", type=str, default=None)
     ap.add_argument("--gzip", action="store_true", help="write cfgN.json.gz")
+    ap.add_argument("--random-draft", action="store_true",
+                    help="draft = seeded random tokens instead of the corrupted greedy target (no greedy decoding)")
     ap.add_argument("--trim", type=str, default=None, help="existing output of this script to cut to --max-rounds")
     args = ap.parse_args()
     here = os.path.dirname(os.path.abspath(__file__))
@@ -143,6 +153,7 @@ def main():
         write_out(out, path)
         return
     seed = W.SEED_BASE
+    RANDOM_DRAFT = args.random_draft
     desc = W.CONFIGS[args.config].model
     specs = W.draw_sequences(args.config, seed)
     if args.seqs:

@@ -82,6 +82,10 @@ def test_validate_batch():
     assert B.hsd_validate_batch(d, _pool(), _batch(log_tau=float("-inf"), draft_gap=0x1000), need) == B.HSD_EINVAL
     assert B.hsd_validate_batch(d, _pool(), _batch(log_tau=-0.3), need) == B.HSD_EINVAL
     assert B.hsd_validate_batch(d, _pool(), _batch(log_tau=-0.3, draft_gap=0x1000), need) == B.HSD_OK
+    # packed prefix trees: the depths and the stop-node output come with tree_end
+    assert B.hsd_validate_batch(d, _pool(), _batch(tree_end=0x1000), need) == B.HSD_EINVAL
+    assert B.hsd_validate_batch(d, _pool(), _batch(tree_end=0x1000, tree_depth=0x1000), need) == B.HSD_EINVAL
+    assert B.hsd_validate_batch(d, _pool(), _batch(tree_end=0x1000, tree_depth=0x1000, stop_row=0x1000), need) == B.HSD_OK
     assert B.hsd_validate_batch(d, _pool(n_blocks=0), _batch(), need) == B.HSD_EINVAL
     assert B.hsd_validate_batch(d, _pool(k_pool=None), _batch(), need) == B.HSD_EINVAL
     assert B.hsd_workspace_bytes(_desc(head_dim=32), 10, 1) == 0

@@ -64,6 +64,9 @@ def _run_config(cfg, mode, max_rounds=None):
     drafts = []
     for s, sp in zip(seqs, specs):
         assert pend[len(drafts)] == s["pending"]
+        if s.get("draft_is_target"):       # long-document golden: seeded random draft stored as the target
+            drafts.append(np.asarray(s["target"], np.int32))
+            continue
         fn = W.corrupt_draft_forced if sp.forced_different else W.corrupt_draft
         drafts.append(fn(np.asarray(s["target"], np.int32), sp.corrupt_p, desc.vocab, seed, f"cfg{cfg}.{sp.seq_id}")[0])
     n_rounds = max(len(s["rounds"]) for s in seqs)

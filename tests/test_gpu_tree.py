@@ -279,3 +279,37 @@ def test_tree_rounds_with_commit_are_lossless_model_m():
                                                 tie_gate=0.07)
     print("model M tree rounds", rounds, "moved paths", moved, "near-tie stops", ties)
     assert moved > 0 and len(ties) <= rounds * len(specs) // 4
+
+
+def test_malformed_tree_is_clamped_and_flagged():
+    """tree_end / tree_depth entries that do not describe a packed pre-order tree are clamped on the device to a
+    valid one (so nothing can index outside its block) and reported in the status word; a well-formed call on the
+    same engine afterwards is unaffected."""
+    import paper_2602_12957_amd.binding as B
+    from paper_2602_12957_amd.runtime import pack_prefix_tree
+    desc, seed = BF16, 5
+    weights = W.make_weights(desc, seed)
+    sp = SequenceSpec(0, 20, 3, 40, 0.0)
+    eng = make_engine(desc, weights, [sp], max_dump=0)
+    _, _, tok, emb, pending = prefix_rows(desc, seed, sp)
+    eng.prefill([0], [tok], [emb])
+    cands = [[1, 2, 3, 4], [1, 2, 9], [7, 8]]
+    t, e, d = pack_prefix_tree(pending, cands)
+    for bad_e, bad_d in ((np.zeros_like(e), d), (np.full_like(e, 10 ** 6), d), (e, np.full_like(d, -3)),
+                         (e[::-1].copy(), d[::-1].copy())):
+        eng.status.zero_()
+        for lt in (0.0, math.log(0.5)):
+            eng.verify([0], [t], "region", log_tau=lt, trees=[(bad_e, bad_d)])
+            alpha, bonus, status = eng.read_acceptance(1)
+            assert status & B.HSD_STATUS_BAD_TREE
+            assert 0 <= alpha[0] < len(t)
+            eng.commit()                                   # compaction walks the same (clamped) structure
+            torch.cuda.synchronize()
+            # roll the sequence back to its prefix for the next case
+            eng.reset()
+            eng.prefill([0], [tok], [emb])
+    eng.status.zero_()
+    out = eng.verify([0], [t], "region", trees=[(e, d)])
+    alpha, bonus, status = eng.read_acceptance(1)
+    assert status == 0 and 0 <= out.stop_row.cpu().numpy()[0] < len(t)
+    eng.close()
