@@ -139,9 +139,6 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, const b
   HSD_G8_STORE(0, 0, 0, 4)
   __syncthreads();
   // slice kt+1 lives in set (kt+1) & 1; requests for slice kt+2 reuse set kt & 1 (stored one iteration ago)
-#ifdef HSD_GEMM_TRACE
-  const long long tr1 = clock64();
-#endif
   // the host only launches this kernel with an even number (>= 4) of K slices: full iterations in pairs, then
   // the fixed two-iteration tail (keeping the control flow this simple keeps the kernel free of register spills)
   int kt = 0;
@@ -151,9 +148,6 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, const b
   }
   HSD_G8_ITER(kt, 0, 1, false, true)
   HSD_G8_ITER(kt + 1, 1, 0, false, false)
-#ifdef HSD_GEMM_TRACE
-  const long long tr2 = clock64();
-#endif
 #undef HSD_G8_LOAD
 #undef HSD_G8_STORE
 #undef HSD_G8_FRAG
@@ -162,14 +156,6 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, const b
 
   gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(-1, M),
                            reinterpret_cast<float *>(smem_raw));
-#ifdef HSD_GEMM_TRACE
-  if ((blockIdx.x % 37) == 0 && t == 0 && MODE == kModeDual) {
-    __builtin_amdgcn_s_waitcnt(0);
-    const long long tr3 = clock64();
-    printf("g8 trace wg=%d tile=(%d,%d) prologue=%lld loop=%lld epi_issue=%lld start=%lld\n", (int)blockIdx.x, m0, n0, tr1 - tr0,
-           tr2 - tr1, tr3 - tr2, tr0);
-  }
-#endif
 }
 
 }  // namespace hsd
