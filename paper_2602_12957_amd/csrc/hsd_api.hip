@@ -213,6 +213,10 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_
   if (M <= 64 && !ctx->gemm_cfg_forced) cfg = 2;
   // the 8-wave kernel takes unchunked K in an even number (>= 4) of 64-wide slices
   if (cfg == 8 && !(k_chunks == 1 && K % 128 == 0 && K >= 256)) cfg = 0;
+  // ... and addresses its operands with 32-bit byte offsets (buffer loads): both matrices must stay below 2 GiB
+  // (in dual mode the weight matrix has 2N rows)
+  const int64_t w_rows = site == kSiteGateUp ? 2 * static_cast<int64_t>(N) : N;
+  if (cfg == 8 && (static_cast<int64_t>(M) * K * 2 >= (int64_t{1} << 31) || w_rows * K * 2 >= (int64_t{1} << 31))) cfg = 0;
   if (site == kSiteLM) {
     // the partial-record buffer holds vocab/64 records per row: at least 64 vocabulary rows per wave, and the
     // vocabulary must be a whole number of tiles (it is a multiple of 128 by validation)
