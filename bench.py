@@ -261,6 +261,16 @@ def main():
         out["ar_decode_baseline"] = {"tokens_per_s": round(ar_rate, 1), "ms_per_token_step": round(dar / n_ar * 1e3, 4),
                                      "steps_timed": n_ar, "batch": n,
                                      "speedup_to_completion": round(out["to_completion"]["committed_tokens_per_s"] / ar_rate, 2)}
+    # --- prefix prefill of the same 16 regions (excluded from the decode metric, reported for the end-to-end picture)
+    eng.reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    eng.prefill(slots, toks, embs)
+    torch.cuda.synchronize()
+    dpf = time.perf_counter() - t0
+    n_prefill = sum(len(t) for t in toks)
+    out["prefill"] = {"rows": n_prefill, "ms": round(dpf * 1e3, 3), "rows_per_s": round(n_prefill / dpf, 1),
+                      "note": "includes the upload of the fp32 visual embedding rows"}
     if args.breakdown:
         bd = {}
         for name, cls in prof_map.items():
