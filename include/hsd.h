@@ -5,8 +5,9 @@
  * one forward pass of the decoder over every sequence's block [pending token, d_1 .. d_k] on top of
  * the sequence's accepted context held in a paged KV cache (paper Section 3.2, Eq. 8), the model's own
  * top-1 token at every row (Eq. 10), greedy acceptance of the longest draft prefix that matches it
- * (Eq. 9 and Eq. 11 taken at tau -> 1, i.e. exact match; the linear-draft case in which the prefix
- * tree is a chain and the tree-ancestry mask is the causal mask), and the bonus token of Eq. 12.
+ * (Eq. 9 and Eq. 11; by default at tau -> 1, i.e. exact match, in the linear-draft case in which the
+ * prefix tree is a chain and the tree-ancestry mask is the causal mask; hsd_batch.log_tau selects the
+ * relaxed test and hsd_batch.tree_end a packed prefix tree per sequence), and the bonus token of Eq. 12.
  * Stage 1 (many short region drafts verified together, Eq. 2) and Stage 2 (one long page draft, Eq. 4)
  * are the same operator on different shapes, hence two entry points with one semantic definition.
  *
@@ -164,6 +165,9 @@ int hsd_kv_pool_init(void *stream, const hsd_kv_pool *pool);
  * (writing their ids into block_table), appends the keys/values of ALL q_len rows there
  * (speculatively), computes argmax for every row, then alpha = number of leading draft tokens with
  * tokens[base+i] == argmax[base+i-1], and bonus = argmax[base+alpha] (Eq. 9-12, exact match).
+ * With batch.log_tau < 0 a draft token is accepted iff its logit is within -log_tau of its parent row's
+ * largest (Eq. 11); with batch.tree_end the block is a packed prefix tree, rows see their ancestors only,
+ * and the walk descends from the root through the admissible child (see hsd_batch).
  * seq_len is not modified: call hsd_kv_commit_rollback afterwards. */
 int hsd_verify_region_batch(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch,
                             void *workspace, size_t ws_bytes);
@@ -179,7 +183,9 @@ int hsd_verify_page(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const h
  * pending_out[s] = bonus[s].  With alpha < 0: pure rollback, seq_len and pending_out[s] unchanged.
  * In both cases blocks lying wholly beyond the new length go back to the pool and their
  * block_table slots become -1; rejected rows inside the last kept block are simply overwritten by
- * the next round.  pending_out: dev [n_seq] or NULL. */
+ * the next round.  For a packed prefix tree (batch.tree_end) the accepted path's keys/values are first
+ * moved from their pre-order slots to the contiguous slots seq_len+1 .. seq_len+alpha (needs
+ * batch.stop_row as written by the verify call).  pending_out: dev [n_seq] or NULL. */
 int hsd_kv_commit_rollback(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch,
                            int32_t *pending_out);
 
