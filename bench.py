@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--tau", type=float, default=1.0,
                     help="acceptance threshold of the relaxed rule (paper default 0.75); 1.0 = exact greedy match, "
                          "the rule the headline metric is defined on")
+    ap.add_argument("--attn-key-chunk", type=int, default=0,
+                    help="attention key split (hsd_model_desc.attn_key_chunk): keys per chunk, 0 = unsplit")
     ap.add_argument("--breakdown", action="store_true",
                     help="after the timed region, time every kernel class in turn (extra steps) and report avg us per launch")
     args = ap.parse_args()
@@ -107,7 +109,8 @@ def main():
     maxb = max((sp.n_visual + sp.n_prompt + k_max + 1 + 15) // 16 + 1 for sp in specs)
     n_blocks = sum((sp.n_visual + sp.n_prompt + k_max + 1 + 15) // 16 + 1 for sp in specs) + 8
     total_q = sum(sp.draft_len + 1 for sp in specs)
-    eng = Engine(desc, weights, n_blocks, n, maxb, max(total_q, 4096), max_dump=0 if args.random_target else total_q)
+    eng = Engine(desc, weights, n_blocks, n, maxb, max(total_q, 4096), max_dump=0 if args.random_target else total_q,
+                 attn_key_chunk=args.attn_key_chunk)
     slots = list(range(n))
 
     toks, embs, pend = [], [], []

@@ -63,6 +63,16 @@ typedef struct hsd_model_desc {
   int32_t dtype; /* HSD_BF16 or HSD_FP32: storage type of weights, KV cache and GEMM operands */
   int32_t kv_block_tokens;
   float rms_eps, rope_theta;
+  /* Attention key split (bf16 models; a deployment choice, not part of the architecture).  0: every query tile
+   * walks all of its keys in one workgroup.  c > 0 (a multiple of 64): the keys of a sequence are cut at the
+   * absolute positions c, 2c, ... (at most 8 chunks; the last is open ended), each chunk is scored by a workgroup
+   * of its own and the chunks of a row are folded in ascending order.  Gives short, wide batches (region-level
+   * drafts over ~1k cached tokens: c = 512) and single long drafts (c = 1024) the parallelism to fill the chip;
+   * costs 264 bytes of workspace traffic per (row, head, chunk), so leave it 0 for many long sequences.  The cut
+   * points depend on positions only: results stay independent of the batch; against c = 0 they differ in
+   * rounding (the grouping of the fp32 sums).  When set, hsd_workspace_bytes grows by 8 * n_q_heads * 264 bytes
+   * per row. */
+  int32_t attn_key_chunk;
 } hsd_model_desc;
 
 /* Weights.  The per-layer members are HOST arrays of n_layers device pointers (copied by hsd_create). */

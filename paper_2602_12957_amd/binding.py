@@ -27,7 +27,8 @@ i32, f32, vp = C.c_int32, C.c_float, C.c_void_p
 
 class hsd_model_desc(C.Structure):
     _fields_ = [(n, i32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab",
-                                   "dtype", "kv_block_tokens")] + [("rms_eps", f32), ("rope_theta", f32)]
+                                   "dtype", "kv_block_tokens")] + [("rms_eps", f32), ("rope_theta", f32),
+                                                                       ("attn_key_chunk", i32)]
 
 
 class hsd_weights(C.Structure):

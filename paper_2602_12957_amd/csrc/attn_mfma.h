@@ -47,6 +47,21 @@ __global__ void __launch_bounds__(1024) k_attn_tiles(int n_seq, const int32_t *_
   if (threadIdx.x == 0) tile_cu[n_seq] = total;
 }
 
+// Key split.  With `chunk_keys` > 0 the keys of every sequence are cut at the absolute positions chunk_keys,
+// 2*chunk_keys, ... (a multiple of the 64-key tile; chunk kAttnMaxChunks - 1 is open ended) and each chunk of a
+// query tile goes to a workgroup of its own (grid z), which leaves its un-normalised (max, sum, O^T) in `part_*`;
+// k_attn_merge folds the chunks of a row in ascending order.  The cut points depend on absolute positions only,
+// never on the batch, so a row gets the same bits whether it is scored in a long block or alone; what changes
+// against the unsplit kernel is the grouping of the fp32 sums, i.e. rounding.
+// Short contexts with few query tiles (region-level drafts) gain the workgroups they need to fill the chip; the
+// price is 264 bytes written and read again per (row, head, chunk).
+constexpr int kAttnMaxChunks = 8;
+struct AttnSplit {
+  int chunk_keys, total_q;
+  float *part_o;     // [kAttnMaxChunks][n_q_heads][total_q][64] un-normalised O rows
+  float2 *part_ml;   // [kAttnMaxChunks][n_q_heads][total_q] (integer reference point, sum)
+};
+
 union Frag8 {
   uint4 u;
   bf16x8 v;
@@ -61,15 +76,16 @@ union Frag8 {
 // the end, always in the same order, so results do not depend on timing.  Fewer query sets per workgroup mean
 // more, smaller workgroups (finer load balance over the CUs) at the price of staging each K/V tile more often.
 // TREE selects the tree-ancestry mask (row_end = packed index one past each row's subtree) instead of the causal one.
-// grid: (upper bound of query tiles, n_kv_heads * ceil(group / G4)), block 64*QS*KQ, dynamic LDS
+// SPLIT: grid z = key chunk (see AttnSplit); results go to the partial buffers instead of `out`.
+// grid: (upper bound of query tiles, n_kv_heads * ceil(group / G4), chunks), block 64*QS*KQ, dynamic LDS
 // attn_smem_bytes(KQ, QS).
-template <int G4, int KQ, int QS, bool TREE>
+template <int G4, int KQ, int QS, bool TREE, bool SPLIT>
 __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_heads, const int32_t *__restrict__ cu_q,
                                                    const int32_t *__restrict__ seq_slot, int n_slots,
                                                    const int32_t *__restrict__ seq_len,
                                                    const int32_t *__restrict__ tile_cu, PagedKV kv,
                                                    const bf16 *__restrict__ q, bf16 *__restrict__ out,
-                                                   const int32_t *__restrict__ row_end) {
+                                                   const int32_t *__restrict__ row_end, AttnSplit sp) {
   constexpr int kAttnKeys = 32 * KQ, kAttnStage = attn_stage_elems(KQ);
   // threads; 16-byte K (and V) pieces staged per thread and tile (with 8 query sets only the first 256*KQ threads stage)
   constexpr int NT = 64 * QS * KQ, NS = QS >= 4 ? 1 : 4 / QS;
@@ -101,7 +117,14 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
   const int wave_keys = S + min(row0 + 32, Lq);                    // keys any query of this wave can see
   const int wg_keys = S + min(tile_in_seq * QT + QT, Lq);          // ... of this workgroup
   const int n_valid = S + Lq;                                      // positions holding data of this round
-  const int n_tiles = (wg_keys + kAttnKeys - 1) / kAttnKeys;
+  // tiles kt0 .. kt1-1 of 32*KQ keys are this workgroup's
+  int key_lo = 0, key_hi = wg_keys;
+  if constexpr (SPLIT) {
+    key_lo = static_cast<int>(blockIdx.z) * sp.chunk_keys;
+    if (key_lo >= wg_keys) return;  // uniform for the whole workgroup: no query of the tile reaches this chunk
+    if (blockIdx.z + 1 < kAttnMaxChunks) key_hi = min(wg_keys, key_lo + sp.chunk_keys);
+  }
+  const int kt0 = key_lo / kAttnKeys, kt1 = (key_hi + kAttnKeys - 1) / kAttnKeys;
   const int qdim = n_q_heads * kHd;
 
   // ---- query fragments (B operand of S^T): lane holds dims 16*kk + 8*half .. +7 of its query
@@ -187,21 +210,21 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
   // the staging registers (tile kt+1, requested one whole iteration earlier, so long since arrived) were written to
   // the LDS stage that iteration kt-1 finished reading.  No wave ever waits for a load it has just issued, and the
   // LDS stores run ahead of the tile's arithmetic instead of between it and the barrier.
-  fetch_id(0);
+  fetch_id(kt0);
   prefetch();
-  if (n_tiles > 1) fetch_id(1);
-  store_lds(0, 0);
-  if (n_tiles > 1) {
+  if (kt0 + 1 < kt1) fetch_id(kt0 + 1);
+  store_lds(kt0 & 1, kt0);
+  if (kt0 + 1 < kt1) {
     prefetch();
-    if (n_tiles > 2) fetch_id(2);
+    if (kt0 + 2 < kt1) fetch_id(kt0 + 2);
   }
   __syncthreads();
-  for (int kt = 0; kt < n_tiles; ++kt) {
-    if (kt + 1 < n_tiles) {
+  for (int kt = kt0; kt < kt1; ++kt) {
+    if (kt + 1 < kt1) {
       store_lds((kt + 1) & 1, kt + 1);
-      if (kt + 2 < n_tiles) {
+      if (kt + 2 < kt1) {
         prefetch();
-        if (kt + 3 < n_tiles) fetch_id(kt + 3);
+        if (kt + 3 < kt1) fetch_id(kt + 3);
       }
     }
     const int kb = kt * kAttnKeys + kh * 32;   // first key of this wave's half tile
@@ -304,8 +327,10 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
     for (int part = 1; part < KQ; ++part) {
       const float *src = mrg + ((part - 1) * QS + wq) * 34 * 64 + lane;
       const float m_b = src[32 * 64], l_b = src[33 * 64];
-      const float m_tot = fmaxf(m_run, m_b);            // finite: key 0 belongs to part 0 of the first tile
-      const float ca = ldexpf(1.0f, static_cast<int>(m_run - m_tot));   // integer exponents: exact powers of two
+      // integer exponents: exact powers of two.  Unsplit, part 0 is never empty (key 0 is in its first tile); a
+      // chunk of a split pass may hold no visible key for a row in either part
+      const float m_tot = fmaxf(m_run, m_b);
+      const float ca = (m_run > -INFINITY) ? ldexpf(1.0f, static_cast<int>(m_run - m_tot)) : 0.f;
       const float cb = (m_b > -INFINITY) ? ldexpf(1.0f, static_cast<int>(m_b - m_tot)) : 0.f;
       l_run = l_run * ca + l_b * cb;
       m_run = m_tot;
@@ -314,18 +339,66 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[i][v] = o[i][v] * ca + src[(i * 16 + v) * 64] * cb;
     }
-    const float inv = 1.0f / l_run;
-    bf16 *op = out + static_cast<size_t>(base + row0 + qj) * qdim + head * kHd;
+    if constexpr (SPLIT) {
+      const size_t rh = (static_cast<size_t>(blockIdx.z) * n_q_heads + head) * sp.total_q + base + row0 + qj;
+      float *po = sp.part_o + rh * kHd;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        floatx4 ov;
+        for (int g = 0; g < 4; ++g) {
+          floatx4 ov;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) ov[e] = o[i][4 * g + e] * inv;
-        *reinterpret_cast<bf16x4 *>(op + i * 32 + 8 * g + 4 * half) = __builtin_convertvector(ov, bf16x4);
-      }
+          for (int e = 0; e < 4; ++e) ov[e] = o[i][4 * g + e];
+          *reinterpret_cast<floatx4 *>(po + i * 32 + 8 * g + 4 * half) = ov;
+        }
+      if (half == 0) sp.part_ml[rh] = make_float2(m_run, l_run);
+    } else {
+      const float inv = 1.0f / l_run;
+      bf16 *op = out + static_cast<size_t>(base + row0 + qj) * qdim + head * kHd;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          floatx4 ov;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ov[e] = o[i][4 * g + e] * inv;
+          *reinterpret_cast<bf16x4 *>(op + i * 32 + 8 * g + 4 * half) = __builtin_convertvector(ov, bf16x4);
+        }
+    }
   }
+}
+
+// Folds the key chunks of a split pass: row r (cache slot row_slot[r]) has chunks 0 .. min(kAttnMaxChunks - 1,
+// slot / chunk_keys), merged in ascending order with exact power-of-two factors, then normalised.
+// One thread per (head, row, 4 dims); grid ceil(n_q_heads * total_q * 16 / 256), block 256.
+__global__ void __launch_bounds__(256) k_attn_merge(int n_q_heads, const int32_t *__restrict__ row_slot, AttnSplit sp,
+                                                    bf16 *__restrict__ out) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int rh = idx >> 4, piece = idx & 15;            // rh = head * total_q + row
+  if (rh >= n_q_heads * sp.total_q) return;
+  const int head = rh / sp.total_q, row = rh - head * sp.total_q;
+  const int nc = min(kAttnMaxChunks, row_slot[row] / sp.chunk_keys + 1);
+  const size_t cstride = static_cast<size_t>(n_q_heads) * sp.total_q;
+  float2 ml = sp.part_ml[rh];
+  floatx4 o = *reinterpret_cast<const floatx4 *>(sp.part_o + static_cast<size_t>(rh) * kHd + piece * 4);
+  float m_run = ml.x, l_run = ml.y;
+  for (int c = 1; c < nc; ++c) {
+    const float2 b = sp.part_ml[c * cstride + rh];
+    const floatx4 ob = *reinterpret_cast<const floatx4 *>(sp.part_o + (c * cstride + rh) * kHd + piece * 4);
+    const float m_tot = fmaxf(m_run, b.x);
+    const float ca = (m_run > -INFINITY) ? ldexpf(1.0f, static_cast<int>(m_run - m_tot)) : 0.f;
+    const float cb = (b.x > -INFINITY) ? ldexpf(1.0f, static_cast<int>(b.x - m_tot)) : 0.f;
+    l_run = l_run * ca + b.y * cb;
+    m_run = m_tot;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = o[e] * ca + ob[e] * cb;
+  }
+  const float inv = 1.0f / l_run;
+  floatx4 ov;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) ov[e] = o[e] * inv;
+  *reinterpret_cast<bf16x4 *>(out + static_cast<size_t>(row) * n_q_heads * kHd + head * kHd + piece * 4) =
+      __builtin_convertvector(ov, bf16x4);
 }
 
 }  // namespace hsd

@@ -56,6 +56,8 @@ struct Workspace {
   float2 *rope_cs;
   Top2 *lm_part;
   float *part;  // split-K partial sums of the O / down projections
+  float *attn_part_o;    // key-split attention: un-normalised partial rows and their (reference point, sum)
+  float2 *attn_part_ml;
   size_t total;
 };
 
@@ -101,6 +103,9 @@ Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
   w.lm_part = reinterpret_cast<Top2 *>(take(T * (d.vocab / 64) * sizeof(Top2)));
   const int64_t part_rows = T < split_row_limit(d) ? T : split_row_limit(d);
   w.part = reinterpret_cast<float *>(take(d.dtype == HSD_BF16 ? kMaxChunks * part_rows * d.d_model * sizeof(float) : 0));
+  const size_t split_rh = (d.dtype == HSD_BF16 && d.attn_key_chunk > 0) ? kAttnMaxChunks * T * d.n_q_heads : 0;
+  w.attn_part_o = reinterpret_cast<float *>(take(split_rh * d.head_dim * sizeof(float)));
+  w.attn_part_ml = reinterpret_cast<float2 *>(take(split_rh * sizeof(float2)));
   w.total = off;
   return w;
 }
@@ -285,19 +290,35 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
         hipLaunchKernelGGL(k_attn_tiles, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, q_tile, ws.tile_cu);
         HSD_LAUNCH_CHECK();
       }
-#define HSD_ATTN_LAUNCH(G4, KQ, QS, TREE)                                                                        \
+      // Key split (desc.attn_key_chunk > 0): one workgroup per (query tile, chunk of keys); no sequence can hold
+      // more keys than its block-table row addresses, which bounds the chunks worth launching.
+      const int chunk = d.attn_key_chunk;
+      int n_chunks = 1;
+      if (chunk > 0) {
+        const int64_t max_keys = static_cast<int64_t>(b->max_blocks_per_seq) * HSD_KV_BLOCK_TOKENS;
+        n_chunks = static_cast<int>(std::min<int64_t>(kAttnMaxChunks, (max_keys + chunk - 1) / chunk));
+      }
+      const dim3 grid_z(grid.x, grid.y, n_chunks);
+      const AttnSplit sp{chunk, b->total_q, ws.attn_part_o, ws.attn_part_ml};
+#define HSD_ATTN_LAUNCH1(G4, KQ, QS, TREE, SPLIT)                                                                \
   {                                                                                                              \
     constexpr size_t smem = attn_smem_bytes(KQ, QS);                                                             \
     static bool attr_done = false;                                                                               \
     if (!attr_done) {                                                                                            \
-      if (smem > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void *>(k_attn_mfma<G4, KQ, QS, TREE>), \
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) \
+      if (smem > 48 * 1024 &&                                                                                    \
+          hipFuncSetAttribute(reinterpret_cast<const void *>(k_attn_mfma<G4, KQ, QS, TREE, SPLIT>),              \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)                   \
         return HSD_EHIP;                                                                                         \
       attr_done = true;                                                                                          \
     }                                                                                                            \
-    hipLaunchKernelGGL((k_attn_mfma<G4, KQ, QS, TREE>), grid, dim3(64 * QS * KQ), smem, st, b->n_seq,            \
+    hipLaunchKernelGGL((k_attn_mfma<G4, KQ, QS, TREE, SPLIT>), grid_z, dim3(64 * QS * KQ), smem, st, b->n_seq,   \
                        d.n_q_heads, b->cu_q, b->seq_slot, b->n_slots, b->seq_len, ws.tile_cu, kv, q, o,          \
-                       meta.row_end);                                                                            \
+                       meta.row_end, sp);                                                                        \
+  }
+#define HSD_ATTN_LAUNCH(G4, KQ, QS, TREE)                      \
+  {                                                            \
+    if (chunk > 0) HSD_ATTN_LAUNCH1(G4, KQ, QS, TREE, true)    \
+    else HSD_ATTN_LAUNCH1(G4, KQ, QS, TREE, false)             \
   }
       const bool tree = meta.row_end != nullptr;
       if (g4 == 4 && tree) HSD_ATTN_LAUNCH(4, 2, 4, true)
@@ -307,7 +328,14 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
       else if (tree) HSD_ATTN_LAUNCH(1, 2, 4, true)
       else HSD_ATTN_LAUNCH(1, 2, 4, false)
 #undef HSD_ATTN_LAUNCH
+#undef HSD_ATTN_LAUNCH1
       HSD_LAUNCH_CHECK();
+      if (chunk > 0) {
+        const int64_t n_thr = static_cast<int64_t>(d.n_q_heads) * b->total_q * 16;
+        hipLaunchKernelGGL(k_attn_merge, dim3(static_cast<unsigned>((n_thr + 255) / 256)), dim3(256), 0, st,
+                           d.n_q_heads, meta.row_slot, sp, o);
+        HSD_LAUNCH_CHECK();
+      }
       return HSD_OK;
     }
   }
@@ -488,6 +516,7 @@ int hsd_validate_model(const hsd_model_desc *d) {
   if (d->n_q_heads % d->n_kv_heads != 0) return HSD_EINVAL;
   if (d->d_model % 128 != 0 || d->d_ffn % 128 != 0 || d->vocab % 128 != 0) return HSD_EINVAL;
   if (!(d->rms_eps > 0.f) || !(d->rope_theta > 1.f)) return HSD_EINVAL;
+  if (d->attn_key_chunk < 0 || d->attn_key_chunk % 64 != 0) return HSD_EINVAL;
   if (d->n_layers > 1024 || d->n_q_heads > 1024) return HSD_ERANGE;
   return HSD_OK;
 }

@@ -8,6 +8,7 @@ forward, arg-max, acceptance and KV maintenance all run inside libhsd.so.
 from __future__ import annotations
 
 import ctypes as C
+import os
 from dataclasses import dataclass
 from typing import List, Optional, Sequence
 
@@ -85,7 +86,7 @@ class VerifyOutput:
 
 class Engine:
     def __init__(self, desc, weights: dict, n_blocks: int, n_slots: int, max_blocks_per_seq: int,
-                 max_total_q: int, max_dump: int = 0, device: str = "cuda:0"):
+                 max_total_q: int, max_dump: int = 0, device: str = "cuda:0", attn_key_chunk: Optional[int] = None):
         if not torch.cuda.is_available():
             raise RuntimeError("the HSD verification path needs a GPU (MI355X); there is no CPU fallback")
         self.dev = torch.device(device)
@@ -93,7 +94,12 @@ class Engine:
         self.bf16 = desc.dtype == "bf16"
         self.cdesc = B.hsd_model_desc(desc.n_layers, desc.d_model, desc.n_q_heads, desc.n_kv_heads, desc.head_dim,
                                       desc.d_ffn, desc.vocab, B.HSD_BF16 if self.bf16 else B.HSD_FP32,
-                                      desc.kv_block_tokens, desc.rms_eps, desc.rope_theta)
+                                      desc.kv_block_tokens, desc.rms_eps, desc.rope_theta, 0)
+        # attention key split (hsd_model_desc.attn_key_chunk); HSD_ATTN_KEY_CHUNK sets it for engines that do not
+        # choose (used to run whole test suites with the split on)
+        if attn_key_chunk is None:
+            attn_key_chunk = int(os.environ.get("HSD_ATTN_KEY_CHUNK", "0"))
+        self.cdesc.attn_key_chunk = attn_key_chunk
         code = B.hsd_validate_model(self.cdesc)
         B.check("hsd_validate_model", code)
         self.desc = desc

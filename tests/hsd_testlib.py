@@ -19,7 +19,7 @@ def blocks_needed(specs, extra=4, uniform_len=False):
     return sum((s.n_visual + s.n_prompt + (k_max if uniform_len else s.draft_len) + 1 + 15) // 16 + 1 for s in specs) + extra
 
 
-def make_engine(desc, weights, specs, max_total_q=None, max_dump=0, n_blocks=None):
+def make_engine(desc, weights, specs, max_total_q=None, max_dump=0, n_blocks=None, attn_key_chunk=None):
     """Engine sized for the given sequences.  The pool and block tables leave room for every sequence to grow by
     the LONGEST draft length (Engine.greedy_decode advances all sequences in lock step)."""
     from paper_2602_12957_amd.runtime import Engine
@@ -29,7 +29,8 @@ def make_engine(desc, weights, specs, max_total_q=None, max_dump=0, n_blocks=Non
     n_blocks = n_blocks or blocks_needed(specs, uniform_len=True)
     if max_total_q is None:
         max_total_q = max(sum(s.draft_len + 1 for s in specs), max(s.n_visual + s.n_prompt for s in specs))
-    return Engine(desc, weights, n_blocks or blocks_needed(specs), n, maxb, max_total_q, max_dump)
+    return Engine(desc, weights, n_blocks or blocks_needed(specs), n, maxb, max_total_q, max_dump,
+                  attn_key_chunk=attn_key_chunk)
 
 
 def prefix_rows(desc, seed, spec):

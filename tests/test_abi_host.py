@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _desc(**kw):
     base = dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, d_ffn=1024, vocab=4096,
-                dtype=B.HSD_FP32, kv_block_tokens=16, rms_eps=1e-6, rope_theta=10000.0)
+                dtype=B.HSD_FP32, kv_block_tokens=16, rms_eps=1e-6, rope_theta=10000.0, attn_key_chunk=0)
     base.update(kw)
     return B.hsd_model_desc(*[base[n] for n, _ in B.hsd_model_desc._fields_])
 
@@ -39,6 +39,7 @@ def test_status_strings():
     ({"n_q_heads": 6, "n_kv_heads": 4}, B.HSD_EINVAL), ({"d_model": 200}, B.HSD_EINVAL),
     ({"vocab": 1000}, B.HSD_EINVAL), ({"n_layers": 0}, B.HSD_EINVAL), ({"rms_eps": 0.0}, B.HSD_EINVAL),
     ({"n_layers": 5000}, B.HSD_ERANGE),
+    ({"attn_key_chunk": 512}, B.HSD_OK), ({"attn_key_chunk": 100}, B.HSD_EINVAL), ({"attn_key_chunk": -64}, B.HSD_EINVAL),
 ])
 def test_validate_model(kw, code):
     assert B.hsd_validate_model(_desc(**kw)) == code
@@ -60,6 +61,14 @@ def _pool(**kw):
     for k, v in kw.items():
         setattr(p, k, v)
     return p
+
+
+def test_workspace_grows_with_key_split():
+    """The key-split attention keeps 8 partial records of 264 bytes per (row, head); bf16 models only."""
+    plain = B.hsd_workspace_bytes(_desc(dtype=B.HSD_BF16), 1000, 4)
+    split = B.hsd_workspace_bytes(_desc(dtype=B.HSD_BF16, attn_key_chunk=512), 1000, 4)
+    assert 8 * 1000 * 4 * 264 <= split - plain <= 8 * 1000 * 4 * 264 + 1024
+    assert B.hsd_workspace_bytes(_desc(attn_key_chunk=512), 1000, 4) == B.hsd_workspace_bytes(_desc(), 1000, 4)
 
 
 def test_validate_batch():

@@ -20,10 +20,11 @@ from hsd_testlib import make_engine, prefix_rows
 pytestmark = pytest.mark.gpu
 
 
-def _lossless(desc, specs, seed, mode):
+def _lossless(desc, specs, seed, mode, attn_key_chunk=None):
     weights = W.make_weights(desc, seed)
     n = len(specs)
-    eng = make_engine(desc, weights, specs, max_total_q=max(sum(s.draft_len + 1 for s in specs), 4096))
+    eng = make_engine(desc, weights, specs, max_total_q=max(sum(s.draft_len + 1 for s in specs), 4096),
+                      attn_key_chunk=attn_key_chunk)
     toks, embs, pend = [], [], []
     for sp in specs:
         _, _, tok, emb, pending = prefix_rows(desc, seed, sp)
@@ -76,6 +77,17 @@ def test_lossless_small_models(mode):
         specs = [SequenceSpec(0, 40, 3, 90, 0.1), SequenceSpec(1, 5, 2, 70, 0.3), SequenceSpec(2, 130, 5, 33, 0.0),
                  SequenceSpec(3, 0, 4, 150, 0.05)]
         assert _lossless(desc, specs, 11, mode) >= 2
+
+
+def test_lossless_with_attention_key_split():
+    """The key split cuts at absolute positions, so a row's bits still do not depend on the block it is scored in:
+    verification and token-by-token decoding agree exactly with the split on (64-key chunks on a small model; the
+    page-level configuration with the 1024-key chunks that suit it)."""
+    specs = [SequenceSpec(0, 40, 3, 90, 0.1), SequenceSpec(1, 5, 2, 70, 0.3), SequenceSpec(2, 130, 5, 33, 0.0),
+             SequenceSpec(3, 0, 4, 150, 0.05)]
+    assert _lossless(W.ModelDesc(3, 256, 8, 2, 64, 512, 1024, "bf16"), specs, 12, "region", attn_key_chunk=64) >= 2
+    rounds = _lossless(W.MODEL_M, W.draw_sequences(2, W.SEED_BASE), W.SEED_BASE, "page", attn_key_chunk=1024)
+    print("cfg2 lossless rounds with 1024-key chunks", rounds)
 
 
 def test_lossless_config1_model_m():

@@ -38,13 +38,13 @@ def _gpu_prefill(eng, desc, seed, specs):
     return pend
 
 
-def run_rounds_parity(desc, weights, seed, specs, drafts, mode="region", check_logits=True):
+def run_rounds_parity(desc, weights, seed, specs, drafts, mode="region", check_logits=True, attn_key_chunk=None):
     """Runs verification rounds to completion on both sides, teacher-forcing the GPU to the oracle's state
     after each round, and compares every output of every round."""
     n = len(specs)
     total_q = sum(len(d) + 1 for d in drafts)
     eng = make_engine(desc, weights, specs, max_total_q=max(total_q, max(s.n_visual + s.n_prompt for s in specs)),
-                      max_dump=total_q if check_logits else 0)
+                      max_dump=total_q if check_logits else 0, attn_key_chunk=attn_key_chunk)
     ora = _oracle_state(desc, weights, seed, specs)
     pend = _gpu_prefill(eng, desc, seed, specs)
     assert pend == [o[1] for o in ora]
@@ -150,6 +150,48 @@ def test_ragged_batch_rounds(desc, mode):
     stats = run_rounds_parity(desc, weights, seed, specs, drafts, mode=mode)
     print(desc.dtype, mode, stats)
     assert stats["gated_rows"] < 0.5 * stats["rows"]
+
+
+@pytest.mark.parametrize("chunk", [64, 128])
+def test_key_split_attention_rounds(chunk):
+    """The same rounds against the oracle with the attention keys cut into chunks (hsd_model_desc.attn_key_chunk):
+    contexts of 4 to 283 tokens give rows with one to five chunks, query tiles whose rows see different numbers of
+    chunks, and chunks that hold no visible key for some rows of a tile."""
+    desc, seed = SMALL_BF16, 78
+    weights = W.make_weights(desc, seed)
+    shapes = [(40, 3, 1), (5, 2, 70), (130, 5, 131), (61, 3, 64), (64, 8, 200), (0, 4, 66), (33, 0, 90)]
+    specs = [SequenceSpec(i, nv, npr, k, 0.0) for i, (nv, npr, k) in enumerate(shapes)]
+    targets = oracle_targets(desc, weights, seed, specs)
+    drafts = []
+    for (g, _), sp in zip(targets, specs):
+        d = g.copy()
+        if sp.seq_id % 2 and len(d) > 40:
+            d[37] = (d[37] + 1) % desc.vocab
+        drafts.append(d)
+    stats = run_rounds_parity(desc, weights, seed, specs, drafts, mode="region", attn_key_chunk=chunk)
+    print("key split", chunk, stats)
+    assert stats["gated_rows"] < 0.5 * stats["rows"]
+
+
+def test_key_split_last_chunk_is_open_ended():
+    """More keys than 8 chunks hold: the last chunk takes the rest (one pass against the oracle, 64-key chunks,
+    contexts up to 700 tokens), and the result agrees with the unsplit kernel to rounding."""
+    desc, seed = SMALL_BF16, 79
+    weights = W.make_weights(desc, seed)
+    specs = [SequenceSpec(0, 600, 4, 96, 0.0), SequenceSpec(1, 505, 2, 40, 0.0)]
+    rng = np.random.default_rng(5)
+    drafts = [rng.integers(0, desc.vocab, size=sp.draft_len).astype(np.int32) for sp in specs]
+    stats = run_rounds_parity(desc, weights, seed, specs, drafts, mode="page", attn_key_chunk=64)
+    print("key split open-ended", stats)
+    logits = []
+    for chunk in (0, 64):
+        eng = make_engine(desc, weights, specs, max_total_q=1024, max_dump=256, attn_key_chunk=chunk)
+        pend = _gpu_prefill(eng, desc, seed, specs)
+        blocks = [np.concatenate([[p], d]).astype(np.int32) for p, d in zip(pend, drafts)]
+        logits.append(_one_round(eng, [0, 1], blocks)[1])
+        eng.close()
+    diff = np.abs(logits[0].astype(np.float64) - logits[1])
+    assert diff.max() > 0 and np.sqrt((diff ** 2).mean()) < 2e-2, (diff.max(), np.sqrt((diff ** 2).mean()))
 
 
 def test_greedy_decode_matches_oracle_fp32():

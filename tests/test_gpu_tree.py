@@ -60,10 +60,10 @@ def _walk(argmax, tokens, end, gap, want, log_tau):
     return alpha, int(argmax[s]), s
 
 
-@pytest.mark.parametrize("desc", [FP32, BF16], ids=["fp32", "bf16"])
+@pytest.mark.parametrize("desc,chunk", [(FP32, None), (BF16, None), (BF16, 64)], ids=["fp32", "bf16", "bf16-keysplit64"])
 @pytest.mark.parametrize("log_tau", [0.0, math.log(0.75)], ids=["exact", "tau0.75"])
 @pytest.mark.parametrize("mode", ["region", "page"])
-def test_one_pass_over_packed_trees(desc, log_tau, mode):
+def test_one_pass_over_packed_trees(desc, chunk, log_tau, mode):
     from paper_2602_12957_amd.runtime import pack_prefix_tree
     seed = 61
     weights = W.make_weights(desc, seed)
@@ -92,7 +92,7 @@ def test_one_pass_over_packed_trees(desc, log_tau, mode):
         trees.append((e, d))
     total = sum(len(b) for b in blocks)
     sized = [SequenceSpec(sp.seq_id, sp.n_visual, sp.n_prompt, len(b), 0.0) for sp, b in zip(specs, blocks)]
-    eng = make_engine(desc, weights, sized, max_dump=total)
+    eng = make_engine(desc, weights, sized, max_dump=total, attn_key_chunk=chunk)
     toks, embs = [], []
     for sp in specs:
         _, _, tok, emb, _ = prefix_rows(desc, seed, sp)
