@@ -35,16 +35,44 @@ constexpr size_t attn_smem_bytes(int kq, int qs) {
   return stages > merge ? stages : merge;
 }
 
-// tile_cu[s] = number of query tiles of sequences < s, with q_tile rows per tile.  One block of 1024 threads.
-__global__ void __launch_bounds__(1024) k_attn_tiles(int n_seq, const int32_t *__restrict__ cu_q, int q_tile,
-                                                     int32_t *__restrict__ tile_cu) {
+// What a workgroup needs to know about its query tile, resolved once per pass instead of by every workgroup of
+// every layer (a binary search and four dependent reads before the first K/V request could go out).
+struct __attribute__((aligned(32))) AttnTile {
+  int32_t seq;          // batch index of the sequence, -1 past the last tile
+  int32_t tile_in_seq;  // index of the tile among the sequence's tiles
+  int32_t slot;         // state row (seq_len / block_table row)
+  int32_t S, base, Lq;  // cached length, first row and number of rows of the sequence's block
+  int32_t pad[2];
+};
+
+// tiles[t] for t < max_tiles (the grid's upper bound of query tiles), with q_tile rows per tile.  One block of 1024
+// threads; s_cnt is turned into the exclusive prefix of the tile counts.
+__global__ void __launch_bounds__(1024) k_attn_tiles(int n_seq, const int32_t *__restrict__ cu_q,
+                                                     const int32_t *__restrict__ seq_slot, int n_slots,
+                                                     const int32_t *__restrict__ seq_len, int q_tile, int max_tiles,
+                                                     AttnTile *__restrict__ tiles) {
   __shared__ int s_cnt[HSD_MAX_SEQ];
   __shared__ int s_part[1024];
   for (int s = threadIdx.x; s < n_seq; s += blockDim.x) s_cnt[s] = (cu_q[s + 1] - cu_q[s] + q_tile - 1) / q_tile;
   __syncthreads();
-  int total = block_exclusive_scan_4096(s_cnt, n_seq, s_part);
-  for (int s = threadIdx.x; s < n_seq; s += blockDim.x) tile_cu[s] = s_cnt[s];
-  if (threadIdx.x == 0) tile_cu[n_seq] = total;
+  const int total = block_exclusive_scan_4096(s_cnt, n_seq, s_part);
+  for (int t = threadIdx.x; t < max_tiles; t += blockDim.x) {
+    AttnTile d{-1, 0, 0, 0, 0, 0, {0, 0}};
+    if (t < total) {
+      int lo = 0, hi = n_seq - 1;   // last sequence whose first tile is <= t (every sequence has at least one row)
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (s_cnt[mid] <= t) lo = mid; else hi = mid - 1;
+      }
+      d.seq = lo;
+      d.tile_in_seq = t - s_cnt[lo];
+      d.slot = slot_of(seq_slot, lo, n_slots);
+      d.S = seq_len[d.slot];
+      d.base = cu_q[lo];
+      d.Lq = cu_q[lo + 1] - d.base;
+    }
+    tiles[t] = d;
+  }
 }
 
 // Key split.  With `chunk_keys` > 0 the keys of every sequence are cut at the absolute positions chunk_keys,
@@ -80,10 +108,7 @@ union Frag8 {
 // grid: (upper bound of query tiles, n_kv_heads * ceil(group / G4), chunks), block 64*QS*KQ, dynamic LDS
 // attn_smem_bytes(KQ, QS).
 template <int G4, int KQ, int QS, bool TREE, bool SPLIT>
-__global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_heads, const int32_t *__restrict__ cu_q,
-                                                   const int32_t *__restrict__ seq_slot, int n_slots,
-                                                   const int32_t *__restrict__ seq_len,
-                                                   const int32_t *__restrict__ tile_cu, PagedKV kv,
+__global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_q_heads, const AttnTile *__restrict__ tiles, PagedKV kv,
                                                    const bf16 *__restrict__ q, bf16 *__restrict__ out,
                                                    const int32_t *__restrict__ row_end, AttnSplit sp) {
   constexpr int kAttnKeys = 32 * KQ, kAttnStage = attn_stage_elems(KQ);
@@ -94,16 +119,13 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
   uint16_t *smem = reinterpret_cast<uint16_t *>(smem_raw);
   constexpr int SUB = QS / G4, QT = 32 * SUB;
 
-  const int tile = blockIdx.x;
-  if (tile >= tile_cu[n_seq]) return;  // uniform for the whole workgroup
-  int lo = 0, hi = n_seq - 1;
-  while (lo < hi) {
-    int mid = (lo + hi + 1) >> 1;
-    if (tile_cu[mid] <= tile) lo = mid; else hi = mid - 1;
-  }
-  const int s = lo, tile_in_seq = tile - tile_cu[s];
-  const int slot = slot_of(seq_slot, s, n_slots);
-  const int S = seq_len[slot], base = cu_q[s], Lq = cu_q[s + 1] - base;
+  // the tile's descriptor comes through the scalar unit in one read (constant address space: written by an
+  // earlier kernel, never during this one)
+  typedef const int32_t __attribute__((address_space(4))) *ConstI32;
+  const ConstI32 td = (ConstI32)(reinterpret_cast<const int32_t *>(tiles + blockIdx.x));
+  const int s = td[0];
+  if (s < 0) return;  // uniform for the whole workgroup
+  const int tile_in_seq = td[1], slot = td[2], S = td[3], base = td[4], Lq = td[5];
 
   const int group = n_q_heads / kv.n_kv_heads, hb = (group + G4 - 1) / G4;
   const int kvh = blockIdx.y / hb, hgrp = blockIdx.y % hb;
@@ -142,30 +164,34 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_seq, int n_q_h
   // of the data they address, so the K/V loads of the next tile never wait behind a dependent block-table read.
   u32x4 rk[NS], rv[NS];
   int bid[NS];
-  // fetch_id only ISSUES the block-table reads (the index is range-checked, the value is not looked at until the
-  // next iteration): examining the id here would stall the wave for a full memory latency every iteration
+  bool bid_ok[NS];
+  // The pages of a tile are uniform per wave (a wave stages half a page of K and of V^T), so their ids are read
+  // through the scalar unit (constant address space: the table is not written while this kernel runs) and the page
+  // offsets are scalar arithmetic.  fetch_id only ISSUES the read (index clamped to the table row; whether the
+  // entry means anything is settled without looking at it): examining the id here would stall the wave for a
+  // memory latency every iteration.
+  typedef const int32_t __attribute__((address_space(4))) *TablePtr;
+  const TablePtr table_row = (TablePtr)(kv.block_table + static_cast<size_t>(slot) * kv.max_blocks_per_seq);
   auto fetch_id = [&](int kt) {
     if (!stager) return;
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
-      const int p0 = kt * kAttnKeys + ((t + NT * i) >> 7) * kBlk;
-      const int bi = p0 / kBlk;
-      bid[i] = -1;
-      if (p0 < n_valid && bi < kv.max_blocks_per_seq)
-        bid[i] = kv.block_table[static_cast<size_t>(slot) * kv.max_blocks_per_seq + bi];
+      const int page = kt * (kAttnKeys / kBlk) + __builtin_amdgcn_readfirstlane((t + NT * i) >> 7);
+      bid_ok[i] = page * kBlk < n_valid && page < kv.max_blocks_per_seq;
+      bid[i] = table_row[min(page, kv.max_blocks_per_seq - 1)];
     }
   };
   // prefetch only ISSUES the loads; nothing here may depend on the loaded values, or the wave would wait for
   // them on the spot and the whole point of requesting a tile ahead would be lost
   auto prefetch = [&]() {
     if (!stager) return;
-    // unconditional loads: a page id that is absent (-1, beyond the data of this round) or out of range reads
-    // block 0 instead; such a page lies wholly past n_valid, so store_lds zeroes its V and the causal mask
-    // discards its scores.  A branch here would make the compiler wait for the loads inside it.
+    // unconditional loads: a page that is absent (beyond the data of this round, id out of range) reads block 0
+    // instead; such a page lies wholly past n_valid, so store_lds zeroes its V and the causal mask discards its
+    // scores.  A branch here would make the compiler wait for the loads inside it.
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
       const int c = t + NT * i;
-      const int b = (bid[i] >= 0 && bid[i] < kv.n_blocks) ? bid[i] : 0;
+      const int b = (bid_ok[i] && bid[i] >= 0 && bid[i] < kv.n_blocks) ? bid[i] : 0;
       const size_t off = kv_block_offset(kv, b, kvh);
       rk[i] = *reinterpret_cast<const u32x4 *>(kpool + off + ((c >> 3) & 15) * kHd + (c & 7) * 8);
       rv[i] = *reinterpret_cast<const u32x4 *>(vpool + off + ((c & 127) >> 1) * kBlk + (c & 1) * 8);

@@ -51,7 +51,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Workspace {
   float *x;
   void *h, *q, *a, *u;
-  int32_t *row_seq, *row_pos, *row_kv, *row_slot, *row_base, *row_end, *row_par, *dump_slot, *tile_cu;
+  int32_t *row_seq, *row_pos, *row_kv, *row_slot, *row_base, *row_end, *row_par, *dump_slot;
+  AttnTile *attn_tiles;
   float *want_logit, *row_max;
   float2 *rope_cs;
   Top2 *lm_part;
@@ -98,7 +99,7 @@ Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
   w.want_logit = reinterpret_cast<float *>(take(T * sizeof(float)));
   w.row_max = reinterpret_cast<float *>(take(T * sizeof(float)));
   w.dump_slot = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
-  w.tile_cu = reinterpret_cast<int32_t *>(take((n_seq + 1) * sizeof(int32_t)));
+  w.attn_tiles = reinterpret_cast<AttnTile *>(take((T / 32 + n_seq) * sizeof(AttnTile)));   // 32 = smallest query tile
   w.rope_cs = reinterpret_cast<float2 *>(take(T * 32 * sizeof(float2)));
   w.lm_part = reinterpret_cast<Top2 *>(take(T * (d.vocab / 64) * sizeof(Top2)));
   const int64_t part_rows = T < split_row_limit(d) ? T : split_row_limit(d);
@@ -287,7 +288,8 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
       const bf16 *q = static_cast<const bf16 *>(ws.q);
       bf16 *o = static_cast<bf16 *>(ws.a);
       if (kv.layer == 0) {  // the tile map depends on the batch only: built once per pass
-        hipLaunchKernelGGL(k_attn_tiles, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, q_tile, ws.tile_cu);
+        hipLaunchKernelGGL(k_attn_tiles, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, b->seq_slot, b->n_slots,
+                           b->seq_len, q_tile, max_tiles, ws.attn_tiles);
         HSD_LAUNCH_CHECK();
       }
       // Key split (desc.attn_key_chunk > 0): one workgroup per (query tile, chunk of keys); no sequence can hold
@@ -311,9 +313,8 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
         return HSD_EHIP;                                                                                         \
       attr_done = true;                                                                                          \
     }                                                                                                            \
-    hipLaunchKernelGGL((k_attn_mfma<G4, KQ, QS, TREE, SPLIT>), grid_z, dim3(64 * QS * KQ), smem, st, b->n_seq,   \
-                       d.n_q_heads, b->cu_q, b->seq_slot, b->n_slots, b->seq_len, ws.tile_cu, kv, q, o,          \
-                       meta.row_end, sp);                                                                        \
+    hipLaunchKernelGGL((k_attn_mfma<G4, KQ, QS, TREE, SPLIT>), grid_z, dim3(64 * QS * KQ), smem, st,             \
+                       d.n_q_heads, ws.attn_tiles, kv, q, o, meta.row_end, sp);                                  \
   }
 #define HSD_ATTN_LAUNCH(G4, KQ, QS, TREE)                      \
   {                                                            \
