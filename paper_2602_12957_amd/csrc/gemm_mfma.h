@@ -52,6 +52,16 @@ __device__ __forceinline__ void xcd_tile(int pid, int tiles_fast, int n_tiles, i
   t_slow = p / tiles_fast;
 }
 
+// Workgroup -> (activation tile, weight tile).  Workgroups go to the 8 XCDs round robin; xcd_tile gives each XCD
+// a contiguous run of the tile order, so the operand whose tile index is the SLOW one is fetched into one L2 only,
+// the other into all of them.  With few rows the weights are the big operand (each XCD takes a few weight tiles and
+// every activation tile); with many rows it is the activations (each XCD takes a band of rows and every weight
+// tile).  `w_rows` = rows of the weight matrix.
+__device__ __forceinline__ void gemm_tile_of(int pid, int M, int w_rows, int tiles_act, int tiles_w, int &ta, int &tw) {
+  if (M >= 4 * w_rows) xcd_tile(pid, tiles_w, tiles_act * tiles_w, tw, ta);
+  else xcd_tile(pid, tiles_act, tiles_act * tiles_w, ta, tw);
+}
+
 // Tile counts for (M, N) in a mode: activation tiles first, weight tiles second.
 template <typename Cfg, int MODE>
 __host__ __device__ inline void gemm_tiles(int M, int N, int &tiles_act, int &tiles_w) {
@@ -176,12 +186,12 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[Cfg::TM][Cfg::TN],
 // grid: 1-D, tiles_act * tiles_w workgroups of Cfg::kThreads threads, Cfg::kSmemBytes dynamic LDS.
 // N is the number of output columns (for dual mode the weight matrix has 2N rows: gate | up).
 //
-// K may be reduced in `k_chunks` equal chunks whose sums are added in chunk order (chunk 0 first).  With
-// gridDim.y == k_chunks each workgroup handles one chunk and hands its partial sum to the epilogue (split-K; the
-// caller adds the partials in chunk order); with gridDim.y == 1 the workgroup walks all chunks itself, restarting
-// its accumulators at every chunk boundary and adding chunk sums in the same order.  Both forms round identically,
-// so the choice between them (made from the number of tiles) never changes a result bit.
-// WALK_CHUNKS selects the second form at compile time (it needs a second set of accumulators).
+// K may be reduced in `k_chunks` equal chunks whose sums are added to the destination one after the other, chunk 0
+// first: out = ((out + P0) + P1) + ...  With gridDim.y == k_chunks each workgroup handles one chunk and hands its
+// partial sum to the epilogue (split-K; the caller adds the partials in that order); with gridDim.y == 1 the
+// workgroup walks all chunks itself, running the (read-modify-write) epilogue and restarting its accumulators at
+// every chunk boundary.  Both forms round identically, so the choice between them (made from the number of tiles)
+// never changes a result bit.  WALK_CHUNKS selects the second form at compile time.
 template <typename Cfg, int MODE, typename Epi, bool WALK_CHUNKS = false>
 __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K, int k_chunks,
                                                              const bf16 *__restrict__ A,
@@ -195,7 +205,7 @@ __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K
   const int wi = wave / Cfg::WN, wj = wave % Cfg::WN;
   int tiles_act, tiles_w, ta, tw;
   gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
-  xcd_tile(blockIdx.x, tiles_act, tiles_act * tiles_w, ta, tw);
+  gemm_tile_of(blockIdx.x, M, (MODE == kModeDual) ? 2 * N : N, tiles_act, tiles_w, ta, tw);
   // first activation row / first output column of this tile
   const int m0 = ta * ((MODE == kModeSwapLM) ? BQ : BP);
   const int n0 = tw * ((MODE == kModeSwapLM) ? BP : ((MODE == kModeDual) ? BQ / 2 : BQ));
@@ -245,7 +255,6 @@ __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K
   const int k_len = K / k_chunks, nk = k_len / BK;
   const bool split = gridDim.y > 1;
   const int c_begin = split ? blockIdx.y : 0, c_end = split ? blockIdx.y + 1 : k_chunks;
-  floatx16 tot[WALK_CHUNKS ? TM : 1][WALK_CHUNKS ? TN : 1];
 
 #define HSD_GEMM_LOAD(set, k0, h)                                                                   \
   _Pragma("unroll") for (int i = (h) * (Cfg::kLoadsP / 2); i < ((h) + 1) * (Cfg::kLoadsP / 2); ++i) \
@@ -319,30 +328,26 @@ __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K
       HSD_GEMM_ITER(kt, 0, 1, false, false)
     }
     if constexpr (WALK_CHUNKS) {
-      // chunk sums are added in chunk order; the first chunk initialises the total
+      // the chunk's sum goes to the destination now; the LDS stages double as the epilogue's staging area, so
+      // every wave must be through with it before the next chunk's first slice is written
+      gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(-1, M),
+                               reinterpret_cast<float *>(smem_raw));
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          tot[i][j] = (chunk == 0) ? acc[i][j] : tot[i][j] + acc[i][j];
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
           for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-        }
+      __syncthreads();
     }
   }  // chunk loop
 #undef HSD_GEMM_LOAD
 #undef HSD_GEMM_STORE
 #undef HSD_GEMM_KSTEP
 #undef HSD_GEMM_ITER
-  if constexpr (WALK_CHUNKS) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) acc[i][j] = tot[i][j];
-  }
-
-  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(split ? blockIdx.y : -1, M),
-                           reinterpret_cast<float *>(smem_raw));
+  if constexpr (!WALK_CHUNKS)
+    gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(split ? blockIdx.y : -1, M),
+                             reinterpret_cast<float *>(smem_raw));
 }
 
 }  // namespace hsd

@@ -164,7 +164,7 @@ int launch_gemm_mfma_impl(hipStream_t st, int M, int N, int K, const void *A, co
   return HSD_OK;
 }
 
-// k_chunks > 1 without split: the workgroup walks the chunks itself (kernel variant with a second accumulator set)
+// k_chunks > 1 without split: the workgroup walks the chunks itself (kernel variant with an epilogue per chunk)
 template <typename Cfg, typename Epi>
 int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks = 1,
                      bool split = false) {
@@ -174,11 +174,11 @@ int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const v
   return launch_gemm_mfma_impl<Cfg, Epi, false>(st, M, N, K, A, W, epi, k_chunks, split);
 }
 
-template <typename Epi>
-int launch_gemm_mfma8(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi) {
+template <typename Epi, bool WALK>
+int launch_gemm_mfma8_impl(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks) {
   constexpr int MODE = GemmModeOf<Epi>::value;
   using Cfg = GemmCfg8;
-  auto kern = k_gemm_mfma8<MODE, Epi>;
+  auto kern = k_gemm_mfma8<MODE, Epi, WALK>;
   constexpr int smem = Cfg::kSmemBytes;
   static bool attr_done = false;
   if (!attr_done) {
@@ -190,10 +190,20 @@ int launch_gemm_mfma8(hipStream_t st, int M, int N, int K, const void *A, const 
   if constexpr (MODE == kModeSwapLM) epi.n_tiles = (N / Cfg::BP) * Cfg::WM;
   int tiles_act, tiles_w;
   gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
-  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(512), smem, st, M, N, K, static_cast<const bf16 *>(A),
-                     static_cast<const bf16 *>(W), epi);
+  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(512), smem, st, M, N, K, k_chunks,
+                     static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), epi);
   HSD_LAUNCH_CHECK();
   return HSD_OK;
+}
+
+// k_chunks > 1: the workgroup walks the chunks itself (read-modify-write epilogues only)
+template <typename Epi>
+int launch_gemm_mfma8(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks) {
+  if constexpr (Epi::kChunked) {
+    if (k_chunks > 1) return launch_gemm_mfma8_impl<Epi, true>(st, M, N, K, A, W, epi, k_chunks);
+  }
+  if (k_chunks > 1) return HSD_EINVAL;
+  return launch_gemm_mfma8_impl<Epi, false>(st, M, N, K, A, W, epi, 1);
 }
 
 // Tile configurations of the MFMA GEMM (HSD_GEMM_CFG selects one for experiments; default per call site).
@@ -209,7 +219,7 @@ using GemmCfg5 = GemmCfg<128, 128, 64, 4, 2>;   // 8 waves, wave tile 32x64
 // Tile configuration actually used at a call site for a given problem (the launch and everything sized from the
 // tile shape, like the LM-head partial records, must agree on it).  -1 = plain kernels.
 template <typename T>
-int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_chunks) {
+int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_chunks, bool split) {
   if (!std::is_same<T, bf16>::value || ctx->force_simple || K % 64 != 0) return -1;
   int cfg = ctx->gemm_cfg[site];
   if (cfg < 0 || cfg > 8 || cfg == 7) cfg = 0;
@@ -217,8 +227,18 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_
   // The tile shape never changes a result bit (every output element sums its K slices in the same order), so
   // choosing it from the row count keeps the path batch-invariant.
   if (M <= 64 && !ctx->gemm_cfg_forced) cfg = 2;
-  // the 8-wave kernel takes unchunked K in an even number (>= 4) of 64-wide slices
-  if (cfg == 8 && !(k_chunks == 1 && K % 128 == 0 && K >= 256)) cfg = 0;
+  // ... and a pass over many rows (prefill chunks, long-document blocks) has enough row tiles to fill the chip with
+  // the 256x256 tile also on the narrower QKV projection (measured crossover: about 6 k rows at N = 1536)
+  if ((site == kSiteQKV || (site == kSiteDown && !split)) && M >= 6144 && !ctx->gemm_cfg_forced) {
+    // 256x256 tiles, unless their count leaves the last round over the CUs nearly empty and 256x128 tiles (8 waves,
+    // one workgroup per CU as well, 0.575 of the time per tile) fill the rounds better
+    const int64_t rt = (M + 255) / 256, cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
+    const int64_t t8 = rt * ((N + 255) / 256), t6 = rt * ((N + 127) / 128);
+    cfg = ((t6 + cu - 1) / cu) * 575 < ((t8 + cu - 1) / cu) * 900 ? 6 : 8;   // only on a clear (10 %) advantage
+  }
+  // the 8-wave kernel walks its K chunks itself (no split-K form), each an even number (>= 4) of 64-wide slices
+  const int k_len = K / k_chunks;
+  if (cfg == 8 && (split || k_len % 128 != 0 || k_len < 256)) cfg = 0;
   // ... and addresses its operands with 32-bit byte offsets (buffer loads): both matrices must stay below 2 GiB
   // (in dual mode the weight matrix has 2N rows)
   const int64_t w_rows = site == kSiteGateUp ? 2 * static_cast<int64_t>(N) : N;
@@ -236,7 +256,7 @@ template <typename T, typename Epi>
 int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int K, const void *A, const void *W,
                 const Epi &epi, int k_chunks = 1, bool split = false) {
   if constexpr (std::is_same<T, bf16>::value) {
-    switch (effective_gemm_cfg<T>(ctx, site, M, N, K, k_chunks)) {
+    switch (effective_gemm_cfg<T>(ctx, site, M, N, K, k_chunks, split)) {
       case -1: break;
       case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi, k_chunks, split);
       case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi, k_chunks, split);
@@ -244,7 +264,7 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
       case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi, k_chunks, split);
       case 5: return launch_gemm_mfma<GemmCfg5>(st, M, N, K, A, W, epi, k_chunks, split);
       case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi, k_chunks, split);
-      case 8: return launch_gemm_mfma8(st, M, N, K, A, W, epi);
+      case 8: return launch_gemm_mfma8(st, M, N, K, A, W, epi, k_chunks);
       default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi, k_chunks, split);
     }
   }
@@ -259,7 +279,7 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
 template <typename T>
 int lm_head_tiles(const hsd_ctx *ctx, int M) {
   const int V = ctx->desc.vocab;
-  switch (effective_gemm_cfg<T>(ctx, kSiteLM, M, V, ctx->desc.d_model, 1)) {
+  switch (effective_gemm_cfg<T>(ctx, kSiteLM, M, V, ctx->desc.d_model, 1, false)) {
     case -1: return V / 64;
     case 1: return V / GemmCfg1::BP * GemmCfg1::WM;
     case 4: return V / GemmCfg4::BP * GemmCfg4::WM;

@@ -195,7 +195,8 @@ __global__ void k_rmsnorm(int n_rows, int d, float eps, const float *__restrict_
 
 // ------------------------------------------------------------------------------------------------
 // Split-K reduction fused with the residual add and the following RMSNorm:
-//   x[r,:] += ((part[0][r,:] + part[1][r,:]) + ...)   (chunk order, the order the unsplit GEMM uses)
+//   x[r,:] = ((x[r,:] + part[0][r,:]) + part[1][r,:]) + ...   (the order in which a workgroup that walks the
+//                                                              chunks itself adds them to x)
 //   h[r,:]  = rmsnorm(x[r,:]) * gain                  (skipped when gain == nullptr)
 // One wave per row, 4 rows per block.
 // ------------------------------------------------------------------------------------------------
@@ -210,10 +211,8 @@ __global__ void k_reduce_rmsnorm(int n_rows, int d, float eps, float *__restrict
   const floatx4 *pr = reinterpret_cast<const floatx4 *>(part) + static_cast<size_t>(r) * d / 4;
   const int n4 = d >> 2;
   auto reduce_at = [&](int c) {
-    floatx4 s = pr[c];
-    for (int k = 1; k < n_splits; ++k) s += pr[k * split_stride + c];
     floatx4 v = xr[c];
-    v += s;
+    for (int k = 0; k < n_splits; ++k) v += pr[k * split_stride + c];
     xr[c] = v;
     return v;
   };

@@ -317,23 +317,26 @@ def test_device_side_error_flags():
 
 def test_split_k_and_chunk_walking_projections_agree_bitwise(monkeypatch):
     """The O and down projections reduce K in a fixed number of chunks.  Small batches run the chunks in separate
-    workgroups (split-K) and add the partial sums afterwards; large batches let each workgroup walk the chunks.
-    Both must round identically, so that a result never depends on the batch it was computed in."""
+    workgroups (split-K) and add the partial sums afterwards; large batches let each workgroup walk the chunks, in
+    the generic kernel or (down projection over many rows) in the 256x256-tile kernel.  All three must round
+    identically, so that a result never depends on the batch it was computed in."""
     desc, seed = SMALL_BF16, 13
     weights = W.make_weights(desc, seed)
     specs = [SequenceSpec(0, 37, 3, 150, 0.0), SequenceSpec(1, 16, 1, 81, 0.0)]
     rng = np.random.default_rng(4)
     drafts = [rng.integers(0, desc.vocab, size=sp.draft_len).astype(np.int32) for sp in specs]
     results = []
-    for split_rows in (None, "0"):
-        if split_rows is None:
-            monkeypatch.delenv("HSD_SPLIT_ROWS", raising=False)
-        else:
-            monkeypatch.setenv("HSD_SPLIT_ROWS", split_rows)      # read when the context is created
+    for split_rows, gemm_cfg in ((None, None), ("0", None), ("0", "5,2,8,8,8")):
+        for name, val in (("HSD_SPLIT_ROWS", split_rows), ("HSD_GEMM_CFG", gemm_cfg)):   # read at context creation
+            if val is None:
+                monkeypatch.delenv(name, raising=False)
+            else:
+                monkeypatch.setenv(name, val)
         eng = make_engine(desc, weights, specs, max_total_q=256, max_dump=256)
         pend = _gpu_prefill(eng, desc, seed, specs)
         blocks = [np.concatenate([[p], d]).astype(np.int32) for p, d in zip(pend, drafts)]
         results.append(_one_round(eng, [0, 1], blocks))
         eng.close()
-    np.testing.assert_array_equal(results[0][0], results[1][0])
-    np.testing.assert_array_equal(results[0][1], results[1][1])
+    for other in results[1:]:
+        np.testing.assert_array_equal(results[0][0], other[0])
+        np.testing.assert_array_equal(results[0][1], other[1])
