@@ -109,7 +109,9 @@ def main():
     maxb = max((sp.n_visual + sp.n_prompt + k_max + 1 + 15) // 16 + 1 for sp in specs)
     n_blocks = sum((sp.n_visual + sp.n_prompt + k_max + 1 + 15) // 16 + 1 for sp in specs) + 8
     total_q = sum(sp.draft_len + 1 for sp in specs)
-    eng = Engine(desc, weights, n_blocks, n, maxb, max(total_q, 4096), max_dump=0 if args.random_target else total_q,
+    # workspace rows: one verification block, or all prefixes at once (prefill runs in a single pass of 16,880 rows)
+    ws_rows = max(total_q, sum(sp.n_visual + sp.n_prompt - 1 for sp in specs))
+    eng = Engine(desc, weights, n_blocks, n, maxb, ws_rows, max_dump=0 if args.random_target else total_q,
                  attn_key_chunk=args.attn_key_chunk)
     slots = list(range(n))
 
@@ -288,16 +290,23 @@ def main():
             curve[str(tau)] = round(float(a.mean()), 3)
         out["aal_vs_tau_near_miss"] = curve
         eng.restore()
-    # --- prefix prefill of the same 16 regions (excluded from the decode metric, reported for the end-to-end picture)
-    eng.reset()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    eng.prefill(slots, toks, embs)
-    torch.cuda.synchronize()
-    dpf = time.perf_counter() - t0
+    # --- prefix prefill of the same 16 regions (excluded from the decode metric, reported for the end-to-end
+    # picture): with the visual embedding rows already on the device, as a vision encoder leaves them, and with
+    # their upload from pageable host memory
     n_prefill = sum(len(t) for t in toks)
-    out["prefill"] = {"rows": n_prefill, "ms": round(dpf * 1e3, 3), "rows_per_s": round(n_prefill / dpf, 1),
-                      "note": "includes the upload of the fp32 visual embedding rows"}
+    dev_embs = [torch.from_numpy(e).to("cuda:0") for e in embs]
+    pf = {}
+    for key, src in (("ms", dev_embs), ("ms_with_upload", embs)):
+        eng.reset()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        eng.prefill(slots, toks, src)
+        torch.cuda.synchronize()
+        pf[key] = time.perf_counter() - t0
+    out["prefill"] = {"rows": n_prefill, "ms": round(pf["ms"] * 1e3, 3), "rows_per_s": round(n_prefill / pf["ms"], 1),
+                      "ms_with_upload": round(pf["ms_with_upload"] * 1e3, 3),
+                      "note": "visual embedding rows resident on the device; ms_with_upload adds their copy from host memory"}
+    del dev_embs
     if args.breakdown:
         bd = {}
         for name, cls in prof_map.items():

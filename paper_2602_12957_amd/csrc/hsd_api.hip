@@ -223,12 +223,18 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_
   if (!std::is_same<T, bf16>::value || ctx->force_simple || K % 64 != 0) return -1;
   int cfg = ctx->gemm_cfg[site];
   if (cfg < 0 || cfg > 8 || cfg == 7) cfg = 0;
-  // A pass over a few rows (token-by-token decoding) has a single row tile: small tiles give it more workgroups.
-  // The tile shape never changes a result bit (every output element sums its K slices in the same order), so
-  // choosing it from the row count keeps the path batch-invariant.
-  if (M <= 64 && !ctx->gemm_cfg_forced) cfg = 2;
+  // The tile shape never changes a result bit (every output element sums its K slices in the same order), so it
+  // may follow the row count and the path stays batch-invariant.  A kernel's time is set by one workgroup's walk
+  // over K plus fixed costs as long as the launch fits the chip in one round, so fewer rows take smaller tiles: more
+  // workgroups, each with less arithmetic per K slice (measured per site on the 24-layer model at 16 to 1856 rows).
+  if (!ctx->gemm_cfg_forced) {
+    if (M <= 64) cfg = 2;                                              // token-by-token decoding: one row tile
+    else if (site == kSiteQKV || site == kSiteDown) cfg = M <= 1024 ? 2 : cfg;
+    else if (site == kSiteGateUp) cfg = M <= 256 ? 2 : (M <= 768 ? 0 : cfg);
+    else if (site == kSiteLM) cfg = M <= 128 ? 0 : cfg;
+  }
   // ... and a pass over many rows (prefill chunks, long-document blocks) has enough row tiles to fill the chip with
-  // the 256x256 tile also on the narrower QKV projection (measured crossover: about 6 k rows at N = 1536)
+  // the 256x256 tile also on the narrower projections (measured crossover: about 6 k rows at N = 1536)
   if ((site == kSiteQKV || (site == kSiteDown && !split)) && M >= 6144 && !ctx->gemm_cfg_forced) {
     // 256x256 tiles, unless their count leaves the last round over the CUs nearly empty and 256x128 tiles (8 waves,
     // one workgroup per CU as well, 0.575 of the time per tile) fill the rounds better

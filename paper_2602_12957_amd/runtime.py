@@ -270,28 +270,33 @@ class Engine:
         return b
 
     # ------------------------------------------------------------------ library calls
-    def prefill(self, slots: Sequence[int], tokens: Sequence[np.ndarray], embeds: Optional[Sequence[np.ndarray]] = None,
+    def prefill(self, slots: Sequence[int], tokens: Sequence[np.ndarray], embeds: Optional[Sequence] = None,
                 chunk: Optional[int] = None):
-        """Appends rows to the sequences' caches.  tokens[i][r] < 0 takes row r of embeds[i] (fp32 [n, d])."""
+        """Appends rows to the sequences' caches.  tokens[i][r] < 0 takes row r of embeds[i] (fp32 [n, d]): a numpy
+        array (uploaded chunk by chunk) or a tensor already on the device (the output of a vision encoder)."""
         chunk = chunk or self.max_total_q
         n_max = max(len(t) for t in tokens)
         per = max(1, chunk // len(slots))
         for c0 in range(0, n_max, per):
-            sl, tk, em = [], [], []
+            sl, tk, src = [], [], []
             for i, s in enumerate(slots):
                 t = np.asarray(tokens[i][c0:c0 + per], dtype=np.int32)
                 if len(t) == 0:
                     continue
                 sl.append(s)
                 tk.append(t)
-                if embeds is not None and embeds[i] is not None:
-                    em.append(np.asarray(embeds[i][c0:c0 + per], dtype=np.float32))
-                else:
-                    em.append(np.zeros((len(t), self.desc.d_model), dtype=np.float32))
-            need_emb = any((t < 0).any() for t in tk)
+                src.append(embeds[i] if embeds is not None else None)
             dev_emb = None
-            if need_emb:
-                dev_emb = torch.from_numpy(np.concatenate(em, axis=0)).to(self.dev)
+            if any((t < 0).any() for t in tk):
+                em = []
+                for t, e in zip(tk, src):
+                    if e is None:
+                        em.append(torch.zeros((len(t), self.desc.d_model), dtype=torch.float32, device=self.dev))
+                    elif isinstance(e, torch.Tensor):
+                        em.append(e[c0:c0 + per].to(device=self.dev, dtype=torch.float32))
+                    else:
+                        em.append(torch.from_numpy(np.ascontiguousarray(e[c0:c0 + per], dtype=np.float32)).to(self.dev))
+                dev_emb = torch.cat(em, dim=0).contiguous()
             b = self._make_batch(sl, tk, with_outputs=False, embeds=dev_emb)
             B.hsd_prefill(self.ctx, self.stream, self.cpool, b, _ptr(self.ws), self.ws_bytes)
             if dev_emb is not None:
