@@ -287,7 +287,7 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_q_heads, const
       float mx = st[0];
 #pragma unroll
       for (int v = 1; v < 16; ++v) mx = fmaxf(mx, st[v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      mx = half_max(mx);
       // The running reference point is kept as an INTEGER in the base-2 exponent domain (the smallest integer
       // >= max score * scale seen so far).  Every correction factor is then an exact power of two, and the bf16
       // rounding of a probability no longer depends on which tile (or key half) it was computed in: rounding
@@ -337,7 +337,7 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_q_heads, const
   // ---- merge the KQ key parts of each query set through LDS (stage memory is free after the last barrier):
   // part 0 folds in parts 1, 2, ... in that order
   float *mrg = reinterpret_cast<float *>(smem_raw);   // [KQ - 1][QS query sets][34][64 lanes]
-  l_run += __shfl_xor(l_run, 32, kWave);
+  l_run = half_sum(l_run);
   if (kh > 0) {
     float *dst = mrg + ((kh - 1) * QS + wq) * 34 * 64 + lane;
 #pragma unroll

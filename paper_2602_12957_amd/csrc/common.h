@@ -66,6 +66,17 @@ __device__ __forceinline__ void store_row(float *dst, const float (&v)[8]) {
   *reinterpret_cast<floatx4 *>(dst + 4) = f1;
 }
 
+// Exchange between the two lane halves (lane l and lane l ^ 32) in one cross-lane instruction, no LDS round trip:
+// v_permlane32_swap hands back (x of lane l % 32, x of lane 32 + l % 32) in every lane.
+__device__ __forceinline__ float half_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
