@@ -131,7 +131,8 @@ class Engine:
         self.k_pool = torch.zeros(pool_elems, dtype=es, device=self.dev)
         self.v_pool = torch.zeros(pool_elems, dtype=es, device=self.dev)
         # all KV bookkeeping lives in one int32 buffer so that a snapshot/restore is a single device copy
-        n_state = n_blocks + 1 + n_slots + n_slots * max_blocks_per_seq + 1
+        # (the outputs the host reads back every round -- status, alpha, bonus -- sit together at its end: one copy)
+        n_state = n_blocks + 1 + n_slots + n_slots * max_blocks_per_seq + 1 + 2 * n_slots
         self._state = torch.zeros(n_state, dtype=torch.int32, device=self.dev)
         o = 0
         self.free_list = self._state[o:o + n_blocks]; o += n_blocks
@@ -140,6 +141,9 @@ class Engine:
         self.block_table = self._state[o:o + n_slots * max_blocks_per_seq].view(n_slots, max_blocks_per_seq)
         o += n_slots * max_blocks_per_seq
         self.status = self._state[o:o + 1]
+        self.accept_len = self._state[o + 1:o + 1 + n_slots]
+        self.bonus = self._state[o + 1 + n_slots:o + 1 + 2 * n_slots]
+        self._readback = self._state[o:o + 1 + 2 * n_slots]
         self._snapshot = torch.zeros_like(self._state)
         self.cpool = B.hsd_kv_pool(_ptr(self.k_pool), _ptr(self.v_pool), n_blocks, _ptr(self.free_list),
                                    _ptr(self.free_count))
@@ -153,12 +157,9 @@ class Engine:
         self.argmax = torch.zeros(max_total_q, dtype=torch.int32, device=self.dev)
         self.margin = torch.zeros(max_total_q, dtype=torch.float32, device=self.dev)
         self.gap = torch.zeros(max_total_q, dtype=torch.float32, device=self.dev)
-        self.accept_len = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
-        self.bonus = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
         self.stop_row = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
         self.pending = torch.zeros(n_slots, dtype=torch.int32, device=self.dev)
         self._h_out = torch.empty(2 * n_slots + 1, dtype=torch.int32).pin_memory()
-        self._d_out = torch.empty(2 * n_slots + 1, dtype=torch.int32, device=self.dev)
         self.embeds = None
         self.logits_dump = (torch.zeros((max_dump, desc.vocab), dtype=torch.float32, device=self.dev)
                             if max_dump > 0 else None)
@@ -344,13 +345,10 @@ class Engine:
 
     def read_acceptance(self, n: int):
         """Small device-to-host readback of (alpha, bonus, status); synchronises the stream."""
-        self._d_out[:n].copy_(self.accept_len[:n])
-        self._d_out[n:2 * n].copy_(self.bonus[:n])
-        self._d_out[2 * n:2 * n + 1].copy_(self.status)
-        self._h_out[:2 * n + 1].copy_(self._d_out[:2 * n + 1], non_blocking=True)
+        self._h_out.copy_(self._readback, non_blocking=True)
         torch.cuda.current_stream(self.dev).synchronize()
         h = self._h_out.numpy()
-        return h[:n].copy(), h[n:2 * n].copy(), int(h[2 * n])
+        return h[1:1 + n].copy(), h[1 + self.n_slots:1 + self.n_slots + n].copy(), int(h[0])
 
     def greedy_decode(self, slots: Sequence[int], pending: Sequence[int], n_tokens: int,
                       mode: str = "region") -> np.ndarray:
