@@ -17,7 +17,8 @@
 //    element sit in the same lane and register index of adjacent sub-tiles (SwiGLU in place).
 //
 // Workgroups are numbered so that the 8 XCDs (round-robin over workgroup ids) each walk a contiguous
-// range of tiles, activation tile fastest: consecutive tiles on one XCD share the weight tile in its L2.
+// range of tiles: activation tile fastest while the weights are the larger operand (consecutive tiles on one XCD
+// share the weight tile in its L2), weight tile fastest for passes over many rows (see gemm_tile_of).
 #pragma once
 
 #include "common.h"
