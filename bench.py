@@ -87,6 +87,10 @@ def main():
     ap.add_argument("--tau", type=float, default=1.0,
                     help="acceptance threshold of the relaxed rule (paper default 0.75); 1.0 = exact greedy match, "
                          "the rule the headline metric is defined on")
+    ap.add_argument("--config", type=int, default=1, choices=[1, 2, 3, 4],
+                    help="profiling aid: run round 1 of another configuration of BASELINE.json (2, 3: page-level entry "
+                         "point; 4: 64 ragged regions) instead of configs[1], the one the metric is quoted on; needs "
+                         "--random-target, prints the timed step only")
     ap.add_argument("--attn-key-chunk", type=int, default=0,
                     help="attention key split (hsd_model_desc.attn_key_chunk): keys per chunk, 0 = unsplit")
     ap.add_argument("--breakdown", action="store_true",
@@ -100,8 +104,12 @@ def main():
     from paper_2602_12957_amd.runtime import Engine
     import paper_2602_12957_amd.binding as B
 
-    cfg_index = 1
+    cfg_index = args.config
+    if cfg_index != 1 and not args.random_target:
+        print("bench.py: --config other than 1 is a profiling aid and needs --random-target", file=sys.stderr)
+        sys.exit(2)
     W, desc, weights, specs = build_workload(cfg_index, args.seed or 20260212)
+    mode = W.CONFIGS[cfg_index].kind        # "region" or "page": the entry point
     seed = args.seed or W.SEED_BASE
     n = len(specs)
     k_max = max(sp.draft_len for sp in specs)
@@ -110,7 +118,8 @@ def main():
     n_blocks = sum((sp.n_visual + sp.n_prompt + k_max + 1 + 15) // 16 + 1 for sp in specs) + 8
     total_q = sum(sp.draft_len + 1 for sp in specs)
     # workspace rows: one verification block, or all prefixes at once (prefill runs in a single pass of 16,880 rows)
-    ws_rows = max(total_q, sum(sp.n_visual + sp.n_prompt - 1 for sp in specs))
+    prefix_len = [sp.n_visual + max(sp.n_prompt - 1, 0) for sp in specs]
+    ws_rows = max(total_q, sum(prefix_len) if cfg_index == 1 else 4096)
     eng = Engine(desc, weights, n_blocks, n, maxb, ws_rows, max_dump=0 if args.random_target else total_q,
                  attn_key_chunk=args.attn_key_chunk)
     slots = list(range(n))
@@ -139,7 +148,7 @@ def main():
 
     def step():
         eng.restore()                       # bookkeeping back to "prefix cached" (one small device copy)
-        eng.verify_prepared(batch, "region")
+        eng.verify_prepared(batch, mode)
         eng.commit()
         return eng.read_acceptance(n)       # synchronises: the host needs alpha to slice the next round
 
@@ -173,7 +182,8 @@ def main():
         ach = flops_per_launch[args.profile_kernel] / (avg_ms * 1e-3) / 1e12
         roofline = {"kernel": f"k_gemm_mfma ({args.profile_kernel})", "bound": "mfma", "achieved": round(ach, 1),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.profile_kernel), "avg_launch_ms": round(avg_ms, 5),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.profile_kernel) if cfg_index == 1 else None,
+                    "avg_launch_ms": round(avg_ms, 5),
                     "launches_timed": n_launch,
                     "flops_per_launch": flops_per_launch[args.profile_kernel]}
     gemm_flops_step = 2.0 * desc.gemm_params * total_q
@@ -181,9 +191,13 @@ def main():
         "metric": "verified_draft_tokens_per_s", "value": round(verified / (ms_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[1] region-level verify, round 1: 16 regions x (1055 cached + pending + draft "
-                               "U[16,256]), 24-layer d1024 16q/4kv x64 FFN4096 vocab 32768, paged KV 16-token blocks",
-                   "n_seq": n, "rows_per_step": total_q, "draft_tokens_per_step": verified, "corruption_p": 0.05,
+        "config": {"workload": ("configs[1] region-level verify, round 1: 16 regions x (1055 cached + pending + draft "
+                                "U[16,256]), 24-layer d1024 16q/4kv x64 FFN4096 vocab 32768, paged KV 16-token blocks")
+                               if cfg_index == 1 else
+                               (f"configs[{cfg_index}] {mode}-level verify, round 1 (profiling aid, random drafts): "
+                                f"{W.CONFIGS[cfg_index].description}"),
+                   "n_seq": n, "rows_per_step": total_q, "draft_tokens_per_step": verified,
+                   "corruption_p": 0.05 if cfg_index == 1 else None,
                    "acceptance": "exact match (tau = 1)" if log_tau == 0.0 else f"relaxed, tau = {args.tau}"},
         "accepted_tokens_per_s": round(accepted / (ms_step * 1e-3), 1),
         "committed_tokens_per_s": round((accepted + n) / (ms_step * 1e-3), 1),
@@ -206,7 +220,7 @@ def main():
         cnt, ms = eng.profile_read()
         eng.profile(B.HSD_PROF_NONE, 0)
         if cnt > 0:
-            S = [sp.n_visual + sp.n_prompt - 1 for sp in specs]
+            S = prefix_len
             Lq = [sp.draft_len + 1 for sp in specs]
             flops = sum(4.0 * desc.n_q_heads * desc.head_dim * (l * s_ + l * (l + 1) / 2) for s_, l in zip(S, Lq))
             kv_bytes = sum((s_ + l) * desc.n_kv_heads * desc.head_dim * 2 * 2 for s_, l in zip(S, Lq))
@@ -293,20 +307,23 @@ def main():
     # --- prefix prefill of the same 16 regions (excluded from the decode metric, reported for the end-to-end
     # picture): with the visual embedding rows already on the device, as a vision encoder leaves them, and with
     # their upload from pageable host memory
-    n_prefill = sum(len(t) for t in toks)
-    dev_embs = [torch.from_numpy(e).to("cuda:0") for e in embs]
-    pf = {}
-    for key, src in (("ms", dev_embs), ("ms_with_upload", embs)):
-        eng.reset()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        eng.prefill(slots, toks, src)
-        torch.cuda.synchronize()
-        pf[key] = time.perf_counter() - t0
-    out["prefill"] = {"rows": n_prefill, "ms": round(pf["ms"] * 1e3, 3), "rows_per_s": round(n_prefill / pf["ms"], 1),
-                      "ms_with_upload": round(pf["ms_with_upload"] * 1e3, 3),
-                      "note": "visual embedding rows resident on the device; ms_with_upload adds their copy from host memory"}
-    del dev_embs
+    if cfg_index == 1:
+        n_prefill = sum(len(t) for t in toks)
+        dev_embs = [torch.from_numpy(e).to("cuda:0") for e in embs]
+        pf = {}
+        for key, src in (("ms", dev_embs), ("ms_with_upload", embs)):
+            eng.reset()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            eng.prefill(slots, toks, src)
+            torch.cuda.synchronize()
+            pf[key] = time.perf_counter() - t0
+        out["prefill"] = {"rows": n_prefill, "ms": round(pf["ms"] * 1e3, 3),
+                          "rows_per_s": round(n_prefill / pf["ms"], 1),
+                          "ms_with_upload": round(pf["ms_with_upload"] * 1e3, 3),
+                          "note": "visual embedding rows resident on the device; ms_with_upload adds their copy from "
+                                  "host memory"}
+        del dev_embs
     if args.breakdown:
         bd = {}
         for name, cls in prof_map.items():
@@ -320,7 +337,7 @@ def main():
                         "us_per_step": round(ms / 3 * 1e3, 1)}
         eng.profile(B.HSD_PROF_NONE, 0)
         out["breakdown"] = bd
-    if args.cpu_sample > 0:
+    if args.cpu_sample > 0 and cfg_index == 1:
         out["cpu_baseline"] = cpu_baseline(W, desc, weights, seed, specs, drafts, pend, min(args.cpu_sample, n))
     eng.close()
     print(json.dumps(out))
