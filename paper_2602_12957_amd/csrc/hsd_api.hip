@@ -235,7 +235,7 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_
   }
   // ... and a pass over many rows (prefill chunks, long-document blocks) has enough row tiles to fill the chip with
   // the 256x256 tile also on the narrower projections (measured crossover: about 6 k rows at N = 1536)
-  if ((site == kSiteQKV || (site == kSiteDown && !split)) && M >= 6144 && !ctx->gemm_cfg_forced) {
+  if ((site == kSiteQKV || site == kSiteO || (site == kSiteDown && !split)) && M >= 6144 && !ctx->gemm_cfg_forced) {
     // 256x256 tiles, unless their count leaves the last round over the CUs nearly empty and 256x128 tiles (8 waves,
     // one workgroup per CU as well, 0.575 of the time per tile) fill the rounds better
     const int64_t rt = (M + 255) / 256, cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
