@@ -314,11 +314,17 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_q_heads, const
         for (int e = 0; e < 8; ++e) {
           // bare hardware exponential: arguments are <= 0 and results below 2^-126 may flush to zero, far
           // beneath half a bf16 unit of any probability that matters
-          const float p = __builtin_amdgcn_exp2f(fmaf(st[8 * kk + e], sc, -msc));
-          l_run += p;
-          pv[e] = p;
+          pv[e] = __builtin_amdgcn_exp2f(fmaf(st[8 * kk + e], sc, -msc));
         }
         pf[kk] = __builtin_convertvector(pv, bf16x8);
+        // the row sum takes the probabilities as the second product will see them (rounded to bf16), two per
+        // instruction: l += p0 * 1 + p1 * 1
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[kk], pf[kk], 0, 1), ones, l_run, false);
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[kk], pf[kk], 2, 3), ones, l_run, false);
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[kk], pf[kk], 4, 5), ones, l_run, false);
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[kk], pf[kk], 6, 7), ones, l_run, false);
       }
       m_run = m_new;
 #pragma unroll
