@@ -88,7 +88,7 @@ def main():
                     help="acceptance threshold of the relaxed rule (paper default 0.75); 1.0 = exact greedy match, "
                          "the rule the headline metric is defined on")
     ap.add_argument("--config", type=int, default=1, choices=[1, 2, 3, 4],
-                    help="profiling aid: run round 1 of another configuration of BASELINE.json (2, 3: page-level entry "
+                    help="profiling aid: run round 1 of another workload configuration (2, 3: page-level entry "
                          "point; 4: 64 ragged regions) instead of configs[1], the one the metric is quoted on; needs "
                          "--random-target, prints the timed step only")
     ap.add_argument("--attn-key-chunk", type=int, default=0,
