@@ -194,6 +194,32 @@ def test_key_split_last_chunk_is_open_ended():
     assert diff.max() > 0 and np.sqrt((diff ** 2).mean()) < 2e-2, (diff.max(), np.sqrt((diff ** 2).mean()))
 
 
+def test_prefill_takes_device_resident_embeddings():
+    """Visual embedding rows handed over as device tensors (what a vision encoder leaves behind) give the same cache
+    as host arrays uploaded chunk by chunk, also when the prefill runs in several passes."""
+    import torch
+    desc, seed = SMALL_BF16, 31
+    weights = W.make_weights(desc, seed)
+    specs = [SequenceSpec(0, 150, 3, 40, 0.0), SequenceSpec(1, 33, 2, 25, 0.0)]
+    rng = np.random.default_rng(6)
+    drafts = [rng.integers(0, desc.vocab, size=sp.draft_len).astype(np.int32) for sp in specs]
+    outs = []
+    for on_device, chunk in ((False, None), (True, None), (True, 64)):
+        eng = make_engine(desc, weights, specs, max_total_q=256, max_dump=128)
+        toks, embs, pend = [], [], []
+        for sp in specs:
+            _, _, tok, emb, pending = prefix_rows(desc, seed, sp)
+            toks.append(tok), pend.append(pending)
+            embs.append(torch.from_numpy(emb).to("cuda:0") if on_device else emb)
+        eng.prefill([0, 1], toks, embs, chunk=chunk)
+        blocks = [np.concatenate([[p], d]).astype(np.int32) for p, d in zip(pend, drafts)]
+        outs.append(_one_round(eng, [0, 1], blocks))
+        eng.close()
+    for other in outs[1:]:
+        np.testing.assert_array_equal(outs[0][0], other[0])
+        np.testing.assert_array_equal(outs[0][1], other[1])
+
+
 def test_greedy_decode_matches_oracle_fp32():
     """Blocks of length 1 (k = 0) are plain decode steps; the GPU greedy loop reproduces the oracle's
     token-by-token output.  The fp32 path's logits are within 1e-4 of the oracle's, so the comparison runs
