@@ -194,6 +194,37 @@ def test_key_split_last_chunk_is_open_ended():
     assert diff.max() > 0 and np.sqrt((diff ** 2).mean()) < 2e-2, (diff.max(), np.sqrt((diff ** 2).mean()))
 
 
+def test_random_shapes_against_oracle():
+    """Forty seeded random combinations of depth, width, GQA grouping (1, 2, 4 query heads per kv head and
+    kv-head counts of 1 to 8), storage type, vocabulary, entry point, attention key split and ragged sequences whose
+    prefix and draft lengths sit on and around the tile and page boundaries (0, 1, 15-17, 63-65, ...), drafts
+    corrupted at 4 % of the positions: every round of every case against the oracle."""
+    rng = np.random.default_rng(20260212)
+    for it in range(40):
+        heads = [(4, 1), (4, 2), (8, 2), (4, 4), (8, 8), (16, 4)][rng.integers(0, 6)]
+        dt = "bf16" if rng.random() < 0.7 else "fp32"
+        desc = W.ModelDesc(n_layers=int(rng.integers(1, 4)), d_model=int(rng.choice([128, 256])), n_q_heads=heads[0],
+                           n_kv_heads=heads[1], head_dim=64, d_ffn=int(rng.choice([256, 512])),
+                           vocab=int(rng.choice([512, 640, 1024])), dtype=dt)
+        seed = int(rng.integers(1, 10000))
+        specs = []
+        for i in range(int(rng.integers(1, 6))):
+            nv = int(rng.choice([0, 1, 15, 16, 17, 63, 64, 65, 130, 300]))
+            npr = int(rng.integers(1 if nv == 0 else 0, 6))
+            specs.append(SequenceSpec(i, nv, npr, int(rng.choice([1, 2, 31, 32, 33, 64, 65, 100, 190])), 0.0))
+        mode = "page" if rng.random() < 0.4 else "region"
+        chunk = int(rng.choice([0, 0, 64, 128])) if dt == "bf16" else 0
+        weights = W.make_weights(desc, seed)
+        drafts = []
+        for (g, _) in oracle_targets(desc, weights, seed, specs):
+            d = g.copy()
+            for pos in np.nonzero(rng.random(len(d)) < 0.04)[0]:
+                d[pos] = (d[pos] + 1 + rng.integers(0, desc.vocab - 1)) % desc.vocab
+            drafts.append(d)
+        print(it, desc, [(s.n_visual, s.n_prompt, s.draft_len) for s in specs], mode, chunk, seed, flush=True)
+        run_rounds_parity(desc, weights, seed, specs, drafts, mode=mode, attn_key_chunk=chunk or None)
+
+
 def test_prefill_takes_device_resident_embeddings():
     """Visual embedding rows handed over as device tensors (what a vision encoder leaves behind) give the same cache
     as host arrays uploaded chunk by chunk, also when the prefill runs in several passes."""
