@@ -64,12 +64,43 @@ def _walk(argmax, tokens, end, gap, want, log_tau):
 @pytest.mark.parametrize("log_tau", [0.0, math.log(0.75)], ids=["exact", "tau0.75"])
 @pytest.mark.parametrize("mode", ["region", "page"])
 def test_one_pass_over_packed_trees(desc, chunk, log_tau, mode):
-    from paper_2602_12957_amd.runtime import pack_prefix_tree
-    seed = 61
-    weights = W.make_weights(desc, seed)
     shapes = [(40, 3, 30), (5, 2, 70), (17, 1, 12), (64, 8, 45), (0, 4, 20)]
     specs = [SequenceSpec(i, nv, npr, k, 0.0) for i, (nv, npr, k) in enumerate(shapes)]
-    rng = np.random.default_rng(7)
+    decided = _one_pass_trees(desc, chunk, log_tau, mode, 61, specs, [1, 4, 0, 6, 3], np.random.default_rng(7), 3)
+    assert decided >= 1
+
+
+def test_random_packed_trees_against_oracle():
+    """Thirty seeded random combinations of model shape, GQA grouping, storage type, entry point, acceptance rule,
+    attention key split and per-sequence candidate sets (0 to 6 drafts of up to 60 tokens that share prefixes of
+    random length with the greedy continuation and with each other)."""
+    rng = np.random.default_rng(20260213)
+    decided = 0
+    for it in range(30):
+        heads = [(4, 1), (4, 2), (8, 2), (4, 4), (16, 4)][rng.integers(0, 5)]
+        dt = "bf16" if rng.random() < 0.7 else "fp32"
+        desc = W.ModelDesc(n_layers=int(rng.integers(1, 4)), d_model=int(rng.choice([128, 256])), n_q_heads=heads[0],
+                           n_kv_heads=heads[1], head_dim=64, d_ffn=256, vocab=int(rng.choice([512, 1024])), dtype=dt)
+        specs, n_cands = [], []
+        for i in range(int(rng.integers(1, 5))):
+            nv = int(rng.choice([0, 1, 16, 47, 64, 130]))
+            specs.append(SequenceSpec(i, nv, int(rng.integers(1 if nv == 0 else 0, 5)), int(rng.choice([1, 7, 31, 60])), 0.0))
+            n_cands.append(int(rng.integers(0, 7)))
+        log_tau = 0.0 if rng.random() < 0.5 else math.log(0.75)
+        mode = "page" if rng.random() < 0.4 else "region"
+        chunk = int(rng.choice([0, 64])) if dt == "bf16" else 0
+        seed = int(rng.integers(1, 10000))
+        print(it, desc, [(s.n_visual, s.n_prompt, s.draft_len) for s in specs], n_cands, mode, log_tau, chunk, seed, flush=True)
+        decided += _one_pass_trees(desc, chunk or None, log_tau, mode, seed, specs, n_cands, rng, -1)
+    assert decided >= 30
+
+
+def _one_pass_trees(desc, chunk, log_tau, mode, seed, specs, n_cands, rng, with_target):
+    """One verification pass over packed prefix trees against the oracle; returns the number of sequences whose
+    acceptance could be compared exactly (every deciding row clear of the tie gate).  `with_target`: index of the
+    sequence whose candidate set also holds the greedy continuation itself (-1: none)."""
+    from paper_2602_12957_amd.runtime import pack_prefix_tree
+    weights = W.make_weights(desc, seed)
     act = act_dtype_of(desc)
     n = len(specs)
     ora, blocks, trees = [], [], []
@@ -79,9 +110,8 @@ def test_one_pass_over_packed_trees(desc, chunk, log_tau, mode):
         base = len(cache)
         target = O.greedy_decode(desc, weights, cache, pending, sp.draft_len, act_dtype=act)
         cache.truncate(base)
-        n_cand = [1, 4, 0, 6, 3][sp.seq_id]
-        cands = _candidates(rng, target, desc.vocab, n_cand, sp.draft_len)
-        if sp.seq_id == 3:
+        cands = _candidates(rng, target, desc.vocab, n_cands[sp.seq_id], sp.draft_len)
+        if sp.seq_id == with_target:
             cands.append(target.tolist())           # the greedy continuation itself is among the drafts
         acc, bonus, logits, (tokens, parent, depth, end) = O.verify_tree(desc, weights, cache, pending, cands,
                                                                          act_dtype=act, log_tau=log_tau)
@@ -136,7 +166,7 @@ def test_one_pass_over_packed_trees(desc, chunk, log_tau, mode):
             decided += 1
     eng.close()
     print(desc.dtype, mode, log_tau, "decided", decided, "of", n)
-    assert decided >= 1
+    return decided
 
 
 def _row_of_path(tokens, end, path):
