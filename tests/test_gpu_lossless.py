@@ -90,6 +90,28 @@ def test_lossless_with_attention_key_split():
     print("cfg2 lossless rounds with 1024-key chunks", rounds)
 
 
+def test_lossless_random_shapes():
+    """Twenty-five seeded random combinations of depth, width, GQA grouping, storage type, entry point, key split and
+    ragged sequences (prefixes of 0 to 700 tokens, drafts of 1 to 260, corruption 0 / 5 / 30 %): verification rounds
+    reproduce token-by-token decoding exactly in every one."""
+    rng = np.random.default_rng(20260214)
+    for it in range(25):
+        heads = [(4, 1), (4, 2), (8, 2), (4, 4), (16, 4), (8, 8)][rng.integers(0, 6)]
+        dt = "bf16" if rng.random() < 0.8 else "fp32"
+        desc = W.ModelDesc(int(rng.integers(1, 5)), int(rng.choice([128, 256, 512])), heads[0], heads[1], 64,
+                           int(rng.choice([256, 512, 1024])), int(rng.choice([512, 1024, 2048])), dt)
+        specs = []
+        for i in range(int(rng.integers(1, 7))):
+            nv = int(rng.choice([0, 1, 15, 16, 17, 63, 64, 65, 130, 300, 700]))
+            specs.append(SequenceSpec(i, nv, int(rng.integers(1 if nv == 0 else 0, 6)),
+                                      int(rng.choice([1, 2, 31, 33, 64, 65, 150, 260])), float(rng.choice([0.0, 0.05, 0.3]))))
+        mode = "page" if rng.random() < 0.4 else "region"
+        chunk = int(rng.choice([0, 64, 128, 256])) if dt == "bf16" else 0
+        seed = int(rng.integers(1, 10000))
+        print(it, desc, [(s.n_visual, s.n_prompt, s.draft_len, s.corrupt_p) for s in specs], mode, chunk, seed, flush=True)
+        _lossless(desc, specs, seed, mode, attn_key_chunk=chunk or None)
+
+
 def test_lossless_config1_model_m():
     """configs[1] shapes (16 regions, 1055 cached tokens, drafts U[16,256], 5 % corruption), 24-layer bf16 model."""
     specs = W.draw_sequences(1, W.SEED_BASE)
