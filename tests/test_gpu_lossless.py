@@ -112,6 +112,17 @@ def test_lossless_random_shapes():
         _lossless(desc, specs, seed, mode, attn_key_chunk=chunk or None)
 
 
+def test_lossless_through_every_row_count_regime():
+    """Drafts long enough that round 1 scores more than 6 k rows (256x256 tiles on QKV and O, the down projection's K
+    chunks walked inside one workgroup, row-band tile order) and the following rounds shrink through every tile
+    choice down to a few rows: all of them must reproduce token-by-token decoding bit for bit, on small models with
+    ragged tile tails."""
+    for desc, lens in ((W.ModelDesc(3, 256, 8, 2, 64, 512, 1024, "bf16"), [1500, 1300, 1700, 999, 801]),
+                       (W.ModelDesc(2, 256, 16, 4, 64, 1536, 2048, "bf16"), [3000, 3200, 67, 1])):
+        specs = [SequenceSpec(i, 40 + 13 * i, 3, k, 0.02) for i, k in enumerate(lens)]
+        assert _lossless(desc, specs, 17, "region") >= 20
+
+
 def test_lossless_config1_model_m():
     """configs[1] shapes (16 regions, 1055 cached tokens, drafts U[16,256], 5 % corruption), 24-layer bf16 model."""
     specs = W.draw_sequences(1, W.SEED_BASE)
