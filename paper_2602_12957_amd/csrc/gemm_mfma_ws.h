@@ -1,0 +1,145 @@
+// bf16 MFMA GEMM, 128x128x64 tile, eight waves in two roles: waves 0-3 multiply (wave tile 64x64, as the 4-wave
+// 128x128 configuration of gemm_mfma.h), waves 4-7 only move the operands (global -> registers -> LDS).
+//
+// Why.  With one workgroup per CU -- all a launch over ~2 k rows offers for the narrow projections -- a 4-wave
+// workgroup has one wave per SIMD, and that wave's instruction stream serialises fragment reads + MFMAs (0.31 us
+// per K slice), operand loads (0.07), LDS stores (0.14) and the barrier (0.08): measured by removing each part in
+// turn, the parts add up to the 0.6 us a slice takes.  Giving the data movement to waves of its own puts two waves
+// on every SIMD whose stalls are independent: the stores and load waits of one hide behind the MFMAs of the other.
+//
+// Same pipeline as the generic kernel (two LDS stages, two register sets, a slice requested two iterations before
+// it is stored), same tile order, same epilogue (multiplying waves only), same K order in every accumulator, so
+// results are bit-identical to every other tile configuration.  Modes: normal only; K chunks only as split-K.
+// Every wave executes exactly 1 + K/64 workgroup barriers, whichever role it has.
+#pragma once
+
+#include "gemm_mfma.h"
+
+namespace hsd {
+
+using GemmCfgWS = GemmCfg<128, 128, 64, 2, 2>;
+
+// grid: (tiles_act * tiles_w, k_chunks or 1), 512 threads, GemmCfgWS::kSmemBytes dynamic LDS.
+template <typename Epi>
+__global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, int k_chunks, const bf16 *__restrict__ A,
+                                                      const bf16 *__restrict__ W, Epi epi) {
+  using Cfg = GemmCfgWS;
+  constexpr int BP = Cfg::BP, BQ = Cfg::BQ, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN, LS = Cfg::kStride;
+  constexpr int NT = 256, CH = Cfg::kChunks, LP = Cfg::kLoadsP, LQ = Cfg::kLoadsQ;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  uint16_t *smem = reinterpret_cast<uint16_t *>(smem_raw);
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const bool mover = wave >= 4;
+  int tiles_act, tiles_w, ta, tw;
+  gemm_tiles<Cfg, kModeNormal>(M, N, tiles_act, tiles_w);
+  gemm_tile_of(blockIdx.x, M, N, tiles_act, tiles_w, ta, tw);
+  const int m0 = ta * BP, n0 = tw * BQ;
+  const bool split = gridDim.y > 1;
+  const int k_len = K / k_chunks, nk = k_len / BK;
+  const int kc0 = split ? static_cast<int>(blockIdx.y) * k_len : 0;
+
+  if (mover) {
+    const int tp = t - NT;
+    const bf16 *srcP[LP];
+    const bf16 *srcQ[LQ];
+#pragma unroll
+    for (int i = 0; i < LP; ++i) {
+      const int c = tp + NT * i, r = c / CH, kc = c % CH;
+      srcP[i] = A + static_cast<size_t>(min(m0 + r, M - 1)) * K + kc0 + kc * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < LQ; ++i) {
+      const int c = tp + NT * i, r = c / CH, kc = c % CH;
+      srcQ[i] = W + static_cast<size_t>(min(n0 + r, N - 1)) * K + kc0 + kc * 8;
+    }
+    u32x4 regP[2][LP], regQ[2][LQ];
+    // requests are unconditional (past the last slice they re-read the last one; the LDS store that follows fills a
+    // stage nobody multiplies from), so every store waits for exactly the older of the two sets in flight
+#define HSD_WS_LOAD(set, slice)                                                                     \
+  {                                                                                                 \
+    const int k0 = min((slice), nk - 1) * BK;                                                       \
+    _Pragma("unroll") for (int i = 0; i < LP; ++i)                                                  \
+        regP[set][i] = *reinterpret_cast<const u32x4 *>(srcP[i] + k0);                              \
+    _Pragma("unroll") for (int i = 0; i < LQ; ++i)                                                  \
+        regQ[set][i] = *reinterpret_cast<const u32x4 *>(srcQ[i] + k0);                              \
+  }
+#define HSD_WS_STORE(set, stage)                                                                    \
+  {                                                                                                 \
+    uint16_t *sd = smem + (stage) * Cfg::kStage;                                                    \
+    _Pragma("unroll") for (int i = 0; i < LP; ++i) {                                                \
+      const int c = tp + NT * i;                                                                    \
+      *reinterpret_cast<u32x4 *>(sd + (c / CH) * LS + (c % CH) * 8) = regP[set][i];                 \
+    }                                                                                               \
+    _Pragma("unroll") for (int i = 0; i < LQ; ++i) {                                                \
+      const int c = tp + NT * i;                                                                    \
+      *reinterpret_cast<u32x4 *>(sd + BP * LS + (c / CH) * LS + (c % CH) * 8) = regQ[set][i];       \
+    }                                                                                               \
+  }
+    HSD_WS_LOAD(0, 0)
+    HSD_WS_LOAD(1, 1)
+    HSD_WS_STORE(0, 0)
+    HSD_WS_LOAD(0, 2)
+    __syncthreads();                                   // barrier 1: slice 0 is in stage 0
+    // iteration kt: slice kt+1 (set and stage (kt+1) & 1) goes to LDS, slice kt+3 is requested into its set
+    // (four sets, i.e. requests four iterations ahead, were measured and change nothing)
+    int kt = 0;
+    for (; kt + 2 <= nk; kt += 2) {
+      HSD_WS_STORE(1, 1)
+      HSD_WS_LOAD(1, kt + 3)
+      __syncthreads();
+      HSD_WS_STORE(0, 0)
+      HSD_WS_LOAD(0, kt + 4)
+      __syncthreads();
+    }
+    if (kt < nk) {
+      HSD_WS_STORE(1, 1)
+      __syncthreads();
+    }
+#undef HSD_WS_LOAD
+#undef HSD_WS_STORE
+    return;                                            // 1 + nk barriers executed
+  }
+
+  // ---- multiplying waves
+  const int wi = wave / Cfg::WN, wj = wave % Cfg::WN;
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  const int frag_p = (wi * (BP / Cfg::WM) + (lane & 31)) * LS + (lane >> 5) * 8;
+  const int frag_q = BP * LS + (wj * (BQ / Cfg::WN) + (lane & 31)) * LS + (lane >> 5) * 8;
+  __syncthreads();                                     // barrier 1
+  for (int kt = 0; kt < nk; ++kt) {
+    const uint16_t *sp = smem + (kt & 1) * Cfg::kStage;
+    bf16x8 fa[2][TM], fb[2][TN];
+#define HSD_WS_FRAG(buf, kk)                                                                        \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i) fa[buf][i] =                                       \
+      *reinterpret_cast<const bf16x8 *>(sp + frag_p + i * 32 * LS + (kk) * 16);                     \
+  _Pragma("unroll") for (int j = 0; j < TN; ++j) fb[buf][j] =                                       \
+      *reinterpret_cast<const bf16x8 *>(sp + frag_q + j * 32 * LS + (kk) * 16);
+#define HSD_WS_MMA(buf)                                                                             \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j)     \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+    HSD_WS_FRAG(0, 0)
+    HSD_WS_FRAG(1, 1)
+    HSD_WS_MMA(0)
+    HSD_WS_FRAG(0, 2)
+    HSD_WS_MMA(1)
+    HSD_WS_FRAG(1, 3)
+    HSD_WS_MMA(0)
+    HSD_WS_MMA(1)
+#undef HSD_WS_FRAG
+#undef HSD_WS_MMA
+    __syncthreads();
+  }
+  // the moving waves have left; their last LDS stores came before the last barrier, so the stages are free for
+  // the epilogue's staging
+  gemm_epilogue<Cfg, kModeNormal>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(split ? blockIdx.y : -1, M),
+                                  reinterpret_cast<float *>(smem_raw));
+}
+
+}  // namespace hsd
