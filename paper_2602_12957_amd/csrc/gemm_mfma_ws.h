@@ -1,5 +1,6 @@
-// bf16 MFMA GEMM, 128x128x64 tile, eight waves in two roles: waves 0-3 multiply (wave tile 64x64, as the 4-wave
-// 128x128 configuration of gemm_mfma.h), waves 4-7 only move the operands (global -> registers -> LDS).
+// bf16 MFMA GEMM with eight waves in two roles: waves 0-3 multiply (a 2x2 arrangement of wave tiles, as the 4-wave
+// configurations of gemm_mfma.h: 128x128 tile with 64x64 wave tiles, or 64x128 with 32x64), waves 4-7 only move the
+// operands (global -> registers -> LDS).
 //
 // Why.  With one workgroup per CU -- all a launch over ~2 k rows offers for the narrow projections -- a 4-wave
 // workgroup has one wave per SIMD, and that wave's instruction stream serialises fragment reads + MFMAs (0.31 us
@@ -9,7 +10,8 @@
 //
 // Same pipeline as the generic kernel (two LDS stages, two register sets, a slice requested two iterations before
 // it is stored), same tile order, same epilogue (multiplying waves only), same K order in every accumulator, so
-// results are bit-identical to every other tile configuration.  Modes: normal only; K chunks only as split-K.
+// results are bit-identical to every other tile configuration.  Modes: normal and dual (the swapped LM-head mode
+// has its own kernel); K chunks only as split-K.
 // Every wave executes exactly 1 + K/64 workgroup barriers, whichever role it has.
 #pragma once
 
@@ -18,12 +20,15 @@
 namespace hsd {
 
 using GemmCfgWS = GemmCfg<128, 128, 64, 2, 2>;
+using GemmCfgWS64 = GemmCfg<64, 128, 64, 2, 2>;
 
-// grid: (tiles_act * tiles_w, k_chunks or 1), 512 threads, GemmCfgWS::kSmemBytes dynamic LDS.
-template <typename Epi>
+// Cfg: a configuration with four (multiplying) waves.
+// grid: (tiles_act * tiles_w, k_chunks or 1), 512 threads, Cfg::kSmemBytes dynamic LDS.
+template <typename Cfg, int MODE, typename Epi>
 __global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, int k_chunks, const bf16 *__restrict__ A,
                                                       const bf16 *__restrict__ W, Epi epi) {
-  using Cfg = GemmCfgWS;
+  static_assert(Cfg::kThreads == 256 && Cfg::BK == 64, "four multiplying waves, 64-wide K slices");
+  static_assert(MODE == kModeNormal || MODE == kModeDual, "normal or dual mode");
   constexpr int BP = Cfg::BP, BQ = Cfg::BQ, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN, LS = Cfg::kStride;
   constexpr int NT = 256, CH = Cfg::kChunks, LP = Cfg::kLoadsP, LQ = Cfg::kLoadsQ;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -32,9 +37,9 @@ __global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, int k
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const bool mover = wave >= 4;
   int tiles_act, tiles_w, ta, tw;
-  gemm_tiles<Cfg, kModeNormal>(M, N, tiles_act, tiles_w);
-  gemm_tile_of(blockIdx.x, M, N, tiles_act, tiles_w, ta, tw);
-  const int m0 = ta * BP, n0 = tw * BQ;
+  gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
+  gemm_tile_of(blockIdx.x, M, (MODE == kModeDual) ? 2 * N : N, tiles_act, tiles_w, ta, tw);
+  const int m0 = ta * BP, n0 = tw * ((MODE == kModeDual) ? BQ / 2 : BQ);
   const bool split = gridDim.y > 1;
   const int k_len = K / k_chunks, nk = k_len / BK;
   const int kc0 = split ? static_cast<int>(blockIdx.y) * k_len : 0;
@@ -51,7 +56,16 @@ __global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, int k
 #pragma unroll
     for (int i = 0; i < LQ; ++i) {
       const int c = tp + NT * i, r = c / CH, kc = c % CH;
-      srcQ[i] = W + static_cast<size_t>(min(n0 + r, N - 1)) * K + kc0 + kc * 8;
+      int row;
+      if (MODE == kModeDual) {
+        // Q row r: wave column r / WNC, 32-row sub-tile (r % WNC) / 32 (even: gate, odd: up), lane row r % 32
+        constexpr int WNC = BQ / Cfg::WN;
+        const int wq = r / WNC, tn = (r % WNC) >> 5, j = r & 31;
+        row = min(((tn & 1) ? N : 0) + n0 + wq * (WNC / 2) + (tn >> 1) * 32 + j, 2 * N - 1);
+      } else {
+        row = min(n0 + r, N - 1);
+      }
+      srcQ[i] = W + static_cast<size_t>(row) * K + kc0 + kc * 8;
     }
     u32x4 regP[2][LP], regQ[2][LQ];
     // requests are unconditional (past the last slice they re-read the last one; the LDS store that follows fills a
@@ -138,7 +152,7 @@ __global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, int k
   }
   // the moving waves have left; their last LDS stores came before the last barrier, so the stages are free for
   // the epilogue's staging
-  gemm_epilogue<Cfg, kModeNormal>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(split ? blockIdx.y : -1, M),
+  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(split ? blockIdx.y : -1, M),
                                   reinterpret_cast<float *>(smem_raw));
 }
 

@@ -207,11 +207,11 @@ int launch_gemm_mfma8(hipStream_t st, int M, int N, int K, const void *A, const 
   return launch_gemm_mfma8_impl<Epi, false>(st, M, N, K, A, W, epi, 1);
 }
 
-template <typename Epi>
+template <typename Cfg, typename Epi>
 int launch_gemm_mfma_ws(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks,
                         bool split) {
-  using Cfg = GemmCfgWS;
-  auto kern = k_gemm_mfma_ws<Epi>;
+  constexpr int MODE = GemmModeOf<Epi>::value;
+  auto kern = k_gemm_mfma_ws<Cfg, MODE, Epi>;
   constexpr int smem = Cfg::kSmemBytes;
   static bool attr_done = false;
   if (!attr_done) {
@@ -222,7 +222,7 @@ int launch_gemm_mfma_ws(hipStream_t st, int M, int N, int K, const void *A, cons
   }
   if (k_chunks > 1 && !split) return HSD_EINVAL;   // K chunks only as split-K
   int tiles_act, tiles_w;
-  gemm_tiles<Cfg, kModeNormal>(M, N, tiles_act, tiles_w);
+  gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
   hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w, split ? k_chunks : 1), dim3(512), smem, st, M, N, K, k_chunks,
                      static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), epi);
   HSD_LAUNCH_CHECK();
@@ -237,7 +237,8 @@ using GemmCfg6 = GemmCfg<256, 128, 64, 4, 2>;   // 8 waves, wave tile 64x64
 using GemmCfg2 = GemmCfg<64, 128, 64, 2, 2>;    // small tiles for narrow projections (more workgroups)
 using GemmCfg3 = GemmCfg<128, 64, 64, 2, 1>;
 using GemmCfg5 = GemmCfg<128, 128, 64, 4, 2>;   // 8 waves, wave tile 32x64
-// configuration 7 = k_gemm_mfma_ws (128x128 tile, four multiplying and four moving waves), 8 = k_gemm_mfma8
+// configurations 7 and 9 = k_gemm_mfma_ws (128x128 / 64x128 tile, four multiplying and four moving waves),
+// 8 = k_gemm_mfma8
 
 
 // Tile configuration actually used at a call site for a given problem (the launch and everything sized from the
@@ -246,16 +247,18 @@ template <typename T>
 int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_chunks, bool split) {
   if (!std::is_same<T, bf16>::value || ctx->force_simple || K % 64 != 0) return -1;
   int cfg = ctx->gemm_cfg[site];
-  if (cfg < 0 || cfg > 8) cfg = 0;
+  if (cfg < 0 || cfg > 9) cfg = 0;
   // The tile shape never changes a result bit (every output element sums its K slices in the same order), so it
   // may follow the row count and the path stays batch-invariant.  A kernel's time is set by one workgroup's walk
   // over K plus fixed costs as long as the launch fits the chip in one round, so fewer rows take smaller tiles: more
   // workgroups, each with less arithmetic per K slice (measured per site on the 24-layer model at 16 to 1856 rows).
   if (!ctx->gemm_cfg_forced) {
-    if (M <= 64) cfg = 2;                                              // token-by-token decoding: one row tile
-    else if (site == kSiteQKV || site == kSiteDown) cfg = M <= 1024 ? 2 : 7;   // 7: 128x128 with moving waves
-    else if (site == kSiteGateUp) cfg = M <= 256 ? 2 : (M <= 768 ? 0 : cfg);
-    else if (site == kSiteLM) cfg = M <= 128 ? 0 : cfg;
+    // 9 / 7: 64x128 / 128x128 tiles with separate operand-moving waves
+    if (site == kSiteLM) cfg = M <= 128 ? 0 : cfg;
+    else if (M <= 64) cfg = 9;                                         // token-by-token decoding: one row tile
+    else if (site == kSiteQKV || site == kSiteDown) cfg = M <= 1024 ? 9 : 7;
+    else if (site == kSiteO) cfg = 9;
+    else if (site == kSiteGateUp) cfg = M <= 256 ? 9 : (M <= 768 ? 7 : cfg);
   }
   // ... and a pass over many rows (prefill chunks, long-document blocks) has enough row tiles to fill the chip with
   // the 256x256 tile also on the narrower projections (measured crossover: about 6 k rows at N = 1536)
@@ -266,8 +269,8 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_
     const int64_t t8 = rt * ((N + 255) / 256), t6 = rt * ((N + 127) / 128);
     cfg = ((t6 + cu - 1) / cu) * 575 < ((t8 + cu - 1) / cu) * 900 ? 6 : 8;   // only on a clear (10 %) advantage
   }
-  // the two-role 128x128 kernel: normal-mode sites only, K chunks only as split-K
-  if (cfg == 7 && (site == kSiteGateUp || site == kSiteLM || (k_chunks > 1 && !split))) cfg = 0;
+  // the two-role kernels: not for the swapped LM-head mode, K chunks only as split-K
+  if ((cfg == 7 || cfg == 9) && (site == kSiteLM || (k_chunks > 1 && !split))) cfg = cfg == 7 ? 0 : 2;
   // the 8-wave kernel walks its K chunks itself (no split-K form), each an even number (>= 4) of 64-wide slices
   const int k_len = K / k_chunks;
   if (cfg == 8 && (split || k_len % 128 != 0 || k_len < 256)) cfg = 0;
@@ -297,7 +300,12 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
       case 5: return launch_gemm_mfma<GemmCfg5>(st, M, N, K, A, W, epi, k_chunks, split);
       case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi, k_chunks, split);
       case 7:
-        if constexpr (GemmModeOf<Epi>::value == kModeNormal) return launch_gemm_mfma_ws(st, M, N, K, A, W, epi, k_chunks, split);
+        if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
+          return launch_gemm_mfma_ws<GemmCfgWS>(st, M, N, K, A, W, epi, k_chunks, split);
+        break;
+      case 9:
+        if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
+          return launch_gemm_mfma_ws<GemmCfgWS64>(st, M, N, K, A, W, epi, k_chunks, split);
         break;
       case 8: return launch_gemm_mfma8(st, M, N, K, A, W, epi, k_chunks);
       default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi, k_chunks, split);
