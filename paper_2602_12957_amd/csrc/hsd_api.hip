@@ -258,7 +258,7 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_
     else if (M <= 64) cfg = 9;                                         // token-by-token decoding: one row tile
     else if (site == kSiteQKV || site == kSiteDown) cfg = M <= 1024 ? 9 : 7;
     else if (site == kSiteO) cfg = 9;
-    else if (site == kSiteGateUp) cfg = M <= 256 ? 9 : (M <= 768 ? 7 : cfg);
+    else if (site == kSiteGateUp) cfg = M <= 256 ? 9 : (M <= 1024 ? 7 : cfg);
   }
   // ... and a pass over many rows (prefill chunks, long-document blocks) has enough row tiles to fill the chip with
   // the 256x256 tile also on the narrower projections (measured crossover: about 6 k rows at N = 1536)
