@@ -64,7 +64,7 @@ typedef struct hsd_model_desc {
   int32_t kv_block_tokens;
   float rms_eps, rope_theta;
   /* Attention key split (bf16 models; a deployment choice, not part of the architecture).  0: every query tile
-   * walks all of its keys in one workgroup.  c > 0 (a multiple of 64): the keys of a sequence are cut at the
+   * walks all of its keys in one workgroup.  c > 0 (a multiple of 128): the keys of a sequence are cut at the
    * absolute positions c, 2c, ... (at most 8 chunks; the last is open ended), each chunk is scored by a workgroup
    * of its own and the chunks of a row are folded in ascending order.  Gives short, wide batches (region-level
    * drafts over ~1k cached tokens: c = 512) and single long drafts (c = 1024) the parallelism to fill the chip;
@@ -183,12 +183,15 @@ int hsd_verify_region_batch(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool,
                             void *workspace, size_t ws_bytes);
 
 /* Page-level verification (Section 3.1 Stage 2, Eq. 4): few long draft blocks.  Same semantics and
- * outputs as hsd_verify_region_batch; the kernels are tiled for long blocks. */
+ * outputs as hsd_verify_region_batch, and the same bits for every row (a row's arithmetic does not depend on the
+ * entry point).  The attention workgroups are twice as large here (64 query rows of four query heads share each
+ * 128-key K/V stage in LDS instead of 32), which halves the K/V traffic per query of a long block; batches of
+ * many short blocks are better served by the smaller workgroups of hsd_verify_region_batch. */
 int hsd_verify_page(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch,
                     void *workspace, size_t ws_bytes);
 
-/* KV maintenance after a verify (the "accept/reject control flow, rollbacks, KV-cache maintenance"
- * part of the decoding loop, Section 4.2).  For each sequence with accept_len[s] = alpha >= 0:
+/* KV maintenance after a verify: the cache upkeep and the rollback of rejected rows that Section 4.2 counts
+ * into the decoding time.  For each sequence with accept_len[s] = alpha >= 0:
  * seq_len += 1 + alpha (the pending token and the accepted draft tokens become committed context);
  * pending_out[s] = bonus[s].  With alpha < 0: pure rollback, seq_len and pending_out[s] unchanged.
  * In both cases blocks lying wholly beyond the new length go back to the pool and their
@@ -223,6 +226,30 @@ enum {
 };
 int hsd_profile_enable(hsd_ctx *ctx, int which, int32_t max_launches);
 int hsd_profile_read(hsd_ctx *ctx, int32_t *n_launches, float *total_ms);
+
+/* Debug and experiment controls (not a step of the method; production callers never need them).  They change how
+ * the work is launched, never what a row's result is, except HSD_DEBUG_FORCE_SIMPLE (other kernels, other rounding).
+ *   HSD_DEBUG_SYNC_LAYERS   value != 0: the verify/prefill calls WAIT for the stream after every layer (an
+ *                           exception to "never synchronises"; bounds the launches in flight for counter tools)
+ *   HSD_DEBUG_FORCE_SIMPLE  value != 0: bf16 models run the plain fp32-FMA kernels (cross-check of the MFMA path)
+ *   HSD_DEBUG_SPLIT_ROWS    largest row count for which the down projection runs as split-K (lowered by tests to
+ *                           reach the chunk-walking form with few rows)
+ *   HSD_DEBUG_KCHUNKS_O / _DOWN   K chunks of the O / down projection, 1..4 (0 = default)
+ *   HSD_DEBUG_GEMM_CFG_*    tile configuration (0..9) of one GEMM call site, used for every row count
+ * Returns HSD_EINVAL for an unknown knob or a value out of range. */
+enum {
+  HSD_DEBUG_SYNC_LAYERS = 1,
+  HSD_DEBUG_FORCE_SIMPLE = 2,
+  HSD_DEBUG_SPLIT_ROWS = 3,
+  HSD_DEBUG_KCHUNKS_O = 4,
+  HSD_DEBUG_KCHUNKS_DOWN = 5,
+  HSD_DEBUG_GEMM_CFG_QKV = 6,
+  HSD_DEBUG_GEMM_CFG_O = 7,
+  HSD_DEBUG_GEMM_CFG_GATE_UP = 8,
+  HSD_DEBUG_GEMM_CFG_DOWN = 9,
+  HSD_DEBUG_GEMM_CFG_LM_HEAD = 10
+};
+int hsd_debug_set(hsd_ctx *ctx, int knob, int64_t value);
 
 #ifdef __cplusplus
 }

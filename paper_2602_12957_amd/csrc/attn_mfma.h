@@ -4,18 +4,31 @@
 // sequence s at absolute position p attends to the cached positions 0..p of s -- the accepted prefix plus
 // the rows before it in its own block, which the QKV epilogue appended to the pages just before.
 //
-// Work split.  A workgroup (4 waves) owns one (sequence, kv head, tile of query rows); its waves are the
-// query heads that share the kv head (GQA) and/or 32-row sub-tiles, so every K/V tile staged in LDS is used
-// by all of them.  Each wave keeps 32 queries: lane l <-> query l % 32.
+// Work split.  A workgroup owns one (sequence, kv head, tile of query rows).  Its waves come in pairs: the two
+// waves of a pair hold the same 32 queries of one query head (lane l <-> query l % 32) and share every
+// 128-key stage between them, the first taking keys 0-63 of the stage and the second keys 64-127 ("parity").
+// The pairs of a workgroup are the query heads that share the kv head (GQA) and/or further 32-row sub-tiles,
+// so every K/V stage in LDS is used by all of them: 4 pairs per workgroup for region-level batches (many short
+// blocks, Eq. 2), 8 pairs for page-level ones (few long blocks, Eq. 4: twice the reuse of each stage).
+//
+// One row's arithmetic is the same in every variant and every batch: its keys are visited in 64-key groups at
+// absolute positions, even groups by one accumulator set and odd groups by another, in ascending order, and the
+// two sets are folded at the end (even first).  Verification of a block and token-by-token decoding therefore give
+// the same bits.
 //
 // Orientation.  Both products are computed transposed so that a lane owns ONE query:
-//   S^T = K Q^T   (MFMA i = key, j = query)  -> the lane's 16 registers per tile are 16 keys of its query:
+//   S^T = K Q^T   (MFMA i = key, j = query)  -> the lane's 32 registers per step are 32 keys of its query:
 //                 row max / row sum are in-register plus one exchange between the two lane halves;
 //   O^T = V^T P^T (MFMA i = head dim, j = query) -> rescaling by the softmax correction is a per-lane scalar.
 // P^T is fed straight from the S^T registers as the B operand.  Register v of lane half h holds key
 // 8*(v/4) + 4h + v%4, so the contraction slots of a 16-key step are keys {4h..4h+3, 8+4h..8+4h+3}; the V
 // pages are stored transposed and in exactly that token order ([dim][perm(token)], see kv_v_slot), hence the
 // A operand of the second product is one 16-byte LDS read per lane and no transpose is ever done here.
+//
+// The key loop has two forms.  Stages whose every key is visible to every query of the workgroup (the bulk of a
+// cached prefix) run with no mask, no validity checks and no special cases; the last one or two stages of a
+// workgroup (the diagonal of the causal mask, the tree-ancestry mask, the partly filled last page) run the
+// checked form.
 #pragma once
 
 #include "common.h"
@@ -24,14 +37,16 @@
 
 namespace hsd {
 
+constexpr int kAttnKeys = 128;            // keys per LDS stage: 8 pages; keys 0-63 for parity 0, 64-127 for parity 1
 constexpr int kKsStride = kHd + 8;        // bf16 per K row in LDS (16 B pad: conflict-free 128-bit reads)
-constexpr int kVtStride = kBlk + 8;       // bf16 per (page, dim) row of V^T in LDS (48 B)
-// One LDS stage holds a tile of 32*KQ keys (2*KQ pages): K rows, then V^T rows.  bf16 elements per stage:
-constexpr int attn_stage_elems(int kq) { return 32 * kq * kKsStride + 2 * kq * kHd * kVtStride; }
-// Dynamic LDS of k_attn_mfma<., KQ>: two stages, reused after the key loop for the merge of the KQ - 1 partial
-// results of each of the QS query sets (34 floats per lane).
-constexpr size_t attn_smem_bytes(int kq, int qs) {
-  const size_t stages = 2 * static_cast<size_t>(attn_stage_elems(kq)) * 2, merge = static_cast<size_t>(kq - 1) * qs * 34 * 64 * 4;
+constexpr int kVtStride = kAttnKeys + 8;  // bf16 per V^T row (one head dim, the 8 pages' token slots side by side;
+                                          // 16 B pad: a row is 68 dwords, so the 128-bit reads of 16 consecutive
+                                          // dims, and the stores of 16 consecutive dims, cover all 64 banks once)
+constexpr int kAttnStage = kAttnKeys * kKsStride + kHd * kVtStride;   // bf16 elements per stage: K rows, then V^T rows
+// Dynamic LDS of k_attn_mfma: two stages, reused after the key loop for handing the odd-parity partial results of
+// each of the QS query sets (34 floats per lane) to their even-parity partners.
+constexpr size_t attn_smem_bytes(int qs) {
+  const size_t stages = 2 * static_cast<size_t>(kAttnStage) * 2, merge = static_cast<size_t>(qs) * 34 * 64 * 4;
   return stages > merge ? stages : merge;
 }
 
@@ -76,7 +91,7 @@ __global__ void __launch_bounds__(1024) k_attn_tiles(int n_seq, const int32_t *_
 }
 
 // Key split.  With `chunk_keys` > 0 the keys of every sequence are cut at the absolute positions chunk_keys,
-// 2*chunk_keys, ... (a multiple of the 64-key tile; chunk kAttnMaxChunks - 1 is open ended) and each chunk of a
+// 2*chunk_keys, ... (a multiple of the 128-key stage; chunk kAttnMaxChunks - 1 is open ended) and each chunk of a
 // query tile goes to a workgroup of its own (grid z), which leaves its un-normalised (max, sum, O^T) in `part_*`;
 // k_attn_merge folds the chunks of a row in ascending order.  The cut points depend on absolute positions only,
 // never on the batch, so a row gets the same bits whether it is scored in a long block or alone; what changes
@@ -96,25 +111,21 @@ union Frag8 {
   uint16_t h[8];
 };
 
-// QS = query sets (waves' worth of 32 queries x one head) per workgroup: 1, 2, 4 or 8.
-// G4 = query heads of one kv head among them (1, 2 or 4, G4 <= QS); QS/G4 row sub-tiles of 32 queries.
-// KQ = key parts per tile (2 or 4).  The workgroup has QS*KQ waves: waves w, w+QS, ... own the same 32 queries
-// and split every tile of 32*KQ keys between them (32 keys each), which multiplies the waves in flight per query
-// tile and divides the number of sequential tile steps; their partial (max, sum, O^T) are merged through LDS at
-// the end, always in the same order, so results do not depend on timing.  Fewer query sets per workgroup mean
-// more, smaller workgroups (finer load balance over the CUs) at the price of staging each K/V tile more often.
+// QS = query sets (pairs of waves; 32 queries x one head each) per workgroup: 4 (region-level) or 8 (page-level).
+// G4 = query heads of one kv head among them (1, 2 or 4); QS/G4 row sub-tiles of 32 queries.
+// Waves w and w + QS form a pair: same queries, parity 0 / 1 of every stage.  Their partial (reference point, sum,
+// O^T) are folded through LDS at the end, always in the same order, so results do not depend on timing.
 // TREE selects the tree-ancestry mask (row_end = packed index one past each row's subtree) instead of the causal one.
 // SPLIT: grid z = key chunk (see AttnSplit); results go to the partial buffers instead of `out`.
-// grid: (upper bound of query tiles, n_kv_heads * ceil(group / G4), chunks), block 64*QS*KQ, dynamic LDS
-// attn_smem_bytes(KQ, QS).
-template <int G4, int KQ, int QS, bool TREE, bool SPLIT>
-__global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_q_heads, const AttnTile *__restrict__ tiles, PagedKV kv,
-                                                   const bf16 *__restrict__ q, bf16 *__restrict__ out,
-                                                   const int32_t *__restrict__ row_end, AttnSplit sp) {
-  constexpr int kAttnKeys = 32 * KQ, kAttnStage = attn_stage_elems(KQ);
-  // threads; 16-byte K (and V) pieces staged per thread and tile (with 8 query sets only the first 256*KQ threads stage)
-  constexpr int NT = 64 * QS * KQ, NS = QS >= 4 ? 1 : 4 / QS;
-  const bool stager = QS <= 4 || threadIdx.x < 256 * KQ;
+// grid: (upper bound of query tiles, n_kv_heads * ceil(group / G4), chunks), block 128*QS, dynamic LDS
+// attn_smem_bytes(QS).
+template <int G4, int QS, bool TREE, bool SPLIT>
+__global__ void __launch_bounds__(128 * QS) k_attn_mfma(int n_q_heads, const AttnTile *__restrict__ tiles, PagedKV kv,
+                                                        const bf16 *__restrict__ q, bf16 *__restrict__ out,
+                                                        const int32_t *__restrict__ row_end, AttnSplit sp) {
+  // staging: the 8 pages of a stage are spread over the 2*QS waves; a page's K is 128 16-byte pieces, its V^T too
+  constexpr int NS = 8 / QS;                      // K pieces (and V^T pieces) per lane and stage: 2 or 1
+  static_assert(QS == 4 || QS == 8, "a stage's 8 pages are staged by 8 or 16 waves");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   uint16_t *smem = reinterpret_cast<uint16_t *>(smem_raw);
   constexpr int SUB = QS / G4, QT = 32 * SUB;
@@ -129,17 +140,19 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_q_heads, const
 
   const int group = n_q_heads / kv.n_kv_heads, hb = (group + G4 - 1) / G4;
   const int kvh = blockIdx.y / hb, hgrp = blockIdx.y % hb;
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5, qj = lane & 31;
-  const int wq = wave % QS, kh = wave / QS;                        // query-set index, key part of each tile
+  const int t = threadIdx.x, lane = t & 63, half = lane >> 5, qj = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wq = wave % QS, par = wave / QS;                       // query-set index, parity of the wave
   const int head = kvh * group + hgrp * G4 + (wq % G4);
-  const int row0 = tile_in_seq * QT + (wq / G4) * 32;              // first query row (within the block) of this wave
+  const int row0_wg = tile_in_seq * QT;
+  const int row0 = row0_wg + (wq / G4) * 32;                       // first query row (within the block) of this wave
   const bool wave_active = row0 < Lq;
   const int my_row = min(row0 + qj, Lq - 1);
   const int pos_j = S + my_row;                                    // absolute position of the lane's query
   const int wave_keys = S + min(row0 + 32, Lq);                    // keys any query of this wave can see
-  const int wg_keys = S + min(tile_in_seq * QT + QT, Lq);          // ... of this workgroup
+  const int wg_keys = S + min(row0_wg + QT, Lq);                   // ... of this workgroup
   const int n_valid = S + Lq;                                      // positions holding data of this round
-  // tiles kt0 .. kt1-1 of 32*KQ keys are this workgroup's
+  // stages kt0 .. kt1-1 of 128 keys are this workgroup's
   int key_lo = 0, key_hi = wg_keys;
   if constexpr (SPLIT) {
     key_lo = static_cast<int>(blockIdx.z) * sp.chunk_keys;
@@ -147,6 +160,9 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_q_heads, const
     if (blockIdx.z + 1 < kAttnMaxChunks) key_hi = min(wg_keys, key_lo + sp.chunk_keys);
   }
   const int kt0 = key_lo / kAttnKeys, kt1 = (key_hi + kAttnKeys - 1) / kAttnKeys;
+  // stages before kt_plain need no mask and no checks: every key lies in the cached prefix (tree) or at or before
+  // the workgroup's first query (chain), hence holds data and is visible to every query of the workgroup
+  const int kt_plain = min(kt1, (TREE ? S : S + row0_wg + 1) / kAttnKeys);
   const int qdim = n_q_heads * kHd;
 
   // ---- query fragments (B operand of S^T): lane holds dims 16*kk + 8*half .. +7 of its query
@@ -159,58 +175,50 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_q_heads, const
 
   const bf16 *kpool = static_cast<const bf16 *>(kv.k_pool);
   const bf16 *vpool = static_cast<const bf16 *>(kv.v_pool);
-  // Staging: piece c = t + NT*i (i < NS) is one 16-byte piece of K (key c/8, piece c%8) and one of V^T (page
-  // c/128, dim (c%128)/2, half row c%2); both lie in page c/128 of the tile.  Page ids are fetched one tile ahead
-  // of the data they address, so the K/V loads of the next tile never wait behind a dependent block-table read.
+  // Staging.  A wave stages (QS = 4) one whole page of every stage or (QS = 8) half a page: piece c of a page is
+  // 16 bytes at byte offset 16*c of the K page (key c/8, dims 8*(c%8)..) and of the V^T page (dim c/2, token slots
+  // 8*(c%2)..).  For V^T a lane takes piece cv = 2*(c%32) + c/32 of its 64-piece group instead of piece c, so that 16
+  // consecutive lanes write 16 consecutive dims (LDS rows) and never two halves of one row.  The page id is therefore uniform per wave: it is read through the scalar unit (constant address
+  // space: the table is not written while this kernel runs), one stage ahead of the data it addresses, and the page
+  // offset is scalar arithmetic.
+  const int pgw = (QS == 4) ? wave : (wave >> 1);                  // page of the stage this wave stages
+  const int c0 = (QS == 4) ? lane : ((wave & 1) * 64 + lane);      // first K piece of the lane; piece i is c0 + 64*i
+  const int cv0 = c0 - lane + 2 * (lane & 31) + (lane >> 5);       // first V^T piece
   u32x4 rk[NS], rv[NS];
-  int bid[NS];
-  bool bid_ok[NS];
-  // The pages of a tile are uniform per wave (a wave stages half a page of K and of V^T), so their ids are read
-  // through the scalar unit (constant address space: the table is not written while this kernel runs) and the page
-  // offsets are scalar arithmetic.  fetch_id only ISSUES the read (index clamped to the table row; whether the
-  // entry means anything is settled without looking at it): examining the id here would stall the wave for a
-  // memory latency every iteration.
+  int bid;
   typedef const int32_t __attribute__((address_space(4))) *TablePtr;
   const TablePtr table_row = (TablePtr)(kv.block_table + static_cast<size_t>(slot) * kv.max_blocks_per_seq);
-  auto fetch_id = [&](int kt) {
-    if (!stager) return;
-#pragma unroll
-    for (int i = 0; i < NS; ++i) {
-      const int page = kt * (kAttnKeys / kBlk) + __builtin_amdgcn_readfirstlane((t + NT * i) >> 7);
-      bid_ok[i] = page * kBlk < n_valid && page < kv.max_blocks_per_seq;
-      bid[i] = table_row[min(page, kv.max_blocks_per_seq - 1)];
-    }
-  };
-  // prefetch only ISSUES the loads; nothing here may depend on the loaded values, or the wave would wait for
-  // them on the spot and the whole point of requesting a tile ahead would be lost
+  const int last_entry = kv.max_blocks_per_seq - 1;
+  // fetch_id only ISSUES the read (index clamped to the table row); examining the id here would stall the wave
+  // for a memory latency every iteration
+  auto fetch_id = [&](int kt) { bid = table_row[min(kt * (kAttnKeys / kBlk) + pgw, last_entry)]; };
+  // prefetch only ISSUES the loads.  They are unconditional: an id that is out of range (a page beyond the data of
+  // this round, a damaged table) reads block 0 instead; every position such a page could stand for is masked (and
+  // its V zeroed) by the checked form of the loop, and the plain form only sees pages of the cached prefix.
   auto prefetch = [&]() {
-    if (!stager) return;
-    // unconditional loads: a page that is absent (beyond the data of this round, id out of range) reads block 0
-    // instead; such a page lies wholly past n_valid, so store_lds zeroes its V and the causal mask discards its
-    // scores.  A branch here would make the compiler wait for the loads inside it.
+    const int b = (bid >= 0 && bid < kv.n_blocks) ? bid : 0;
+    const size_t off = kv_block_offset(kv, b, kvh);
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
-      const int c = t + NT * i;
-      const int b = (bid_ok[i] && bid[i] >= 0 && bid[i] < kv.n_blocks) ? bid[i] : 0;
-      const size_t off = kv_block_offset(kv, b, kvh);
-      rk[i] = *reinterpret_cast<const u32x4 *>(kpool + off + ((c >> 3) & 15) * kHd + (c & 7) * 8);
-      rv[i] = *reinterpret_cast<const u32x4 *>(vpool + off + ((c & 127) >> 1) * kBlk + (c & 1) * 8);
+      rk[i] = *reinterpret_cast<const u32x4 *>(kpool + off + (c0 + 64 * i) * 8);
+      rv[i] = *reinterpret_cast<const u32x4 *>(vpool + off + (cv0 + 64 * i) * 8);
     }
   };
-  // kt = tile the staged registers belong to
-  auto store_lds = [&](int stage, int kt) {
-    if (!stager) return;
+  // kt = stage the staged registers belong to
+  auto store_lds = [&](int stage, int kt, bool checked) {
     uint16_t *ks = smem + stage * kAttnStage, *vt = ks + kAttnKeys * kKsStride;
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
-      const int c = t + NT * i, pg = c >> 7, vd = (c & 127) >> 1, hf = c & 1;
-      *reinterpret_cast<u32x4 *>(ks + (c >> 3) * kKsStride + (c & 7) * 8) = rk[i];
+      const int c = c0 + 64 * i;
+      *reinterpret_cast<u32x4 *>(ks + (pgw * kBlk + (c >> 3)) * kKsStride + (c & 7) * 8) = rk[i];
       u32x4 f = rv[i];
-      const int p0 = kt * kAttnKeys + pg * kBlk;
-      if (p0 + kBlk > n_valid) {
-        // last, partly filled page: slots of positions that hold no data of this sequence must read as 0
+      const int cv = cv0 + 64 * i;
+      const int p0 = kt * kAttnKeys + pgw * kBlk;
+      if (checked && p0 + kBlk > n_valid) {
+        // partly filled (or absent) page: slots of positions that hold no data of this sequence must read as 0
         // (their probability is 0, but 0 * stale-NaN would poison the product).  Element e of the piece is
         // token 4*hf + e (e < 4) or 8 + 4*hf + e - 4; two elements per 32-bit word.
+        const int hf = cv & 1;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
           const int tok0 = (w < 2) ? 4 * hf + 2 * w : 8 + 4 * hf + 2 * (w - 2);
@@ -220,7 +228,7 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_q_heads, const
           f[w] &= keep;
         }
       }
-      *reinterpret_cast<u32x4 *>(vt + (pg * kHd + vd) * kVtStride + hf * 8) = f;
+      *reinterpret_cast<u32x4 *>(vt + (cv >> 1) * kVtStride + pgw * kBlk + (cv & 1) * 8) = f;
     }
   };
 
@@ -232,120 +240,155 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_q_heads, const
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = 0.125f * 1.4426950408889634f;  // 1/sqrt(64) * log2(e): softmax in base 2
 
-  // Pipeline: K/V of tile kt+2 and the page ids of tile kt+3 are requested at the top of iteration kt, right after
-  // the staging registers (tile kt+1, requested one whole iteration earlier, so long since arrived) were written to
+  // One stage of this wave: its 64 keys (parity `par`) against its 32 queries.  CHECKED adds the masks.
+  auto step = [&](int kt, auto checked_tag) {
+    constexpr bool CHECKED = decltype(checked_tag)::value;
+    const int kb = kt * kAttnKeys + par * 64;   // first key of this wave's part of the stage
+    if (CHECKED && !(wave_active && kb < wave_keys)) return;
+    const uint16_t *ks = smem + (kt & 1) * kAttnStage, *vt = ks + kAttnKeys * kKsStride;
+    floatx16 st[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) st[b][v] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        bf16x8 a = *reinterpret_cast<const bf16x8 *>(ks + (par * 64 + b * 32 + qj) * kKsStride + kk * 16 + half * 8);
+        st[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk].v, st[b], 0, 0, 0);
+      }
+    }
+    // scores stay unscaled; the softmax scale rides in the exponent's fused multiply-add
+    if constexpr (CHECKED) {
+      if constexpr (TREE) {
+        // packed prefix tree (tree-ancestry mask): inside the block, the key in slot S + p is visible to local
+        // row r iff p is r itself or an ancestor of r, i.e. p <= r < end of p's subtree (rows are in pre-order)
+        if (kb + 63 >= S) {  // the wave's keys reach into the block (wave-uniform)
+          // branch-free: every subtree end is fetched (index clamped into the block) before any is looked at, so
+          // the 32 reads are in flight together
+          int e_sub[2][16];
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int kpos = kb + 32 * b + 8 * (v >> 2) + 4 * half + (v & 3);
+              e_sub[b][v] = row_end[base + min(max(kpos - S, 0), Lq - 1)];
+            }
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int kpos = kb + 32 * b + 8 * (v >> 2) + 4 * half + (v & 3);
+              const bool vis = (kpos <= pos_j) & ((kpos < S) | (e_sub[b][v] > base + my_row));
+              st[b][v] = vis ? st[b][v] : -INFINITY;
+            }
+        }
+      } else if (kb + 63 > S + row0) {  // the wave's keys reach past its first query: causal mask (wave-uniform)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int kpos = kb + 32 * b + 8 * (v >> 2) + 4 * half + (v & 3);
+            if (kpos > pos_j) st[b][v] = -INFINITY;
+          }
+      }
+    }
+    float mx = fmaxf(st[0][0], st[1][0]);
+#pragma unroll
+    for (int v = 1; v < 16; ++v) mx = fmaxf(fmaxf(mx, st[0][v]), st[1][v]);
+    mx = half_max(mx);
+    // The running reference point is kept as an INTEGER in the base-2 exponent domain (the smallest integer
+    // >= max score * scale seen so far).  Every correction factor is then an exact power of two, and the bf16
+    // rounding of a probability no longer depends on which stage it was computed in: rounding commutes with
+    // powers of two.  Probabilities lie in (0, 1].
+    const float m_new = fmaxf(m_run, ceilf(mx * sc));
+    // a query that has seen no visible key yet keeps -inf (checked form only: its first keys lie in the other
+    // parity); the reference point 0 then yields p = 0 and corr = 0 without producing inf - inf
+    const float msc = (CHECKED && m_new == -INFINITY) ? 0.f : m_new;
+    // the reference point is an integer and seldom moves after the first stages; when it moved for no lane
+    // every factor is exactly 1 and the rescale is skipped (wave-uniform branch, same bits either way)
+    if (__any(m_new != m_run)) {
+      const float corr = (m_run == -INFINITY) ? 0.f : ldexpf(1.0f, static_cast<int>(m_run - msc));
+      l_run *= corr;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[i][v] *= corr;
+    }
+    m_run = m_new;
+    bf16x8 pf[4];
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+#pragma unroll
+    for (int pg = 0; pg < 4; ++pg) {
+      floatx8 pv;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        // bare hardware exponential: arguments are <= 0 and results below 2^-126 may flush to zero, far
+        // beneath half a bf16 unit of any probability that matters
+        pv[e] = __builtin_amdgcn_exp2f(fmaf(st[pg >> 1][8 * (pg & 1) + e], sc, -msc));
+      }
+      pf[pg] = __builtin_convertvector(pv, bf16x8);
+      // the row sum takes the probabilities as the second product will see them (rounded to bf16), two per
+      // instruction: l += p0 * 1 + p1 * 1
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[pg], pf[pg], 0, 1), ones, l_run, false);
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[pg], pf[pg], 2, 3), ones, l_run, false);
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[pg], pf[pg], 4, 5), ones, l_run, false);
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[pg], pf[pg], 6, 7), ones, l_run, false);
+    }
+#pragma unroll
+    for (int pg = 0; pg < 4; ++pg)
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        bf16x8 a = *reinterpret_cast<const bf16x8 *>(vt + (i * 32 + qj) * kVtStride + (par * 4 + pg) * kBlk + half * 8);
+        o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[pg], o[i], 0, 0, 0);
+      }
+  };
+
+  // Pipeline: K/V of stage kt+2 and the page id of stage kt+3 are requested at the top of iteration kt, right after
+  // the staging registers (stage kt+1, requested one whole iteration earlier, so long since arrived) were written to
   // the LDS stage that iteration kt-1 finished reading.  No wave ever waits for a load it has just issued, and the
-  // LDS stores run ahead of the tile's arithmetic instead of between it and the barrier.
+  // LDS stores run ahead of the stage's arithmetic instead of between it and the barrier.
   fetch_id(kt0);
   prefetch();
   if (kt0 + 1 < kt1) fetch_id(kt0 + 1);
-  store_lds(kt0 & 1, kt0);
+  store_lds(kt0 & 1, kt0, kt0 >= kt_plain);
   if (kt0 + 1 < kt1) {
     prefetch();
     if (kt0 + 2 < kt1) fetch_id(kt0 + 2);
   }
   __syncthreads();
-  for (int kt = kt0; kt < kt1; ++kt) {
+  int kt = kt0;
+  // plain stages: stage kt+1 may already be a checked one (its store then needs the zeroing of absent positions)
+  for (; kt < kt_plain; ++kt) {
     if (kt + 1 < kt1) {
-      store_lds((kt + 1) & 1, kt + 1);
+      if (kt + 1 < kt_plain) store_lds((kt + 1) & 1, kt + 1, false);
+      else store_lds((kt + 1) & 1, kt + 1, true);
       if (kt + 2 < kt1) {
         prefetch();
         if (kt + 3 < kt1) fetch_id(kt + 3);
       }
     }
-    const int kb = kt * kAttnKeys + kh * 32;   // first key of this wave's half tile
-    if (wave_active && kb < wave_keys) {
-      const uint16_t *ks = smem + (kt & 1) * kAttnStage, *vt = ks + kAttnKeys * kKsStride;
-      floatx16 st;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) st[v] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        bf16x8 a = *reinterpret_cast<const bf16x8 *>(ks + (kh * 32 + qj) * kKsStride + kk * 16 + half * 8);
-        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk].v, st, 0, 0, 0);
-      }
-      // scores stay unscaled; the softmax scale rides in the exponent's fused multiply-add
-      if constexpr (TREE) {
-        // packed prefix tree (tree-ancestry mask): inside the block, the key in slot S + p is visible to local
-        // row r iff p is r itself or an ancestor of r, i.e. p <= r < end of p's subtree (rows are in pre-order)
-        if (kb + 31 >= S) {  // half tile reaches into the block (wave-uniform)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int kpos = kb + 8 * (v >> 2) + 4 * half + (v & 3);
-            bool vis = kpos <= pos_j;
-            if (vis && kpos >= S) vis = row_end[base + kpos - S] > base + my_row;
-            if (!vis) st[v] = -INFINITY;
-          }
-        }
-      } else if (kb + 31 > S + row0) {  // half tile reaches past the wave's first query: causal mask (wave-uniform)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int kpos = kb + 8 * (v >> 2) + 4 * half + (v & 3);
-          if (kpos > pos_j) st[v] = -INFINITY;
-        }
-      }
-      float mx = st[0];
-#pragma unroll
-      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, st[v]);
-      mx = half_max(mx);
-      // The running reference point is kept as an INTEGER in the base-2 exponent domain (the smallest integer
-      // >= max score * scale seen so far).  Every correction factor is then an exact power of two, and the bf16
-      // rounding of a probability no longer depends on which tile (or key half) it was computed in: rounding
-      // commutes with powers of two.  Probabilities lie in (0, 1].
-      const float m_new = fmaxf(m_run, ceilf(mx * sc));
-      // a query that has seen no visible key yet (its first keys lie in the other half tile) keeps -inf;
-      // the reference point 0 then yields p = 0 and corr = 0 without producing inf - inf
-      const float msc = (m_new == -INFINITY) ? 0.f : m_new;
-      const float corr = (m_run == -INFINITY) ? 0.f : ldexpf(1.0f, static_cast<int>(m_run - msc));
-      // the reference point is an integer and seldom moves after the first tiles; when it moved for no lane
-      // every factor is exactly 1 and the rescale is skipped (wave-uniform branch, same bits either way)
-      if (__any(m_new != m_run)) {
-        l_run *= corr;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) o[i][v] *= corr;
-      }
-      bf16x8 pf[2];
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        floatx8 pv;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          // bare hardware exponential: arguments are <= 0 and results below 2^-126 may flush to zero, far
-          // beneath half a bf16 unit of any probability that matters
-          pv[e] = __builtin_amdgcn_exp2f(fmaf(st[8 * kk + e], sc, -msc));
-        }
-        pf[kk] = __builtin_convertvector(pv, bf16x8);
-        // the row sum takes the probabilities as the second product will see them (rounded to bf16), two per
-        // instruction: l += p0 * 1 + p1 * 1
-        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-        const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
-        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[kk], pf[kk], 0, 1), ones, l_run, false);
-        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[kk], pf[kk], 2, 3), ones, l_run, false);
-        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[kk], pf[kk], 4, 5), ones, l_run, false);
-        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[kk], pf[kk], 6, 7), ones, l_run, false);
-      }
-      m_run = m_new;
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        const int pgk = 2 * kh + kk;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          bf16x8 a = *reinterpret_cast<const bf16x8 *>(vt + (pgk * kHd + i * 32 + qj) * kVtStride + half * 8);
-          o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kk], o[i], 0, 0, 0);
-        }
+    step(kt, std::false_type{});
+    __syncthreads();
+  }
+  for (; kt < kt1; ++kt) {
+    if (kt + 1 < kt1) {
+      store_lds((kt + 1) & 1, kt + 1, true);
+      if (kt + 2 < kt1) {
+        prefetch();
+        if (kt + 3 < kt1) fetch_id(kt + 3);
       }
     }
+    step(kt, std::true_type{});
     __syncthreads();
   }
 
-  // ---- merge the KQ key parts of each query set through LDS (stage memory is free after the last barrier):
-  // part 0 folds in parts 1, 2, ... in that order
-  float *mrg = reinterpret_cast<float *>(smem_raw);   // [KQ - 1][QS query sets][34][64 lanes]
+  // ---- fold the two parities of each query set through LDS (stage memory is free after the last barrier):
+  // parity 0 takes in parity 1
+  float *mrg = reinterpret_cast<float *>(smem_raw);   // [QS query sets][34][64 lanes]
   l_run = half_sum(l_run);
-  if (kh > 0) {
-    float *dst = mrg + ((kh - 1) * QS + wq) * 34 * 64 + lane;
+  if (par == 1) {
+    float *dst = mrg + wq * 34 * 64 + lane;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -354,13 +397,12 @@ __global__ void __launch_bounds__(64 * QS * KQ) k_attn_mfma(int n_q_heads, const
     dst[33 * 64] = l_run;
   }
   __syncthreads();
-  if (kh == 0 && wave_active && row0 + qj < Lq) {
-#pragma unroll
-    for (int part = 1; part < KQ; ++part) {
-      const float *src = mrg + ((part - 1) * QS + wq) * 34 * 64 + lane;
+  if (par == 0 && wave_active && row0 + qj < Lq) {
+    {
+      const float *src = mrg + wq * 34 * 64 + lane;
       const float m_b = src[32 * 64], l_b = src[33 * 64];
-      // integer exponents: exact powers of two.  Unsplit, part 0 is never empty (key 0 is in its first tile); a
-      // chunk of a split pass may hold no visible key for a row in either part
+      // integer exponents: exact powers of two.  Unsplit, parity 0 is never empty (key 0 is in its first stage); a
+      // chunk of a split pass may hold no visible key for a row in either parity
       const float m_tot = fmaxf(m_run, m_b);
       const float ca = (m_run > -INFINITY) ? ldexpf(1.0f, static_cast<int>(m_run - m_tot)) : 0.f;
       const float cb = (m_b > -INFINITY) ? ldexpf(1.0f, static_cast<int>(m_b - m_tot)) : 0.f;

@@ -31,12 +31,13 @@ struct hsd_ctx {
   std::vector<const float *> attn_norm, ffn_norm;
   std::vector<const void *> wqkv, wo, w_gate_up, w_down;
   int n_cu;
-  bool sync_layers = false;  // HSD_SYNC_LAYERS=1: wait for the stream after every layer (bounds the launches in flight
-                             // for tools that track each dispatch; never set in timed runs)
-  bool force_simple;  // HSD_FORCE_SIMPLE=1: run the plain kernels also for bf16 (cross-check of the MFMA path)
-  int k_chunks[2] = {0, 0};  // experiment override of the O / down K chunking (0 = default)
+  // hsd_debug_set knobs (defaults are what production runs use)
+  bool sync_layers = false;  // wait for the stream after every layer (bounds the launches in flight for tools that
+                             // track each dispatch; never set in timed runs)
+  bool force_simple;  // run the plain kernels also for bf16 (cross-check of the MFMA path)
+  int k_chunks[2] = {0, 0};  // override of the O / down K chunking (0 = default)
   int64_t split_rows; // largest row count for which the O / down projections run as split-K
-  bool gemm_cfg_forced = false;  // HSD_GEMM_CFG given: use it for every row count
+  bool gemm_cfg_forced = false;  // a tile configuration was set by hand: use it for every row count
   int gemm_cfg[5];    // tile configuration of the MFMA GEMM per call site (qkv, o, gate_up, down, lm_head)
   // per-kernel timing (hsd_profile_*)
   int prof_which = HSD_PROF_NONE;
@@ -70,7 +71,7 @@ inline int64_t split_row_limit(const hsd_model_desc &d) {
   return (512 / tiles_n) * 128;
 }
 // K chunking per projection, fixed: the K-reduction order never depends on the batch.  The O projection (K = 1024)
-// runs unsplit; the down projection (K = 4096) in two chunks.  kMaxChunks bounds the HSD_KCHUNKS experiment override
+// runs unsplit; the down projection (K = 4096) in two chunks.  kMaxChunks bounds the hsd_debug_set override
 // and sizes the partial-sum buffer.
 constexpr int kChunksO = 1, kChunksDown = 2, kMaxChunks = 4;
 
@@ -148,14 +149,12 @@ int launch_gemm_mfma_impl(hipStream_t st, int M, int N, int K, const void *A, co
   constexpr int MODE = GemmModeOf<Epi>::value;
   auto kern = k_gemm_mfma<Cfg, MODE, Epi, WALK>;
   constexpr int smem = Cfg::kSmemBytes;
-  static bool attr_done = false;  // per instantiation; the attribute is per function, setting it twice is harmless
-  if (!attr_done) {
-    if (smem > 48 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
-            hipSuccess)
-      return HSD_EHIP;
-    attr_done = true;
-  }
+  // set once per instantiation (initialisation of a function-local static is thread safe)
+  static const hipError_t attr_rc =
+      smem > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem)
+                       : hipSuccess;
+  if (attr_rc != hipSuccess) return HSD_EHIP;
   if constexpr (MODE == kModeSwapLM) epi.n_tiles = (N / Cfg::BP) * Cfg::WM;
   int tiles_act, tiles_w;
   gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
@@ -181,13 +180,9 @@ int launch_gemm_mfma8_impl(hipStream_t st, int M, int N, int K, const void *A, c
   using Cfg = GemmCfg8;
   auto kern = k_gemm_mfma8<MODE, Epi, WALK>;
   constexpr int smem = Cfg::kSmemBytes;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
-        hipSuccess)
-      return HSD_EHIP;
-    attr_done = true;
-  }
+  static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (attr_rc != hipSuccess) return HSD_EHIP;
   if constexpr (MODE == kModeSwapLM) epi.n_tiles = (N / Cfg::BP) * Cfg::WM;
   int tiles_act, tiles_w;
   gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
@@ -213,13 +208,9 @@ int launch_gemm_mfma_ws(hipStream_t st, int M, int N, int K, const void *A, cons
   constexpr int MODE = GemmModeOf<Epi>::value;
   auto kern = k_gemm_mfma_ws<Cfg, MODE, Epi>;
   constexpr int smem = Cfg::kSmemBytes;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
-        hipSuccess)
-      return HSD_EHIP;
-    attr_done = true;
-  }
+  static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (attr_rc != hipSuccess) return HSD_EHIP;
   if (k_chunks > 1 && !split) return HSD_EINVAL;   // K chunks only as split-K
   int tiles_act, tiles_w;
   gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
@@ -229,7 +220,7 @@ int launch_gemm_mfma_ws(hipStream_t st, int M, int N, int K, const void *A, cons
   return HSD_OK;
 }
 
-// Tile configurations of the MFMA GEMM (HSD_GEMM_CFG selects one for experiments; default per call site).
+// Tile configurations of the MFMA GEMM (hsd_debug_set selects one for experiments; default per call site).
 using GemmCfg0 = GemmCfg<128, 128, 64, 2, 2>;
 using GemmCfg1 = GemmCfg<256, 128, 64, 2, 2>;
 using GemmCfg4 = GemmCfg<128, 256, 64, 2, 2>;
@@ -333,18 +324,44 @@ int lm_head_tiles(const hsd_ctx *ctx, int M) {
 }
 
 // Verification attention: bf16 goes to the MFMA kernel when the GQA group size fits its wave mapping.
+// A compute unit has 160 KB of LDS; a request above half of it keeps a workgroup alone on its compute unit.
+constexpr size_t kLdsExclusive = 84 * 1024;
+
+template <int G4, int QS, bool TREE, bool SPLIT>
+int launch_attn_mfma(hipStream_t st, dim3 grid, int n_cu, int n_q_heads, const AttnTile *tiles, const PagedKV &kv,
+                     const bf16 *q, bf16 *o, const int32_t *row_end, const AttnSplit &sp) {
+  constexpr size_t smem = attn_smem_bytes(QS);
+  auto kern = k_attn_mfma<G4, QS, TREE, SPLIT>;
+  // set once per instantiation (initialisation of a function-local static is thread safe)
+  static const hipError_t attr_rc =
+      hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          smem > kLdsExclusive ? smem : kLdsExclusive);
+  if (attr_rc != hipSuccess) return HSD_EHIP;
+  // Two workgroups fit a compute unit, and the dispatcher does pair them up while other units are still empty:
+  // with about one workgroup per unit (measured on the 16-region workload: 30 of 256 units held two, 30 none) the
+  // paired ones run 1.7 times as long and set the launch's duration (31 us against 22 us).  A launch with no more
+  // workgroups than the chip has units therefore asks for more LDS than half a unit has, which spreads it one
+  // workgroup per unit.  (With a few more workgroups than units pairing is the better deal: a second round would
+  // cost more.)  Scheduling only: no result depends on it.
+  const size_t n_wg = static_cast<size_t>(grid.x) * grid.y * grid.z;
+  const size_t lds = (n_cu > 0 && n_wg <= static_cast<size_t>(n_cu) && smem < kLdsExclusive) ? kLdsExclusive : smem;
+  hipLaunchKernelGGL(kern, grid, dim3(128 * QS), lds, st, n_q_heads, tiles, kv, q, o, row_end, sp);
+  HSD_LAUNCH_CHECK();
+  return HSD_OK;
+}
+
 template <typename T>
 int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, const RowMeta &meta, const PagedKV &kv,
                      const Workspace &ws, bool page_mode) {
-  (void)page_mode;  // both entry points share one tiling so far
   const hsd_model_desc &d = ctx->desc;
   const int group = d.n_q_heads / d.n_kv_heads;
   if constexpr (std::is_same<T, bf16>::value) {
     if (!ctx->force_simple && (group == 1 || group == 2 || group % 4 == 0)) {
-      // Work split, fixed per model (never chosen from the batch, so results stay bitwise batch-invariant):
-      // g4 query heads of a kv head among the 4 query sets of a workgroup, 2 key parts per 64-key tile.  Measured
-      // alternatives on the 16-region workload (all slower): 4 key parts of 128-key tiles, 1 / 2 / 8 query sets.
-      const int g4 = group >= 4 ? 4 : group, qs = 4;
+      // Work split, fixed per model and entry point (never chosen from the batch; and one row's arithmetic is the
+      // same in both, so results stay bitwise batch-invariant): g4 query heads of a kv head among the query sets of
+      // a workgroup; 4 query sets for region-level batches (many short blocks: more, smaller workgroups), 8 for
+      // page-level ones (few long blocks: each K/V stage in LDS serves twice the queries).
+      const int g4 = group >= 4 ? 4 : group, qs = page_mode ? 8 : 4;
       const int q_tile = 32 * (qs / g4);
       const int max_tiles = b->total_q / q_tile + b->n_seq;
       const dim3 grid(max_tiles, d.n_kv_heads * ((group + g4 - 1) / g4));
@@ -365,35 +382,18 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
       }
       const dim3 grid_z(grid.x, grid.y, n_chunks);
       const AttnSplit sp{chunk, b->total_q, ws.attn_part_o, ws.attn_part_ml};
-#define HSD_ATTN_LAUNCH1(G4, KQ, QS, TREE, SPLIT)                                                                \
-  {                                                                                                              \
-    constexpr size_t smem = attn_smem_bytes(KQ, QS);                                                             \
-    static bool attr_done = false;                                                                               \
-    if (!attr_done) {                                                                                            \
-      if (smem > 48 * 1024 &&                                                                                    \
-          hipFuncSetAttribute(reinterpret_cast<const void *>(k_attn_mfma<G4, KQ, QS, TREE, SPLIT>),              \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)                   \
-        return HSD_EHIP;                                                                                         \
-      attr_done = true;                                                                                          \
-    }                                                                                                            \
-    hipLaunchKernelGGL((k_attn_mfma<G4, KQ, QS, TREE, SPLIT>), grid_z, dim3(64 * QS * KQ), smem, st,             \
-                       d.n_q_heads, ws.attn_tiles, kv, q, o, meta.row_end, sp);                                  \
-  }
-#define HSD_ATTN_LAUNCH(G4, KQ, QS, TREE)                      \
-  {                                                            \
-    if (chunk > 0) HSD_ATTN_LAUNCH1(G4, KQ, QS, TREE, true)    \
-    else HSD_ATTN_LAUNCH1(G4, KQ, QS, TREE, false)             \
-  }
       const bool tree = meta.row_end != nullptr;
-      if (g4 == 4 && tree) HSD_ATTN_LAUNCH(4, 2, 4, true)
-      else if (g4 == 4) HSD_ATTN_LAUNCH(4, 2, 4, false)
-      else if (g4 == 2 && tree) HSD_ATTN_LAUNCH(2, 2, 4, true)
-      else if (g4 == 2) HSD_ATTN_LAUNCH(2, 2, 4, false)
-      else if (tree) HSD_ATTN_LAUNCH(1, 2, 4, true)
-      else HSD_ATTN_LAUNCH(1, 2, 4, false)
-#undef HSD_ATTN_LAUNCH
-#undef HSD_ATTN_LAUNCH1
-      HSD_LAUNCH_CHECK();
+      int rc = HSD_OK;
+#define HSD_ATTN_CASE(G4, QS)                                                                                      \
+  if (g4 == G4 && qs == QS) {                                                                                      \
+    if (tree && chunk > 0) rc = launch_attn_mfma<G4, QS, true, true>(st, grid_z, ctx->n_cu, d.n_q_heads, ws.attn_tiles, kv, q, o, meta.row_end, sp);       \
+    else if (tree) rc = launch_attn_mfma<G4, QS, true, false>(st, grid_z, ctx->n_cu, d.n_q_heads, ws.attn_tiles, kv, q, o, meta.row_end, sp);             \
+    else if (chunk > 0) rc = launch_attn_mfma<G4, QS, false, true>(st, grid_z, ctx->n_cu, d.n_q_heads, ws.attn_tiles, kv, q, o, meta.row_end, sp);        \
+    else rc = launch_attn_mfma<G4, QS, false, false>(st, grid_z, ctx->n_cu, d.n_q_heads, ws.attn_tiles, kv, q, o, meta.row_end, sp);                      \
+  }
+      HSD_ATTN_CASE(4, 4) HSD_ATTN_CASE(4, 8) HSD_ATTN_CASE(2, 4) HSD_ATTN_CASE(2, 8) HSD_ATTN_CASE(1, 4) HSD_ATTN_CASE(1, 8)
+#undef HSD_ATTN_CASE
+      if (rc != HSD_OK) return rc;
       if (chunk > 0) {
         const int64_t n_thr = static_cast<int64_t>(d.n_q_heads) * b->total_q * 16;
         hipLaunchKernelGGL(k_attn_merge, dim3(static_cast<unsigned>((n_thr + 255) / 256)), dim3(256), 0, st,
@@ -580,7 +580,7 @@ int hsd_validate_model(const hsd_model_desc *d) {
   if (d->n_q_heads % d->n_kv_heads != 0) return HSD_EINVAL;
   if (d->d_model % 128 != 0 || d->d_ffn % 128 != 0 || d->vocab % 128 != 0) return HSD_EINVAL;
   if (!(d->rms_eps > 0.f) || !(d->rope_theta > 1.f)) return HSD_EINVAL;
-  if (d->attn_key_chunk < 0 || d->attn_key_chunk % 64 != 0) return HSD_EINVAL;
+  if (d->attn_key_chunk < 0 || d->attn_key_chunk % 128 != 0) return HSD_EINVAL;
   if (d->n_layers > 1024 || d->n_q_heads > 1024) return HSD_ERANGE;
   return HSD_OK;
 }
@@ -652,34 +652,41 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   c->w_gate_up.assign(w->w_gate_up, w->w_gate_up + desc->n_layers);
   c->w_down.assign(w->w_down, w->w_down + desc->n_layers);
   c->n_cu = prop.multiProcessorCount;
-  const char *fs = std::getenv("HSD_FORCE_SIMPLE");
-  c->force_simple = fs != nullptr && fs[0] == '1';
-  if (const char *sl = std::getenv("HSD_SYNC_LAYERS")) c->sync_layers = sl[0] == '1';
-  // HSD_SPLIT_ROWS (tests): lower the row count up to which split-K is used, to exercise the chunk-walking GEMM
+  c->force_simple = false;
   c->split_rows = split_row_limit(*desc);
-  if (const char *sr = std::getenv("HSD_SPLIT_ROWS")) {
-    const int64_t v = std::atoll(sr);
-    if (v >= 0 && v < c->split_rows) c->split_rows = v;
-  }
-  if (const char *kc = std::getenv("HSD_KCHUNKS")) {  // "o,down" (experiments)
-    int v[2] = {0, 0};
-    std::sscanf(kc, "%d,%d", &v[0], &v[1]);
-    for (int i = 0; i < 2; ++i)
-      if (v[i] >= 1 && v[i] <= kMaxChunks) c->k_chunks[i] = v[i];
-  }
-  // HSD_GEMM_CFG="q,o,g,d,l" (or one number for all) overrides the per-site tile configuration (experiments)
   // 256x256 8-wave tiles for the wide projections (gate/up, LM head), 64x128 tiles for QKV and O (more workgroups),
   // 128x128 for the split-K down projection
   const int defaults[5] = {5, 2, 8, 0, 8};
   for (int i = 0; i < 5; ++i) c->gemm_cfg[i] = defaults[i];
-  if (const char *gc = std::getenv("HSD_GEMM_CFG")) {
-    c->gemm_cfg_forced = true;
-    int vals[5], n = std::sscanf(gc, "%d,%d,%d,%d,%d", &vals[0], &vals[1], &vals[2], &vals[3], &vals[4]);
-    for (int i = 0; i < 5; ++i)
-      if (n == 1) c->gemm_cfg[i] = vals[0]; else if (i < n) c->gemm_cfg[i] = vals[i];
-  }
   *out = c;
   return HSD_OK;
+}
+
+int hsd_debug_set(hsd_ctx *c, int knob, int64_t value) {
+  if (c == nullptr) return HSD_EINVAL;
+  switch (knob) {
+    case HSD_DEBUG_SYNC_LAYERS: c->sync_layers = value != 0; return HSD_OK;
+    case HSD_DEBUG_FORCE_SIMPLE: c->force_simple = value != 0; return HSD_OK;
+    case HSD_DEBUG_SPLIT_ROWS:
+      if (value < 0) return HSD_EINVAL;
+      c->split_rows = value < split_row_limit(c->desc) ? value : split_row_limit(c->desc);
+      return HSD_OK;
+    case HSD_DEBUG_KCHUNKS_O:
+    case HSD_DEBUG_KCHUNKS_DOWN:
+      if (value < 0 || value > kMaxChunks) return HSD_EINVAL;
+      c->k_chunks[knob - HSD_DEBUG_KCHUNKS_O] = static_cast<int>(value);
+      return HSD_OK;
+    case HSD_DEBUG_GEMM_CFG_QKV:
+    case HSD_DEBUG_GEMM_CFG_O:
+    case HSD_DEBUG_GEMM_CFG_GATE_UP:
+    case HSD_DEBUG_GEMM_CFG_DOWN:
+    case HSD_DEBUG_GEMM_CFG_LM_HEAD:
+      if (value < 0 || value > 9) return HSD_EINVAL;
+      c->gemm_cfg[knob - HSD_DEBUG_GEMM_CFG_QKV] = static_cast<int>(value);
+      c->gemm_cfg_forced = true;
+      return HSD_OK;
+    default: return HSD_EINVAL;
+  }
 }
 
 void hsd_destroy(hsd_ctx *ctx) {

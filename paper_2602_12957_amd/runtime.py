@@ -8,7 +8,6 @@ forward, arg-max, acceptance and KV maintenance all run inside libhsd.so.
 from __future__ import annotations
 
 import ctypes as C
-import os
 from dataclasses import dataclass
 from typing import List, Optional, Sequence
 
@@ -86,7 +85,10 @@ class VerifyOutput:
 
 class Engine:
     def __init__(self, desc, weights: dict, n_blocks: int, n_slots: int, max_blocks_per_seq: int,
-                 max_total_q: int, max_dump: int = 0, device: str = "cuda:0", attn_key_chunk: Optional[int] = None):
+                 max_total_q: int, max_dump: int = 0, device: str = "cuda:0", attn_key_chunk: int = 0,
+                 debug: Optional[dict] = None):
+        """debug: {"sync_layers" | "force_simple" | "split_rows" | "kchunks_o" | "kchunks_down": int,
+        "gemm_cfg": (qkv, o, gate_up, down, lm_head)} -> hsd_debug_set (experiments and cross-checks only)."""
         if not torch.cuda.is_available():
             raise RuntimeError("the HSD verification path needs a GPU (MI355X); there is no CPU fallback")
         self.dev = torch.device(device)
@@ -95,11 +97,7 @@ class Engine:
         self.cdesc = B.hsd_model_desc(desc.n_layers, desc.d_model, desc.n_q_heads, desc.n_kv_heads, desc.head_dim,
                                       desc.d_ffn, desc.vocab, B.HSD_BF16 if self.bf16 else B.HSD_FP32,
                                       desc.kv_block_tokens, desc.rms_eps, desc.rope_theta, 0)
-        # attention key split (hsd_model_desc.attn_key_chunk); HSD_ATTN_KEY_CHUNK sets it for engines that do not
-        # choose (used to run whole test suites with the split on)
-        if attn_key_chunk is None:
-            attn_key_chunk = int(os.environ.get("HSD_ATTN_KEY_CHUNK", "0"))
-        self.cdesc.attn_key_chunk = attn_key_chunk
+        self.cdesc.attn_key_chunk = int(attn_key_chunk or 0)    # attention key split (hsd_model_desc.attn_key_chunk)
         code = B.hsd_validate_model(self.cdesc)
         B.check("hsd_validate_model", code)
         self.desc = desc
@@ -124,6 +122,12 @@ class Engine:
             setattr(cw, name, C.cast(arr, C.POINTER(C.c_void_p)))
         self._cw, self._arrays = cw, arrays
         self.ctx = B.hsd_create(self.cdesc, cw)
+        for name, val in (debug or {}).items():
+            if name == "gemm_cfg":
+                for site, v in enumerate(val):
+                    B.hsd_debug_set(self.ctx, B.HSD_DEBUG_GEMM_CFG_QKV + site, int(v))
+            else:
+                B.hsd_debug_set(self.ctx, getattr(B, "HSD_DEBUG_" + name.upper()), int(val))
 
         # ---- paged KV pools + per-sequence state
         es = torch.int16 if self.bf16 else torch.float32

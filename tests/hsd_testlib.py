@@ -1,4 +1,5 @@
-"""Shared helpers of the GPU parity tests: build the same seeded workload for the oracle and the HIP path."""
+"""Shared helpers of the GPU parity tests: build the same seeded workload for the oracle and the HIP path.
+The oracle is always taken in its plain form (fp64, nothing rounded), whatever the storage type of the model."""
 from __future__ import annotations
 
 import numpy as np
@@ -9,17 +10,12 @@ import workloads as W
 MARGIN_GATE = 1e-2   # acceptance decisions are compared only where the oracle's top-1/top-2 margin exceeds this
 
 
-def act_dtype_of(desc):
-    """The oracle is evaluated at the storage precision of the model under test (bf16 activations for 'bf16')."""
-    return "bf16" if desc.dtype == "bf16" else None
-
-
 def blocks_needed(specs, extra=4, uniform_len=False):
     k_max = max(s.draft_len for s in specs)
     return sum((s.n_visual + s.n_prompt + (k_max if uniform_len else s.draft_len) + 1 + 15) // 16 + 1 for s in specs) + extra
 
 
-def make_engine(desc, weights, specs, max_total_q=None, max_dump=0, n_blocks=None, attn_key_chunk=None):
+def make_engine(desc, weights, specs, max_total_q=None, max_dump=0, n_blocks=None, attn_key_chunk=None, debug=None):
     """Engine sized for the given sequences.  The pool and block tables leave room for every sequence to grow by
     the LONGEST draft length (Engine.greedy_decode advances all sequences in lock step)."""
     from paper_2602_12957_amd.runtime import Engine
@@ -30,7 +26,7 @@ def make_engine(desc, weights, specs, max_total_q=None, max_dump=0, n_blocks=Non
     if max_total_q is None:
         max_total_q = max(sum(s.draft_len + 1 for s in specs), max(s.n_visual + s.n_prompt for s in specs))
     return Engine(desc, weights, n_blocks or blocks_needed(specs), n, maxb, max_total_q, max_dump,
-                  attn_key_chunk=attn_key_chunk)
+                  attn_key_chunk=attn_key_chunk or 0, debug=debug)
 
 
 def prefix_rows(desc, seed, spec):
@@ -52,9 +48,8 @@ def oracle_targets(desc, weights, seed, specs, dtype=np.float64):
     out = []
     for sp in specs:
         vis, prompt = W.make_prefix(desc, seed, sp.seq_id, sp.n_visual, sp.n_prompt)
-        cache, pending = O.prefill(desc, weights, vis, prompt, dtype, act_dtype=act_dtype_of(desc))
-        g, margins = O.greedy_decode(desc, weights, cache, pending, sp.draft_len, dtype, return_margins=True,
-                                     act_dtype=act_dtype_of(desc))
+        cache, pending = O.prefill(desc, weights, vis, prompt, dtype)
+        g, margins = O.greedy_decode(desc, weights, cache, pending, sp.draft_len, dtype, return_margins=True)
         out.append((g, margins))
     return out
 

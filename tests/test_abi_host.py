@@ -39,7 +39,7 @@ def test_status_strings():
     ({"n_q_heads": 6, "n_kv_heads": 4}, B.HSD_EINVAL), ({"d_model": 200}, B.HSD_EINVAL),
     ({"vocab": 1000}, B.HSD_EINVAL), ({"n_layers": 0}, B.HSD_EINVAL), ({"rms_eps": 0.0}, B.HSD_EINVAL),
     ({"n_layers": 5000}, B.HSD_ERANGE),
-    ({"attn_key_chunk": 512}, B.HSD_OK), ({"attn_key_chunk": 100}, B.HSD_EINVAL), ({"attn_key_chunk": -64}, B.HSD_EINVAL),
+    ({"attn_key_chunk": 512}, B.HSD_OK), ({"attn_key_chunk": 100}, B.HSD_EINVAL), ({"attn_key_chunk": -128}, B.HSD_EINVAL), ({"attn_key_chunk": 64}, B.HSD_EINVAL),
 ])
 def test_validate_model(kw, code):
     assert B.hsd_validate_model(_desc(**kw)) == code

@@ -6,19 +6,24 @@ configuration bench.py times, round after round to completion.  Every round is c
 record of that round.  After each round the GPU is re-synchronised to the oracle's decision (so an ambiguous
 row cannot derail later rounds).
 
-Bars.  The stated bars are: logits max-abs 2e-2 (bf16) / 1e-4 (fp32); decisions exact where the oracle's
-top-1/top-2 margin exceeds 1e-2.  A 24-layer decoder that stores activations in bf16 is chaotic at rounding
-granularity: two CPU evaluations of the same model at the same storage precision that differ only in the
-precision of their sums already deviate by a logit RMS of about 1.1e-2 (golden "noise_floor", measured by the
-oracle alone; tests/test_oracle_noise_floor.py).  No implementation can agree with the oracle more closely
-than that, so for such models the bars are derived from the floor sigma: logit RMS <= 2 sigma, max-abs <= 8 sigma,
-decisions exact where the margin exceeds 7 sigma (5 standard deviations of a logit difference), and EVERY row's
-arg-max must be one of the oracle's four largest logits within that margin of the oracle's maximum (or, for at most
-one row in a thousand, lie outside them where those four themselves tie within the margin).  Where the
-floor is small (fp32, shallow models) these reduce to the stated bars.
+Bars.  Every stored value is the oracle in its plain form (fp64, nothing rounded).  The stated bars are: logits
+max-abs 2e-2 (bf16) / 1e-4 (fp32); decisions exact where the oracle's top-1/top-2 margin exceeds 1e-2.  They hold for
+fp32 and for shallow bf16 models.  For the 24-layer model the bars follow from an error model: a decoder that keeps
+its activations in bf16 rounds six tensors per layer to 8 significant bits; through 24 random-weight layers these
+roundings accumulate to a logit deviation that the oracle itself measures on the CPU (golden "storage_noise": plain
+oracle against the same oracle with every stored activation rounded, RMS sigma ~ 1.3e-2, roughly Gaussian).  From
+sigma: logit RMS <= 1.25 sigma; max-abs <= 6 sigma (the largest of up to 1e6 Gaussian samples sits near 5 sigma);
+decisions exact where the margin exceeds 5 sigma (a flip there needs an error of a logit DIFFERENCE -- standard
+deviation sqrt(2) sigma at most -- of more than 3.5 of its standard deviations; summed over the ~5e4 rows of the
+largest test, weighted by how many rows have such margins, that is an expected 0.03 rows).  Between the stated 1e-2
+and 5 sigma flips are allowed but COUNTED against the model: their number must not exceed what Gaussian errors of
+1.25 sigma predict for the margins at hand (sum of tail probabilities, plus four standard deviations of that
+count).  EVERY row's arg-max must be one of the oracle's four largest logits within the 5-sigma gate of the oracle's
+maximum (or, for at most one row in a thousand, lie outside them where those four themselves tie within the gate).
 """
 import gzip
 import json
+import math
 import os
 
 import numpy as np
@@ -57,15 +62,20 @@ def _run_config(cfg, mode, max_rounds=None):
     total_q = sum(sp.draft_len + 1 for sp in specs)
     eng = make_engine(desc, weights, specs, max_total_q=max(total_q, 4096), max_dump=8 * n)
     toks, embs, pend = [], [], []
-    for sp in specs:
+    for s, sp in zip(seqs, specs):
         _, _, tok, emb, pending = prefix_rows(desc, seed, sp)
+        ctx = s.get("context_tokens")
+        if ctx:      # a later round of the page: tokens that stand for earlier commits are part of the context
+            tok = np.concatenate([tok, [pending], ctx[:-1]]).astype(np.int32)
+            emb = np.concatenate([emb, np.zeros((len(ctx), desc.d_model), np.float32)], axis=0)
+            pending = int(ctx[-1])
         toks.append(tok), embs.append(emb), pend.append(pending)
     eng.prefill(list(range(n)), toks, embs)
     drafts = []
     for s, sp in zip(seqs, specs):
         assert pend[len(drafts)] == s["pending"]
-        if s.get("draft_is_target"):       # long-document golden: seeded random draft stored as the target
-            drafts.append(np.asarray(s["target"], np.int32))
+        if "draft" in s:       # long-document golden: greedy head + seeded random tail, stored explicitly
+            drafts.append(np.asarray(s["draft"], np.int32))
             continue
         fn = W.corrupt_draft_forced if sp.forced_different else W.corrupt_draft
         drafts.append(fn(np.asarray(s["target"], np.int32), sp.corrupt_p, desc.vocab, seed, f"cfg{cfg}.{sp.seq_id}")[0])
@@ -74,11 +84,12 @@ def _run_config(cfg, mode, max_rounds=None):
         n_rounds = min(n_rounds, max_rounds)
     stats = dict(rounds=0, rows=0, gated_rows=0, gated_rounds=0, seq_rounds=0, max_logit_err=0.0, accepted=0,
                  near_max_rows=0, deep_tie_rows=0)
-    sigma = gold["noise_floor"]["rms"]
-    tol = max(TOL[desc.dtype], 8 * sigma)
-    tol_rms = max(TOL[desc.dtype] / 4, 2 * sigma)
-    gate = max(MARGIN_GATE, 7 * sigma)
-    stats.update(sigma=sigma, gate=gate, tol=tol)
+    assert gold["oracle_act_dtype"] is None       # the plain oracle
+    sigma = gold["storage_noise"]["rms"]
+    tol = max(TOL[desc.dtype], 6 * sigma)
+    tol_rms = max(TOL[desc.dtype] / 4, 1.25 * sigma)
+    gate = max(MARGIN_GATE, 5 * sigma)
+    stats.update(sigma=sigma, gate=gate, tol=tol, flips_below_gate=0, flips_expected=0.0, sampled_rounds=0)
     sq_sum, sq_n = 0.0, 0
     pending = list(pend)
     for r in range(n_rounds):
@@ -88,8 +99,8 @@ def _run_config(cfg, mode, max_rounds=None):
         for i in active:
             rec = seqs[i]["rounds"][r]
             blocks.append(np.concatenate([[pending[i]], drafts[i][rec["offset"]:rec["offset"] + rec["k"]]]).astype(np.int32))
-            if r == 0:
-                dump.extend(row0 + np.asarray(seqs[i]["logit_samples"]["rows"]))
+            if "logit_samples" in rec:
+                dump.extend(row0 + np.asarray(rec["logit_samples"]["rows"]))
             row0 += rec["k"] + 1
         out = eng.verify(active, blocks, mode, dump_rows=np.asarray(dump, np.int32) if dump else None)
         g_alpha, g_bonus, status = eng.read_acceptance(len(active))
@@ -116,6 +127,12 @@ def _run_config(cfg, mode, max_rounds=None):
             short = t4v[:, 0] - (t4v * hit).sum(axis=1)
             assert (short <= gate).all(), f"round {r} seq {i}: chosen token {short.max():.4f} below the oracle maximum"
             stats["near_max_rows"] += int((g_argmax[lo:hi] != u_hat).sum())
+            # flips between the stated 1e-2 and the gate, against what the error model predicts for these margins
+            mid = (margin > MARGIN_GATE) & ~ok
+            stats["flips_below_gate"] += int((mid & (g_argmax[lo:hi] != u_hat)).sum())
+            if sigma > 0:
+                z = margin[mid] / (math.sqrt(2.0) * 1.25 * sigma)
+                stats["flips_expected"] += float(sum(0.5 * math.erfc(x / math.sqrt(2.0)) for x in z))
             bad = np.nonzero(ok & (g_argmax[lo:hi] != u_hat))[0]
             if os.environ.get("HSD_TEST_DIAG"):
                 allbad = np.nonzero(g_argmax[lo:hi] != u_hat)[0]
@@ -139,8 +156,9 @@ def _run_config(cfg, mode, max_rounds=None):
             else:
                 stats["gated_rounds"] += 1
             stats["accepted"] += rec["alpha"]
-            if r == 0:
-                smp = seqs[i]["logit_samples"]
+            if "logit_samples" in rec:
+                smp = rec["logit_samples"]
+                stats["sampled_rounds"] += 1
                 cols = np.asarray(smp["cols"])
                 for q, _row in enumerate(smp["rows"]):
                     got = g_logits[d0 + q]
@@ -154,9 +172,8 @@ def _run_config(cfg, mode, max_rounds=None):
         if os.environ.get("HSD_TEST_DIAG") and r == 0:
             print("diag max_logit_err", stats["max_logit_err"])
         assert stats["max_logit_err"] <= tol, stats
-        if r == 0:
-            stats["rms_logit_err"] = (sq_sum / max(sq_n, 1)) ** 0.5
-            assert stats["rms_logit_err"] <= tol_rms, stats
+        stats["rms_logit_err"] = (sq_sum / max(sq_n, 1)) ** 0.5
+        assert stats["rms_logit_err"] <= tol_rms, stats
         eng.override_acceptance(np.array([seqs[i]["rounds"][r]["alpha"] for i in active]),
                                 np.array([seqs[i]["rounds"][r]["bonus"] for i in active]))
         eng.commit()
@@ -174,6 +191,8 @@ def _run_config(cfg, mode, max_rounds=None):
     assert owned + int(eng.free_count.item()) == eng.n_blocks
     eng.close()
     assert stats["deep_tie_rows"] <= max(1, stats["rows"] // 1000), stats
+    e = stats["flips_expected"]
+    assert stats["flips_below_gate"] <= e + 4.0 * math.sqrt(e) + 3.0, stats
     stats["aal"] = stats["accepted"] / max(stats["seq_rounds"], 1)
     return stats
 
@@ -182,7 +201,7 @@ def test_config1_region_level_all_rounds():
     """configs[1]: 16 regions, prefix 1024 visual + 32 prompt, drafts U[16,256] at 5 % corruption, bf16 model M."""
     stats = _run_config(1, "region")
     print("cfg1", stats)
-    assert stats["rounds"] >= 5 and stats["gated_rows"] < 0.6 * stats["rows"]
+    assert stats["rounds"] >= 5 and stats["gated_rows"] < 0.42 * stats["rows"] and stats["sampled_rounds"] > 16
 
 
 def test_config1_through_page_entry_point_round1():
@@ -195,11 +214,16 @@ def test_config2_page_level_all_rounds():
     print("cfg2", stats)
 
 
-def test_config3_long_document_first_rounds():
+def test_config3_long_document_first_and_later_round():
+    """configs[3] at full size: page 0 in its first round (8193 rows on 8192 cached) and page 1 in a later round (4097
+    rows on 12288 cached), each with a draft whose head is the oracle's own greedy continuation: a real accepted run."""
     stats = _run_config(3, "page")
     print("cfg3", stats)
+    assert stats["accepted"] > 0 and stats["rows"] == 8193 + 4097
 
 
 def test_config4_ragged_region_all_rounds():
+    """configs[4] to completion: every round of all 64 ragged regions."""
     stats = _run_config(4, "region")
     print("cfg4", stats)
+    assert stats["gated_rows"] < 0.42 * stats["rows"] and stats["sampled_rounds"] > 64

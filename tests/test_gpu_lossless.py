@@ -81,11 +81,11 @@ def test_lossless_small_models(mode):
 
 def test_lossless_with_attention_key_split():
     """The key split cuts at absolute positions, so a row's bits still do not depend on the block it is scored in:
-    verification and token-by-token decoding agree exactly with the split on (64-key chunks on a small model; the
+    verification and token-by-token decoding agree exactly with the split on (128-key chunks on a small model; the
     page-level configuration with the 1024-key chunks that suit it)."""
-    specs = [SequenceSpec(0, 40, 3, 90, 0.1), SequenceSpec(1, 5, 2, 70, 0.3), SequenceSpec(2, 130, 5, 33, 0.0),
-             SequenceSpec(3, 0, 4, 150, 0.05)]
-    assert _lossless(W.ModelDesc(3, 256, 8, 2, 64, 512, 1024, "bf16"), specs, 12, "region", attn_key_chunk=64) >= 2
+    specs = [SequenceSpec(0, 40, 3, 90, 0.1), SequenceSpec(1, 5, 2, 70, 0.3), SequenceSpec(2, 330, 5, 33, 0.0),
+             SequenceSpec(3, 0, 4, 290, 0.05)]
+    assert _lossless(W.ModelDesc(3, 256, 8, 2, 64, 512, 1024, "bf16"), specs, 12, "region", attn_key_chunk=128) >= 2
     rounds = _lossless(W.MODEL_M, W.draw_sequences(2, W.SEED_BASE), W.SEED_BASE, "page", attn_key_chunk=1024)
     print("cfg2 lossless rounds with 1024-key chunks", rounds)
 
@@ -106,7 +106,7 @@ def test_lossless_random_shapes():
             specs.append(SequenceSpec(i, nv, int(rng.integers(1 if nv == 0 else 0, 6)),
                                       int(rng.choice([1, 2, 31, 33, 64, 65, 150, 260])), float(rng.choice([0.0, 0.05, 0.3]))))
         mode = "page" if rng.random() < 0.4 else "region"
-        chunk = int(rng.choice([0, 64, 128, 256])) if dt == "bf16" else 0
+        chunk = int(rng.choice([0, 128, 256, 384])) if dt == "bf16" else 0
         seed = int(rng.integers(1, 10000))
         print(it, desc, [(s.n_visual, s.n_prompt, s.draft_len, s.corrupt_p) for s in specs], mode, chunk, seed, flush=True)
         _lossless(desc, specs, seed, mode, attn_key_chunk=chunk or None)

@@ -11,7 +11,7 @@ import oracle as O
 import workloads as W
 from workloads.generators import SequenceSpec
 
-from hsd_testlib import MARGIN_GATE, act_dtype_of, make_engine, prefix_rows, oracle_targets, gated_compare_argmax
+from hsd_testlib import MARGIN_GATE, make_engine, prefix_rows, oracle_targets, gated_compare_argmax
 
 pytestmark = pytest.mark.gpu
 
@@ -22,7 +22,7 @@ def _oracle_state(desc, weights, seed, specs):
     st = []
     for sp in specs:
         vis, prompt = W.make_prefix(desc, seed, sp.seq_id, sp.n_visual, sp.n_prompt)
-        cache, pending = O.prefill(desc, weights, vis, prompt, act_dtype=act_dtype_of(desc))
+        cache, pending = O.prefill(desc, weights, vis, prompt)
         st.append([cache, pending])
     return st
 
@@ -58,8 +58,7 @@ def run_rounds_parity(desc, weights, seed, specs, drafts, mode="region", check_l
             rest = drafts[s][committed[s]:]
             blocks.append(np.concatenate([[ora[s][1]], rest]).astype(np.int32))
             base = len(ora[s][0])
-            alpha, bonus, u_hat, logits = O.verify_block(desc, weights, ora[s][0], ora[s][1], rest,
-                                                         act_dtype=act_dtype_of(desc))
+            alpha, bonus, u_hat, logits = O.verify_block(desc, weights, ora[s][0], ora[s][1], rest)
             ora[s][0].truncate(base + 1 + alpha)
             recs.append((alpha, bonus, u_hat, logits, O.top2_margin(logits)))
         T = sum(len(b) for b in blocks)
@@ -152,14 +151,14 @@ def test_ragged_batch_rounds(desc, mode):
     assert stats["gated_rows"] < 0.5 * stats["rows"]
 
 
-@pytest.mark.parametrize("chunk", [64, 128])
+@pytest.mark.parametrize("chunk", [128, 256])
 def test_key_split_attention_rounds(chunk):
     """The same rounds against the oracle with the attention keys cut into chunks (hsd_model_desc.attn_key_chunk):
-    contexts of 4 to 283 tokens give rows with one to five chunks, query tiles whose rows see different numbers of
+    contexts of 4 to 539 tokens give rows with one to five chunks, query tiles whose rows see different numbers of
     chunks, and chunks that hold no visible key for some rows of a tile."""
     desc, seed = SMALL_BF16, 78
     weights = W.make_weights(desc, seed)
-    shapes = [(40, 3, 1), (5, 2, 70), (130, 5, 131), (61, 3, 64), (64, 8, 200), (0, 4, 66), (33, 0, 90)]
+    shapes = [(40, 3, 1), (5, 2, 70), (130, 5, 131), (125, 3, 64), (320, 8, 210), (0, 4, 130), (33, 0, 90)]
     specs = [SequenceSpec(i, nv, npr, k, 0.0) for i, (nv, npr, k) in enumerate(shapes)]
     targets = oracle_targets(desc, weights, seed, specs)
     drafts = []
@@ -174,18 +173,18 @@ def test_key_split_attention_rounds(chunk):
 
 
 def test_key_split_last_chunk_is_open_ended():
-    """More keys than 8 chunks hold: the last chunk takes the rest (one pass against the oracle, 64-key chunks,
-    contexts up to 700 tokens), and the result agrees with the unsplit kernel to rounding."""
+    """More keys than 8 chunks hold: the last chunk takes the rest (one pass against the oracle, 128-key chunks,
+    contexts up to 1300 tokens), and the result agrees with the unsplit kernel to rounding."""
     desc, seed = SMALL_BF16, 79
     weights = W.make_weights(desc, seed)
-    specs = [SequenceSpec(0, 600, 4, 96, 0.0), SequenceSpec(1, 505, 2, 40, 0.0)]
+    specs = [SequenceSpec(0, 1200, 4, 96, 0.0), SequenceSpec(1, 1010, 2, 40, 0.0)]
     rng = np.random.default_rng(5)
     drafts = [rng.integers(0, desc.vocab, size=sp.draft_len).astype(np.int32) for sp in specs]
-    stats = run_rounds_parity(desc, weights, seed, specs, drafts, mode="page", attn_key_chunk=64)
+    stats = run_rounds_parity(desc, weights, seed, specs, drafts, mode="page", attn_key_chunk=128)
     print("key split open-ended", stats)
     logits = []
-    for chunk in (0, 64):
-        eng = make_engine(desc, weights, specs, max_total_q=1024, max_dump=256, attn_key_chunk=chunk)
+    for chunk in (0, 128):
+        eng = make_engine(desc, weights, specs, max_total_q=2048, max_dump=256, attn_key_chunk=chunk)
         pend = _gpu_prefill(eng, desc, seed, specs)
         blocks = [np.concatenate([[p], d]).astype(np.int32) for p, d in zip(pend, drafts)]
         logits.append(_one_round(eng, [0, 1], blocks)[1])
@@ -213,7 +212,7 @@ def test_random_shapes_against_oracle():
             npr = int(rng.integers(1 if nv == 0 else 0, 6))
             specs.append(SequenceSpec(i, nv, npr, int(rng.choice([1, 2, 31, 32, 33, 64, 65, 100, 190])), 0.0))
         mode = "page" if rng.random() < 0.4 else "region"
-        chunk = int(rng.choice([0, 0, 64, 128])) if dt == "bf16" else 0
+        chunk = int(rng.choice([0, 0, 128, 256])) if dt == "bf16" else 0
         weights = W.make_weights(desc, seed)
         drafts = []
         for (g, _) in oracle_targets(desc, weights, seed, specs):
@@ -372,7 +371,7 @@ def test_device_side_error_flags():
     eng.close()
 
 
-def test_split_k_and_chunk_walking_projections_agree_bitwise(monkeypatch):
+def test_split_k_and_chunk_walking_projections_agree_bitwise():
     """The O and down projections reduce K in a fixed number of chunks.  Small batches run the chunks in separate
     workgroups (split-K) and add the partial sums afterwards; large batches let each workgroup walk the chunks, in
     the generic kernel or (down projection over many rows) in the 256x256-tile kernel.  All three must round
@@ -383,13 +382,8 @@ def test_split_k_and_chunk_walking_projections_agree_bitwise(monkeypatch):
     rng = np.random.default_rng(4)
     drafts = [rng.integers(0, desc.vocab, size=sp.draft_len).astype(np.int32) for sp in specs]
     results = []
-    for split_rows, gemm_cfg in ((None, None), ("0", None), ("0", "5,2,8,8,8")):
-        for name, val in (("HSD_SPLIT_ROWS", split_rows), ("HSD_GEMM_CFG", gemm_cfg)):   # read at context creation
-            if val is None:
-                monkeypatch.delenv(name, raising=False)
-            else:
-                monkeypatch.setenv(name, val)
-        eng = make_engine(desc, weights, specs, max_total_q=256, max_dump=256)
+    for debug in (None, {"split_rows": 0}, {"split_rows": 0, "gemm_cfg": (5, 2, 8, 8, 8)}):
+        eng = make_engine(desc, weights, specs, max_total_q=256, max_dump=256, debug=debug)
         pend = _gpu_prefill(eng, desc, seed, specs)
         blocks = [np.concatenate([[p], d]).astype(np.int32) for p, d in zip(pend, drafts)]
         results.append(_one_round(eng, [0, 1], blocks))

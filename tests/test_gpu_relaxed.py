@@ -15,7 +15,7 @@ import oracle as O
 import workloads as W
 from workloads.generators import SequenceSpec
 
-from hsd_testlib import MARGIN_GATE, act_dtype_of, make_engine, prefix_rows
+from hsd_testlib import MARGIN_GATE, make_engine, prefix_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -30,12 +30,11 @@ def _near_miss_drafts(desc, weights, seed, specs):
     out = []
     for sp in specs:
         vis, prompt = W.make_prefix(desc, seed, sp.seq_id, sp.n_visual, sp.n_prompt)
-        act = act_dtype_of(desc)
-        cache, pending = O.prefill(desc, weights, vis, prompt, act_dtype=act)
+        cache, pending = O.prefill(desc, weights, vis, prompt)
         base = len(cache)
-        target = O.greedy_decode(desc, weights, cache, pending, sp.draft_len, act_dtype=act)
+        target = O.greedy_decode(desc, weights, cache, pending, sp.draft_len)
         cache.truncate(base)
-        _, _, _, logits = O.verify_block(desc, weights, cache, pending, target, act_dtype=act)
+        _, _, _, logits = O.verify_block(desc, weights, cache, pending, target)
         cache.truncate(base)
         second = np.argsort(-logits, axis=1)[:, 1]
         draft = target.copy()
@@ -81,8 +80,7 @@ def test_relaxed_acceptance_rounds(desc, tau, mode):
             cache, _, draft = state[i]
             rest = draft[offset[i]:]
             base = len(cache)
-            alpha, bonus, u_hat, logits = O.verify_block(desc, weights, cache, pending[i], rest,
-                                                         act_dtype=act_dtype_of(desc), log_tau=lt)
+            alpha, bonus, u_hat, logits = O.verify_block(desc, weights, cache, pending[i], rest, log_tau=lt)
             cache.truncate(base + 1 + alpha)
             lo, hi = out.cu_q[j], out.cu_q[j + 1]
             ref_gap = O.draft_gap(logits, rest)

@@ -16,7 +16,7 @@ import oracle as O
 import workloads as W
 from workloads.generators import SequenceSpec
 
-from hsd_testlib import act_dtype_of, make_engine, prefix_rows
+from hsd_testlib import make_engine, prefix_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -60,7 +60,7 @@ def _walk(argmax, tokens, end, gap, want, log_tau):
     return alpha, int(argmax[s]), s
 
 
-@pytest.mark.parametrize("desc,chunk", [(FP32, None), (BF16, None), (BF16, 64)], ids=["fp32", "bf16", "bf16-keysplit64"])
+@pytest.mark.parametrize("desc,chunk", [(FP32, None), (BF16, None), (BF16, 128)], ids=["fp32", "bf16", "bf16-keysplit128"])
 @pytest.mark.parametrize("log_tau", [0.0, math.log(0.75)], ids=["exact", "tau0.75"])
 @pytest.mark.parametrize("mode", ["region", "page"])
 def test_one_pass_over_packed_trees(desc, chunk, log_tau, mode):
@@ -88,7 +88,7 @@ def test_random_packed_trees_against_oracle():
             n_cands.append(int(rng.integers(0, 7)))
         log_tau = 0.0 if rng.random() < 0.5 else math.log(0.75)
         mode = "page" if rng.random() < 0.4 else "region"
-        chunk = int(rng.choice([0, 64])) if dt == "bf16" else 0
+        chunk = int(rng.choice([0, 128])) if dt == "bf16" else 0
         seed = int(rng.integers(1, 10000))
         print(it, desc, [(s.n_visual, s.n_prompt, s.draft_len) for s in specs], n_cands, mode, log_tau, chunk, seed, flush=True)
         decided += _one_pass_trees(desc, chunk or None, log_tau, mode, seed, specs, n_cands, rng, -1)
@@ -101,20 +101,19 @@ def _one_pass_trees(desc, chunk, log_tau, mode, seed, specs, n_cands, rng, with_
     sequence whose candidate set also holds the greedy continuation itself (-1: none)."""
     from paper_2602_12957_amd.runtime import pack_prefix_tree
     weights = W.make_weights(desc, seed)
-    act = act_dtype_of(desc)
     n = len(specs)
     ora, blocks, trees = [], [], []
     for sp in specs:
         vis, prompt = W.make_prefix(desc, seed, sp.seq_id, sp.n_visual, sp.n_prompt)
-        cache, pending = O.prefill(desc, weights, vis, prompt, act_dtype=act)
+        cache, pending = O.prefill(desc, weights, vis, prompt)
         base = len(cache)
-        target = O.greedy_decode(desc, weights, cache, pending, sp.draft_len, act_dtype=act)
+        target = O.greedy_decode(desc, weights, cache, pending, sp.draft_len)
         cache.truncate(base)
         cands = _candidates(rng, target, desc.vocab, n_cands[sp.seq_id], sp.draft_len)
         if sp.seq_id == with_target:
             cands.append(target.tolist())           # the greedy continuation itself is among the drafts
         acc, bonus, logits, (tokens, parent, depth, end) = O.verify_tree(desc, weights, cache, pending, cands,
-                                                                         act_dtype=act, log_tau=log_tau)
+                                                                         log_tau=log_tau)
         ora.append((acc, bonus, logits, tokens, parent, end))
         t, e, d = pack_prefix_tree(pending, cands)
         np.testing.assert_array_equal(t, tokens)
