@@ -182,6 +182,17 @@ int hsd_kv_pool_init(void *stream, const hsd_kv_pool *pool);
 int hsd_verify_region_batch(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch,
                             void *workspace, size_t ws_bytes);
 
+/* hsd_verify_region_batch for callers that cannot allocate or hand over a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs, kernels and bits as
+ * hsd_verify_region_batch; the workspace is a fixed device array inside the library (hsd_noalloc_scratch_bytes(),
+ * 16 MiB, held by every GPU the library runs on until the process ends).  Calls no allocating routine.
+ * Returns HSD_ERANGE when hsd_workspace_bytes(desc, batch->total_q, batch->n_seq) exceeds that size (for the
+ * 24-layer d1024 model: up to about 400 rows per call).  All calls on one GPU share the array (whatever context they
+ * use): calls that overlap in time on one GPU race; calls on one stream, or ordered by events, are safe.  Nothing in
+ * the array needs to start at zero and nothing is kept between calls. */
+int hsd_verify_region_batch_noalloc(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch);
+size_t hsd_noalloc_scratch_bytes(void);
+
 /* Page-level verification (Section 3.1 Stage 2, Eq. 4): few long draft blocks.  Same semantics and
  * outputs as hsd_verify_region_batch, and the same bits for every row (a row's arithmetic does not depend on the
  * entry point).  The attention workgroups are twice as large here (64 query rows of four query heads share each

@@ -62,6 +62,9 @@ lib.hsd_workspace_bytes.restype = C.c_size_t
 lib.hsd_kv_pool_init.argtypes = [vp, _P(hsd_kv_pool)]
 for _n in ("hsd_verify_region_batch", "hsd_verify_page", "hsd_prefill"):
     getattr(lib, _n).argtypes = [vp, vp, _P(hsd_kv_pool), _P(hsd_batch), vp, C.c_size_t]
+lib.hsd_verify_region_batch_noalloc.argtypes = [vp, vp, _P(hsd_kv_pool), _P(hsd_batch)]
+lib.hsd_noalloc_scratch_bytes.argtypes = []
+lib.hsd_noalloc_scratch_bytes.restype = C.c_size_t
 lib.hsd_kv_commit_rollback.argtypes = [vp, vp, _P(hsd_kv_pool), _P(hsd_batch), vp]
 
 lib.hsd_profile_enable.argtypes = [vp, C.c_int, i32]
@@ -74,7 +77,7 @@ lib.hsd_debug_set.argtypes = [vp, C.c_int, C.c_int64]
  HSD_DEBUG_GEMM_CFG_QKV, HSD_DEBUG_GEMM_CFG_O, HSD_DEBUG_GEMM_CFG_GATE_UP, HSD_DEBUG_GEMM_CFG_DOWN,
  HSD_DEBUG_GEMM_CFG_LM_HEAD) = range(1, 11)
 
-EXPORTS = ["hsd_debug_set", "hsd_profile_enable", "hsd_profile_read", "hsd_status_string", "hsd_validate_model", "hsd_validate_batch", "hsd_create", "hsd_destroy",
+EXPORTS = ["hsd_verify_region_batch_noalloc", "hsd_noalloc_scratch_bytes", "hsd_debug_set", "hsd_profile_enable", "hsd_profile_read", "hsd_status_string", "hsd_validate_model", "hsd_validate_batch", "hsd_create", "hsd_destroy",
            "hsd_workspace_bytes", "hsd_kv_pool_init", "hsd_verify_region_batch", "hsd_verify_page",
            "hsd_kv_commit_rollback", "hsd_prefill"]
 
@@ -103,6 +106,9 @@ def hsd_destroy(ctx): lib.hsd_destroy(ctx)
 def hsd_kv_pool_init(stream, pool): check("hsd_kv_pool_init", lib.hsd_kv_pool_init(stream, C.byref(pool)))
 def hsd_verify_region_batch(ctx, stream, pool, batch, ws, ws_bytes):
     check("hsd_verify_region_batch", lib.hsd_verify_region_batch(ctx, stream, C.byref(pool), C.byref(batch), ws, ws_bytes))
+def hsd_verify_region_batch_noalloc(ctx, stream, pool, batch):
+    check("hsd_verify_region_batch_noalloc", lib.hsd_verify_region_batch_noalloc(ctx, stream, C.byref(pool), C.byref(batch)))
+def hsd_noalloc_scratch_bytes(): return lib.hsd_noalloc_scratch_bytes()
 def hsd_verify_page(ctx, stream, pool, batch, ws, ws_bytes):
     check("hsd_verify_page", lib.hsd_verify_page(ctx, stream, C.byref(pool), C.byref(batch), ws, ws_bytes))
 def hsd_prefill(ctx, stream, pool, batch, ws, ws_bytes):

@@ -23,8 +23,15 @@
 
 using namespace hsd;
 
+// Scratch for hsd_verify_region_batch_noalloc: the workspace of a verify call lives in this file-scope device array
+// instead of caller memory.  Every GPU the library runs on holds its own copy until the process ends; host code never
+// uses the array's name as an address, only the pointer hipGetSymbolAddress returns for the current device.
+constexpr size_t kStaticWsBytes = size_t{16} << 20;
+static __device__ __align__(256) unsigned char g_static_ws[kStaticWsBytes];
+
 struct hsd_ctx {
   hsd_model_desc desc;
+  void *static_ws = nullptr;  // device address of g_static_ws on the context's device
   const void *tok_embed;
   const float *final_norm;
   const void *lm_head;
@@ -652,6 +659,12 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
   c->w_gate_up.assign(w->w_gate_up, w->w_gate_up + desc->n_layers);
   c->w_down.assign(w->w_down, w->w_down + desc->n_layers);
   c->n_cu = prop.multiProcessorCount;
+  // the context belongs to the current device: resolve that device's copy of the static scratch array once
+  if (hipGetSymbolAddress(&c->static_ws, HIP_SYMBOL(g_static_ws)) != hipSuccess || c->static_ws == nullptr) {
+    (void)hipGetLastError();
+    delete c;
+    return HSD_EHIP;
+  }
   c->force_simple = false;
   c->split_rows = split_row_limit(*desc);
   // 256x256 8-wave tiles for the wide projections (gate/up, LM head), 64x128 tiles for QKV and O (more workgroups),
@@ -740,6 +753,16 @@ int hsd_verify_region_batch(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool,
                             size_t ws_bytes) {
   return verify_common(ctx, stream, pool, batch, ws, ws_bytes, /*page_mode=*/false, /*prefill=*/false);
 }
+
+int hsd_verify_region_batch_noalloc(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch) {
+  if (ctx == nullptr || batch == nullptr) return HSD_EINVAL;
+  if (batch->total_q < 1 || batch->n_seq < 1) return HSD_EINVAL;
+  // the batch must fit the fixed scratch array (nothing is allocated here or anywhere below)
+  if (hsd_workspace_bytes(&ctx->desc, batch->total_q, batch->n_seq) > kStaticWsBytes) return HSD_ERANGE;
+  return verify_common(ctx, stream, pool, batch, ctx->static_ws, kStaticWsBytes, /*page_mode=*/false, /*prefill=*/false);
+}
+
+size_t hsd_noalloc_scratch_bytes(void) { return kStaticWsBytes; }
 
 int hsd_verify_page(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch, void *ws,
                     size_t ws_bytes) {

@@ -308,14 +308,17 @@ class Engine:
                 torch.cuda.current_stream(self.dev).synchronize()   # dev_emb must outlive the pass
 
     def verify(self, slots: Sequence[int], blocks: Sequence[np.ndarray], mode: str = "region",
-               dump_rows=None, log_tau: float = 0.0, trees=None) -> VerifyOutput:
+               dump_rows=None, log_tau: float = 0.0, trees=None, noalloc: bool = False) -> VerifyOutput:
         """One verification pass; blocks[i] = [pending token, d_1..d_k] of sequence slots[i].  Asynchronous.
         log_tau = 0 is the exact-match rule; log_tau < 0 the relaxed acceptance test with threshold tau.
         With trees[i] = (tree_end, tree_depth), blocks[i] holds the tokens of a packed prefix tree
         (see pack_prefix_tree) instead of a chain."""
         b = self._make_batch(slots, blocks, dump_rows, log_tau=log_tau, trees=trees)
-        fn = B.hsd_verify_region_batch if mode == "region" else B.hsd_verify_page
-        fn(self.ctx, self.stream, self.cpool, b, _ptr(self.ws), self.ws_bytes)
+        if noalloc:       # the library's own fixed scratch array instead of this engine's workspace
+            B.hsd_verify_region_batch_noalloc(self.ctx, self.stream, self.cpool, b)
+        else:
+            fn = B.hsd_verify_region_batch if mode == "region" else B.hsd_verify_page
+            fn(self.ctx, self.stream, self.cpool, b, _ptr(self.ws), self.ws_bytes)
         self._batch = b
         n, T = b.n_seq, b.total_q
         return VerifyOutput(n, T, self._cu.copy(), self.argmax[:T], self.margin[:T], self.accept_len[:n],
