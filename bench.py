@@ -119,8 +119,14 @@ def run_config(cfg_index, args, weights_cache):
     # workspace rows: one verification block, or (configs[1]) all prefixes at once for the prefill figure
     ws_rows = max(total_q, sum(prefix_len) if cfg_index == 1 else 8192)
     steps = args.steps if cfg_index == 1 else max(3, min(args.steps, args.other_steps))
+    debug = None
+    if args.debug_knobs:       # experiments only: "name=value,..." with gemm_cfg=q:o:g:d:l
+        debug = {}
+        for item in args.debug_knobs.split(","):
+            k, v = item.split("=")
+            debug[k] = tuple(int(x) for x in v.split(":")) if k == "gemm_cfg" else int(v)
     eng = Engine(desc, weights, n_blocks, n, maxb, ws_rows, max_dump=total_q if cfg_index == 1 else 0,
-                 attn_key_chunk=args.attn_key_chunk)
+                 attn_key_chunk=args.attn_key_chunk, debug=debug)
     slots = list(range(n))
     toks, embs, pend = [], [], []
     for sp in specs:
@@ -382,6 +388,8 @@ def main():
                          "the rule the headline metric is defined on")
     ap.add_argument("--attn-key-chunk", type=int, default=0,
                     help="attention key split (hsd_model_desc.attn_key_chunk): keys per chunk, 0 = unsplit")
+    ap.add_argument("--debug-knobs", type=str, default="",
+                    help="experiments only: hsd_debug_set knobs, e.g. kchunks_down=1,gemm_cfg=7:9:8:9:8")
     ap.add_argument("--breakdown", action="store_true",
                     help="after the timed region, time every kernel class in turn (extra steps) and report avg us per launch")
     args = ap.parse_args()

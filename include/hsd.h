@@ -243,17 +243,11 @@ int hsd_profile_read(hsd_ctx *ctx, int32_t *n_launches, float *total_ms);
  *   HSD_DEBUG_SYNC_LAYERS   value != 0: the verify/prefill calls WAIT for the stream after every layer (an
  *                           exception to "never synchronises"; bounds the launches in flight for counter tools)
  *   HSD_DEBUG_FORCE_SIMPLE  value != 0: bf16 models run the plain fp32-FMA kernels (cross-check of the MFMA path)
- *   HSD_DEBUG_SPLIT_ROWS    largest row count for which the down projection runs as split-K (lowered by tests to
- *                           reach the chunk-walking form with few rows)
- *   HSD_DEBUG_KCHUNKS_O / _DOWN   K chunks of the O / down projection, 1..4 (0 = default)
  *   HSD_DEBUG_GEMM_CFG_*    tile configuration (0..9) of one GEMM call site, used for every row count
  * Returns HSD_EINVAL for an unknown knob or a value out of range. */
 enum {
   HSD_DEBUG_SYNC_LAYERS = 1,
   HSD_DEBUG_FORCE_SIMPLE = 2,
-  HSD_DEBUG_SPLIT_ROWS = 3,
-  HSD_DEBUG_KCHUNKS_O = 4,
-  HSD_DEBUG_KCHUNKS_DOWN = 5,
   HSD_DEBUG_GEMM_CFG_QKV = 6,
   HSD_DEBUG_GEMM_CFG_O = 7,
   HSD_DEBUG_GEMM_CFG_GATE_UP = 8,

@@ -73,9 +73,9 @@ lib.hsd_profile_read.argtypes = [vp, _P(i32), _P(f32)]
  HSD_PROF_GEMM_LM_HEAD, HSD_PROF_RMSNORM) = range(8)
 
 lib.hsd_debug_set.argtypes = [vp, C.c_int, C.c_int64]
-(HSD_DEBUG_SYNC_LAYERS, HSD_DEBUG_FORCE_SIMPLE, HSD_DEBUG_SPLIT_ROWS, HSD_DEBUG_KCHUNKS_O, HSD_DEBUG_KCHUNKS_DOWN,
- HSD_DEBUG_GEMM_CFG_QKV, HSD_DEBUG_GEMM_CFG_O, HSD_DEBUG_GEMM_CFG_GATE_UP, HSD_DEBUG_GEMM_CFG_DOWN,
- HSD_DEBUG_GEMM_CFG_LM_HEAD) = range(1, 11)
+HSD_DEBUG_SYNC_LAYERS, HSD_DEBUG_FORCE_SIMPLE = 1, 2
+(HSD_DEBUG_GEMM_CFG_QKV, HSD_DEBUG_GEMM_CFG_O, HSD_DEBUG_GEMM_CFG_GATE_UP, HSD_DEBUG_GEMM_CFG_DOWN,
+ HSD_DEBUG_GEMM_CFG_LM_HEAD) = range(6, 11)
 
 EXPORTS = ["hsd_verify_region_batch_noalloc", "hsd_noalloc_scratch_bytes", "hsd_debug_set", "hsd_profile_enable", "hsd_profile_read", "hsd_status_string", "hsd_validate_model", "hsd_validate_batch", "hsd_create", "hsd_destroy",
            "hsd_workspace_bytes", "hsd_kv_pool_init", "hsd_verify_region_batch", "hsd_verify_page",

@@ -11,17 +11,37 @@
 
 namespace hsd {
 
+// RMSNorm folded into the GEMMs around it.  The projection that completes a residual row (EpiResidualNorm below)
+// leaves, besides x itself, the row times the next norm's gain (the next GEMM's operand) and the row's sum of
+// squares in pieces of 64 columns; the next GEMM multiplies its accumulators by the row's
+// rstd = rsqrt(mean(x^2) + eps), which commutes with the contraction: (x g rstd) W^T = rstd (x g) W^T.
+// The pieces are added in ascending column order by every reader, so a row's rstd has the same bits everywhere.
+struct RowScale {
+  const float *ss;   // [rows][n_parts] partial sums of squares, or nullptr: the operand is already normalised
+  int n_parts;       // d_model / 64
+  float inv_d, eps;
+  __device__ __forceinline__ float at(int m) const {
+    if (ss == nullptr) return 1.0f;
+    const float *p = ss + static_cast<size_t>(m) * n_parts;
+    float s = 0.f;
+    for (int i = 0; i < n_parts; ++i) s += p[i];
+    return 1.0f / sqrtf(s * inv_d + eps);
+  }
+};
+
 // C = A W^T for the QKV projection, then rotary embedding on q and k heads, q to the packed q buffer,
 // k and v appended to the paged cache at the row's absolute position (speculative append).
 template <typename T>
 struct EpiQKV {
   static constexpr bool kDual = false;
   static constexpr bool kChunked = false;
+  static constexpr bool kRowScale = true;
   __device__ __forceinline__ const EpiQKV &for_split(int, int) const { return *this; }
   int n_q_heads, n_kv_heads;
   RowMeta meta;
   PagedKV kv;
   T *q_out;  // [T, n_q_heads*64]
+  RowScale rs;
 
   // One (row, column pair) at a time, given the row's rotary pair cs = rope_cs[m][n & 31] and cache destination
   // kvd = row_kv[m].
@@ -98,52 +118,85 @@ struct EpiQKV {
   }
 };
 
-// x += A W^T (fp32 residual stream, each element owned by one thread: deterministic).  When the GEMM runs as
-// split-K, the chunk's partial sum goes to part[split][m][n] instead and a later kernel adds the partials in
-// chunk order to x (k_reduce_rmsnorm).
+// x += A W^T (fp32 residual stream, each element owned by one thread: deterministic).  Plain-kernel path; the MFMA
+// kernels use EpiResidualNorm.
 struct EpiResidual {
   static constexpr bool kDual = false;
-  static constexpr bool kChunked = true;
+  static constexpr bool kChunked = false;
+  static constexpr bool kRowScale = false;
+  __device__ __forceinline__ const EpiResidual &for_split(int, int) const { return *this; }
   float *x;
   int ld;
-  float *part;  // [k_chunks][M][ld] or nullptr when the GEMM is never launched split
-  bool to_part;
-  __device__ __forceinline__ EpiResidual for_split(int split, int M) const {
-    EpiResidual e = *this;
-    e.to_part = split >= 0;
-    if (split >= 0) e.part = part + static_cast<size_t>(split) * M * ld;
-    return e;
-  }
-  // Row-piece form used by the MFMA kernels: four consecutive columns n .. n+3 (lo) and n+32 .. n+35 (hi); eight
-  // adjacent lanes cover a full 128-byte line of the row.
   static constexpr int kPiece = 4;
   __device__ __forceinline__ void piece(int m, int n, float (&lo)[4], float (&hi)[4]) const {
-    if (to_part) {
-      float *p = part + static_cast<size_t>(m) * ld + n;
-      store_row(p, lo);
-      store_row(p + 32, hi);
-    } else {
-      float *p = x + static_cast<size_t>(m) * ld + n;
-      const floatx4 a = *reinterpret_cast<const floatx4 *>(p), b = *reinterpret_cast<const floatx4 *>(p + 32);
+    float *p = x + static_cast<size_t>(m) * ld + n;
+    const floatx4 a = *reinterpret_cast<const floatx4 *>(p), b = *reinterpret_cast<const floatx4 *>(p + 32);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        lo[e] += a[e];
-        hi[e] += b[e];
-      }
-      store_row(p, lo);
-      store_row(p + 32, hi);
+    for (int e = 0; e < 4; ++e) {
+      lo[e] += a[e];
+      hi[e] += b[e];
     }
+    store_row(p, lo);
+    store_row(p + 32, hi);
   }
   __device__ __forceinline__ void pair(int m, int n, float lo, float hi) const {
-    if (to_part) {
-      float *p = part + static_cast<size_t>(m) * ld + n;
-      p[0] = lo;
-      p[32] = hi;
-    } else {
-      float *p = x + static_cast<size_t>(m) * ld + n;
-      p[0] += lo;
-      p[32] += hi;
+    float *p = x + static_cast<size_t>(m) * ld + n;
+    p[0] += lo;
+    p[32] += hi;
+  }
+};
+
+// Sum over the 8 adjacent lanes that hold one 64-column piece of a row (lanes 8k .. 8k+7), by lane-crossing moves
+// inside the vector unit; every lane ends up with the same bits (the additions pair up commutatively).
+__device__ __forceinline__ float sum8_lanes(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, true));   // quad_perm [1,0,3,2]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, true));   // quad_perm [2,3,0,1]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, true));  // row_half_mirror
+  return v;
+}
+
+// x += A W^T as EpiResidual (never split), and everything the RMSNorm after it needs (see RowScale): h = x * gain
+// in the GEMM operand type and the sum of squares of each 64-column piece of the row.  With gain == nullptr (no
+// norm follows: last layer of a prefill) only x is updated.  MFMA kernels only.
+struct EpiResidualNorm {
+  static constexpr bool kDual = false;
+  static constexpr bool kChunked = false;
+  static constexpr bool kRowScale = false;
+  __device__ __forceinline__ const EpiResidualNorm &for_split(int, int) const { return *this; }
+  float *x;
+  int ld;
+  const float *gain;  // [ld] gain of the norm that follows, or nullptr
+  bf16 *h;            // [M][ld]
+  float *ss;          // [M][ld / 64]
+  static constexpr int kPiece = 4;
+  __device__ __forceinline__ void piece(int m, int n, float (&lo)[4], float (&hi)[4]) const {
+    float *p = x + static_cast<size_t>(m) * ld + n;
+    const floatx4 a = *reinterpret_cast<const floatx4 *>(p), b = *reinterpret_cast<const floatx4 *>(p + 32);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      lo[e] += a[e];
+      hi[e] += b[e];
     }
+    store_row(p, lo);
+    store_row(p + 32, hi);
+    if (gain == nullptr) return;
+    const floatx4 g0 = *reinterpret_cast<const floatx4 *>(gain + n), g1 = *reinterpret_cast<const floatx4 *>(gain + n + 32);
+    floatx4 h0, h1;
+    float sq = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      h0[e] = lo[e] * g0[e];
+      h1[e] = hi[e] * g1[e];
+      sq += lo[e] * lo[e];
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sq += hi[e] * hi[e];
+    bf16 *hp = h + static_cast<size_t>(m) * ld + n;
+    *reinterpret_cast<bf16x4 *>(hp) = __builtin_convertvector(h0, bf16x4);
+    *reinterpret_cast<bf16x4 *>(hp + 32) = __builtin_convertvector(h1, bf16x4);
+    // the 8 lanes n % 64 / 4 = 0..7 of this row hold the 64-column piece between them
+    sq = sum8_lanes(sq);
+    if ((n & 63) == 0) ss[static_cast<size_t>(m) * (ld >> 6) + (n >> 6)] = sq;
   }
 };
 
@@ -152,9 +205,11 @@ template <typename T>
 struct EpiSwiGLU {
   static constexpr bool kDual = true;
   static constexpr bool kChunked = false;
+  static constexpr bool kRowScale = true;
   __device__ __forceinline__ const EpiSwiGLU &for_split(int, int) const { return *this; }
   T *u;
   int ld;
+  RowScale rs;
   // silu(g) * up with the hardware exp2 and reciprocal (each within 1 ulp; the result is rounded to the operand
   // type right after).  g -> -inf gives exp2 = +inf, rcp = 0, result -0.
   __device__ __forceinline__ static float f(float g, float up) {
@@ -187,6 +242,7 @@ struct EpiSwiGLU {
 struct EpiLMHead {
   static constexpr bool kDual = false;
   static constexpr bool kChunked = false;
+  static constexpr bool kRowScale = true;
   __device__ __forceinline__ const EpiLMHead &for_split(int, int) const { return *this; }
   Top2 *part;  // [T][n_tiles]
   int n_tiles;
@@ -198,6 +254,7 @@ struct EpiLMHead {
   const int32_t *tokens;     // [T] packed token ids
   const int32_t *row_end;    // [T] packed index one past each row's subtree
   float *want_logit;         // [T] out, indexed by the CANDIDATE row, pre-filled with -inf; nullptr = exact rule
+  RowScale rs;
   // called with the logits v[0..count) of row m at vocabulary ids n[e]: every (row, id) pair is computed by exactly
   // one thread of the launch, so each wanted logit is written once, from the accumulator that feeds the arg-max
   template <typename F>

@@ -36,7 +36,7 @@ struct GemmCfg {
   static constexpr int TM = BP / WM / 32, TN = BQ / WN / 32;  // 32x32 MFMA tiles per wave
   static constexpr int kStride = BK + 8;                      // bf16 elements per LDS row
   static constexpr int kStage = (BP + BQ) * kStride;          // bf16 elements per stage
-  static constexpr int kSmemBytes = 2 * kStage * 2;
+  static constexpr int kSmemBytes = 2 * kStage * 2;            // operand stages; kRowScaleBytes more follow them
   static constexpr int kChunks = BK / 8;                      // 16-byte chunks per tile row
   static constexpr int kLoadsP = BP * kChunks / kThreads, kLoadsQ = BQ * kChunks / kThreads;
   static constexpr int kEpiStride = TN * 32 + 4;              // floats per row of a wave's epilogue staging region
@@ -78,10 +78,27 @@ __host__ __device__ inline void gemm_tiles(int M, int N, int &tiles_act, int &ti
   }
 }
 
-// Hands the accumulators of one wave to the epilogue functor (see the mode descriptions above).
+// Row scales (the rstd of a folded RMSNorm, see RowScale) of a tile's activation rows live in LDS behind the operand
+// stages: computed once per workgroup while the first K slices are on their way, read by the epilogue.
+constexpr int kRowScaleBytes = 256 * 4;   // up to 256 activation rows per tile
+
+template <typename Cfg, int MODE, typename Epi>
+__device__ __forceinline__ void gemm_row_scales(const Epi &epi, int M, int m0, int t, int n_threads,
+                                                unsigned char *smem_raw) {
+  if constexpr (Epi::kRowScale) {
+    constexpr int ROWS = (MODE == kModeSwapLM) ? Cfg::BQ : Cfg::BP;
+    static_assert(ROWS * 4 <= kRowScaleBytes, "row scales must fit their LDS region");
+    float *rsl = reinterpret_cast<float *>(smem_raw + Cfg::kSmemBytes);
+    for (int r = t; r < ROWS; r += n_threads) rsl[r] = (m0 + r < M) ? epi.rs.at(m0 + r) : 1.0f;
+  }
+}
+
+// Hands the accumulators of one wave to the epilogue functor (see the mode descriptions above).  A barrier must lie
+// between gemm_row_scales and this call (every K loop has one).
 template <typename Cfg, int MODE, typename Epi>
 __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[Cfg::TM][Cfg::TN], int M, int N, int m0, int n0, int tw,
                                               int wi, int wj, int lane, const Epi &epi, float *stage) {
+  const float *rsl = reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(stage) + Cfg::kSmemBytes);
   constexpr int BP = Cfg::BP, BQ = Cfg::BQ, TM = Cfg::TM, TN = Cfg::TN;
   const int col = lane & 31, half = lane >> 5;
   if constexpr (MODE == kModeSwapLM) {
@@ -89,6 +106,13 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[Cfg::TM][Cfg::TN],
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int m = m0 + wj * (BQ / Cfg::WN) + j * 32 + col;
+      if (epi.rs.ss != nullptr && m < M) {   // fold in the row's rstd before anything looks at the logits
+        const float rsc = rsl[wj * (BQ / Cfg::WN) + j * 32 + col];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[i][j][v] *= rsc;
+      }
       Top2 tp = top2_init();
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -157,6 +181,8 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[Cfg::TM][Cfg::TN],
       for (int it = 0; it < 32 / RPI; ++it) {
         const int r = it * RPI + pr;
         const int m = m0 + wi * (BP / Cfg::WM) + i * 32 + r;
+        float rsc = 1.0f;
+        if constexpr (Epi::kRowScale) rsc = rsl[wi * (BP / Cfg::WM) + i * 32 + r];
 #pragma unroll
         for (int jg = 0; jg < TN / 2; ++jg) {
           float lo[PC], hi[PC];
@@ -167,8 +193,8 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[Cfg::TM][Cfg::TN],
             const floatx4 b = *reinterpret_cast<const floatx4 *>(src + 32 + 4 * q);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              lo[4 * q + e] = a[e];
-              hi[4 * q + e] = b[e];
+              lo[4 * q + e] = Epi::kRowScale ? a[e] * rsc : a[e];
+              hi[4 * q + e] = Epi::kRowScale ? b[e] * rsc : b[e];
             }
           }
           if (m >= M) continue;
@@ -210,6 +236,7 @@ __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K
   // first activation row / first output column of this tile
   const int m0 = ta * ((MODE == kModeSwapLM) ? BQ : BP);
   const int n0 = tw * ((MODE == kModeSwapLM) ? BP : ((MODE == kModeDual) ? BQ / 2 : BQ));
+  gemm_row_scales<Cfg, MODE>(epi, M, m0, t, NT, smem_raw);
 
   // ---- global source of every 16-byte chunk this thread stages (fixed over the K loop)
   const bf16 *srcP[Cfg::kLoadsP];

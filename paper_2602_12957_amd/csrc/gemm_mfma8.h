@@ -44,6 +44,7 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, int k_c
   gemm_tile_of(blockIdx.x, M, (MODE == kModeDual) ? 2 * N : N, tiles_act, tiles_w, ta, tw);
   const int m0 = ta * ((MODE == kModeSwapLM) ? BQ : BP);
   const int n0 = tw * ((MODE == kModeSwapLM) ? BP : ((MODE == kModeDual) ? BQ / 2 : BQ));
+  gemm_row_scales<Cfg, MODE>(epi, M, m0, t, 512, smem_raw);
 
   // ---- staging map: chunk c = t + 512*i covers tile row t/8 + 64*i, 16-byte piece t%8
   const int r8 = t >> 3, kc = t & 7;

@@ -126,6 +126,7 @@ __global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, int k
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   const int frag_p = (wi * (BP / Cfg::WM) + (lane & 31)) * LS + (lane >> 5) * 8;
   const int frag_q = BP * LS + (wj * (BQ / Cfg::WN) + (lane & 31)) * LS + (lane >> 5) * 8;
+  gemm_row_scales<Cfg, MODE>(epi, M, m0, t, NT, smem_raw);   // while the moving waves fetch the first slices
   __syncthreads();                                     // barrier 1
   for (int kt = 0; kt < nk; ++kt) {
     const uint16_t *sp = smem + (kt & 1) * Cfg::kStage;

@@ -42,8 +42,6 @@ struct hsd_ctx {
   bool sync_layers = false;  // wait for the stream after every layer (bounds the launches in flight for tools that
                              // track each dispatch; never set in timed runs)
   bool force_simple;  // run the plain kernels also for bf16 (cross-check of the MFMA path)
-  int k_chunks[2] = {0, 0};  // override of the O / down K chunking (0 = default)
-  int64_t split_rows; // largest row count for which the O / down projections run as split-K
   bool gemm_cfg_forced = false;  // a tile configuration was set by hand: use it for every row count
   int gemm_cfg[5];    // tile configuration of the MFMA GEMM per call site (qkv, o, gate_up, down, lm_head)
   // per-kernel timing (hsd_profile_*)
@@ -65,22 +63,11 @@ struct Workspace {
   float *want_logit, *row_max;
   float2 *rope_cs;
   Top2 *lm_part;
-  float *part;  // split-K partial sums of the O / down projections
+  float *ss;    // [T][d_model / 64] sums of squares of the residual rows, in 64-column pieces (see RowScale)
   float *attn_part_o;    // key-split attention: un-normalised partial rows and their (reference point, sum)
   float2 *attn_part_ml;
   size_t total;
 };
-
-// The O and down projections run as split-K while the launch would otherwise leave most CUs idle: fewer output
-// tiles than twice the 256 CUs of the chip.  Returns the largest row count for which that is the case.
-inline int64_t split_row_limit(const hsd_model_desc &d) {
-  const int64_t tiles_n = d.d_model / 128;
-  return (512 / tiles_n) * 128;
-}
-// K chunking per projection, fixed: the K-reduction order never depends on the batch.  The O projection (K = 1024)
-// runs unsplit; the down projection (K = 4096) in two chunks.  kMaxChunks bounds the hsd_debug_set override
-// and sizes the partial-sum buffer.
-constexpr int kChunksO = 1, kChunksDown = 2, kMaxChunks = 4;
 
 // Carves the workspace; with base == nullptr only the size is computed.
 Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
@@ -111,8 +98,7 @@ Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
   w.attn_tiles = reinterpret_cast<AttnTile *>(take((T / 32 + n_seq) * sizeof(AttnTile)));   // 32 = smallest query tile
   w.rope_cs = reinterpret_cast<float2 *>(take(T * 32 * sizeof(float2)));
   w.lm_part = reinterpret_cast<Top2 *>(take(T * (d.vocab / 64) * sizeof(Top2)));
-  const int64_t part_rows = T < split_row_limit(d) ? T : split_row_limit(d);
-  w.part = reinterpret_cast<float *>(take(d.dtype == HSD_BF16 ? kMaxChunks * part_rows * d.d_model * sizeof(float) : 0));
+  w.ss = reinterpret_cast<float *>(take(T * (d.d_model / 64) * sizeof(float)));
   const size_t split_rh = (d.dtype == HSD_BF16 && d.attn_key_chunk > 0) ? kAttnMaxChunks * T * d.n_q_heads : 0;
   w.attn_part_o = reinterpret_cast<float *>(take(split_rh * d.head_dim * sizeof(float)));
   w.attn_part_ml = reinterpret_cast<float2 *>(take(split_rh * sizeof(float2)));
@@ -155,12 +141,10 @@ int launch_gemm_mfma_impl(hipStream_t st, int M, int N, int K, const void *A, co
                           bool split) {
   constexpr int MODE = GemmModeOf<Epi>::value;
   auto kern = k_gemm_mfma<Cfg, MODE, Epi, WALK>;
-  constexpr int smem = Cfg::kSmemBytes;
+  constexpr int smem = Cfg::kSmemBytes + kRowScaleBytes;
   // set once per instantiation (initialisation of a function-local static is thread safe)
-  static const hipError_t attr_rc =
-      smem > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem)
-                       : hipSuccess;
+  static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (attr_rc != hipSuccess) return HSD_EHIP;
   if constexpr (MODE == kModeSwapLM) epi.n_tiles = (N / Cfg::BP) * Cfg::WM;
   int tiles_act, tiles_w;
@@ -186,7 +170,7 @@ int launch_gemm_mfma8_impl(hipStream_t st, int M, int N, int K, const void *A, c
   constexpr int MODE = GemmModeOf<Epi>::value;
   using Cfg = GemmCfg8;
   auto kern = k_gemm_mfma8<MODE, Epi, WALK>;
-  constexpr int smem = Cfg::kSmemBytes;
+  constexpr int smem = Cfg::kSmemBytes + kRowScaleBytes;
   static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (attr_rc != hipSuccess) return HSD_EHIP;
@@ -214,7 +198,7 @@ int launch_gemm_mfma_ws(hipStream_t st, int M, int N, int K, const void *A, cons
                         bool split) {
   constexpr int MODE = GemmModeOf<Epi>::value;
   auto kern = k_gemm_mfma_ws<Cfg, MODE, Epi>;
-  constexpr int smem = Cfg::kSmemBytes;
+  constexpr int smem = Cfg::kSmemBytes + kRowScaleBytes;
   static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (attr_rc != hipSuccess) return HSD_EHIP;
@@ -254,8 +238,9 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_
     // 9 / 7: 64x128 / 128x128 tiles with separate operand-moving waves
     if (site == kSiteLM) cfg = M <= 128 ? 0 : cfg;
     else if (M <= 64) cfg = 9;                                         // token-by-token decoding: one row tile
-    else if (site == kSiteQKV || site == kSiteDown) cfg = M <= 1024 ? 9 : 7;
-    else if (site == kSiteO) cfg = 9;
+    else if (site == kSiteQKV) cfg = M <= 1024 ? 9 : 7;
+    else if (site == kSiteO || site == kSiteDown) cfg = 9;   // down walks all of K in one workgroup: small tiles,
+                                                             // so that a pass over ~2 k rows still fills the chip
     else if (site == kSiteGateUp) cfg = M <= 256 ? 9 : (M <= 1024 ? 7 : cfg);
   }
   // ... and a pass over many rows (prefill chunks, long-document blocks) has enough row tiles to fill the chip with
@@ -309,11 +294,15 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
       default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi, k_chunks, split);
     }
   }
-  dim3 grid(N / 64, (M + 63) / 64);
-  hipLaunchKernelGGL((k_gemm_simple<T, Epi>), grid, dim3(256), 0, st, M, N, K, static_cast<const T *>(A),
-                     static_cast<const T *>(W), epi);
-  HSD_LAUNCH_CHECK();
-  return HSD_OK;
+  if constexpr (std::is_same<Epi, EpiResidualNorm>::value) {
+    return HSD_EINVAL;   // this epilogue exists for the MFMA kernels only (the caller never gets here with it)
+  } else {
+    dim3 grid(N / 64, (M + 63) / 64);
+    hipLaunchKernelGGL((k_gemm_simple<T, Epi>), grid, dim3(256), 0, st, M, N, K, static_cast<const T *>(A),
+                       static_cast<const T *>(W), epi);
+    HSD_LAUNCH_CHECK();
+    return HSD_OK;
+  }
 }
 
 // Number of (row, column-tile) partial records the LM-head GEMM writes per row.
@@ -444,38 +433,41 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
   const bool tree = b->tree_end != nullptr;
   RowMeta meta{ws.row_seq, ws.row_pos, ws.rope_cs, ws.row_kv, ws.row_slot, ws.row_base, tree ? ws.row_end : nullptr};
   const bool mfma_path = std::is_same<T, bf16>::value && !ctx->force_simple;
-  auto chunks_for = [&](int want, int K) { return (mfma_path && K % (want * 64) == 0) ? want : 1; };
-  const bool split_ok = mfma_path && Tq <= ctx->split_rows;
 
-  // RMSNorm of the residual stream; when the projection before it ran as split-K (`pending_chunks` > 0) the same
-  // kernel first adds the partial sums to x in chunk order.
-  auto norm = [&](const float *gain, int pending_chunks) -> int {
+  // RMSNorm as a kernel of its own: the first norm of a pass, and every norm of the plain-kernel path
+  auto norm = [&](const float *gain) -> int {
     ProfScope ps(ctx, st, HSD_PROF_RMSNORM);
-    if (pending_chunks > 0)
-      hipLaunchKernelGGL((k_reduce_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x,
-                         ws.part, pending_chunks, gain, static_cast<T *>(ws.h));
-    else if (gain != nullptr)
-      hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x, gain,
-                         static_cast<T *>(ws.h));
+    hipLaunchKernelGGL((k_rmsnorm<T>), dim3((Tq + 3) / 4), dim3(256), 0, st, Tq, d.d_model, d.rms_eps, ws.x, gain,
+                       static_cast<T *>(ws.h));
     HSD_LAUNCH_CHECK();
     return HSD_OK;
   };
-  // x += A W^T with a fixed chunking of K; returns (through `pending`) the number of partials left to add
-  auto residual_proj = [&](int site, int prof, const void *A, const void *W, int K, int want_chunks,
-                           int *pending) -> int {
-    ProfScope ps(ctx, st, prof);
-    const int chunks = chunks_for(want_chunks, K);
-    const bool split = split_ok && chunks > 1;
-    EpiResidual er{ws.x, d.d_model, ws.part, false};
-    *pending = split ? chunks : 0;
-    return launch_gemm<T>(ctx, st, site, Tq, d.d_model, K, A, W, er, chunks, split);
+  // x += A W^T.  MFMA path: the epilogue also prepares the norm that follows (operand x * gain and the row sums of
+  // squares, see RowScale), so that norm never runs as a kernel; plain path: residual only, then the norm kernel.
+  auto residual_proj = [&](int site, int prof, const void *A, const void *W, int K, const float *next_gain) -> int {
+    {
+      ProfScope ps(ctx, st, prof);
+      int rc2;
+      if constexpr (std::is_same<T, bf16>::value) {
+        if (mfma_path) {
+          EpiResidualNorm en{ws.x, d.d_model, next_gain, static_cast<bf16 *>(ws.h), ws.ss};
+          rc2 = launch_gemm<T>(ctx, st, site, Tq, d.d_model, K, A, W, en);
+          return rc2;
+        }
+      }
+      EpiResidual er{ws.x, d.d_model};
+      if ((rc2 = launch_gemm<T>(ctx, st, site, Tq, d.d_model, K, A, W, er))) return rc2;
+    }
+    return next_gain != nullptr ? norm(next_gain) : HSD_OK;
   };
+  const RowScale rs_none{nullptr, 0, 0.f, 0.f};
+  const RowScale rs_fused{mfma_path ? ws.ss : nullptr, d.d_model / 64, 1.0f / static_cast<float>(d.d_model), d.rms_eps};
 
-  int pending = 0;
-  if ((rc = norm(ctx->attn_norm[0], 0))) return rc;
+  if ((rc = norm(ctx->attn_norm[0]))) return rc;
   for (int l = 0; l < d.n_layers; ++l) {
     PagedKV kv{pool->k_pool, pool->v_pool, b->block_table, b->max_blocks_per_seq, pool->n_blocks, d.n_kv_heads, l};
-    EpiQKV<T> eq{d.n_q_heads, d.n_kv_heads, meta, kv, static_cast<T *>(ws.q)};
+    // layer 0 reads the operand the norm kernel normalised; later layers the one the previous down projection left
+    EpiQKV<T> eq{d.n_q_heads, d.n_kv_heads, meta, kv, static_cast<T *>(ws.q), l == 0 ? rs_none : rs_fused};
     {
       ProfScope ps(ctx, st, HSD_PROF_GEMM_QKV);
       if ((rc = launch_gemm<T>(ctx, st, kSiteQKV, Tq, qdim + 2 * kvdim, d.d_model, ws.h, ctx->wqkv[l], eq))) return rc;
@@ -484,20 +476,15 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
       ProfScope ps(ctx, st, HSD_PROF_ATTENTION);
       if ((rc = launch_attention<T>(ctx, st, b, meta, kv, ws, page_mode))) return rc;
     }
-    if ((rc = residual_proj(kSiteO, HSD_PROF_GEMM_O, ws.a, ctx->wo[l], qdim, ctx->k_chunks[0] ? ctx->k_chunks[0] : kChunksO, &pending))) return rc;
-    if ((rc = norm(ctx->ffn_norm[l], pending))) return rc;
-    EpiSwiGLU<T> es{static_cast<T *>(ws.u), d.d_ffn};
+    if ((rc = residual_proj(kSiteO, HSD_PROF_GEMM_O, ws.a, ctx->wo[l], qdim, ctx->ffn_norm[l]))) return rc;
+    EpiSwiGLU<T> es{static_cast<T *>(ws.u), d.d_ffn, rs_fused};
     {
       ProfScope ps(ctx, st, HSD_PROF_GEMM_GATE_UP);
       if ((rc = launch_gemm<T>(ctx, st, kSiteGateUp, Tq, d.d_ffn, d.d_model, ws.h, ctx->w_gate_up[l], es))) return rc;
     }
-    if ((rc = residual_proj(kSiteDown, HSD_PROF_GEMM_DOWN, ws.u, ctx->w_down[l], d.d_ffn,
-                            ctx->k_chunks[1] ? ctx->k_chunks[1] : kChunksDown, &pending)))
-      return rc;
     // the norm that follows: next layer's attention norm, or the final norm before the LM head (none for prefill)
     const float *next_gain = (l + 1 < d.n_layers) ? ctx->attn_norm[l + 1] : (with_head ? ctx->final_norm : nullptr);
-    if (next_gain != nullptr || pending > 0)
-      if ((rc = norm(next_gain, pending))) return rc;
+    if ((rc = residual_proj(kSiteDown, HSD_PROF_GEMM_DOWN, ws.u, ctx->w_down[l], d.d_ffn, next_gain))) return rc;
     if (ctx->sync_layers && hipStreamSynchronize(st) != hipSuccess) return HSD_EHIP;
   }
   if (!with_head) return HSD_OK;
@@ -513,7 +500,7 @@ int forward(hsd_ctx *ctx, hipStream_t st, const hsd_kv_pool *pool, const hsd_bat
   }
   const int n_tiles = lm_head_tiles<T>(ctx, Tq);
   EpiLMHead el{ws.lm_part, n_tiles, d.vocab, dump_slot, b->logits_dump, b->tokens, ws.row_end,
-               relaxed ? ws.want_logit : nullptr};
+               relaxed ? ws.want_logit : nullptr, rs_fused};
   {
     ProfScope ps(ctx, st, HSD_PROF_GEMM_LM_HEAD);
     if ((rc = launch_gemm<T>(ctx, st, kSiteLM, Tq, d.vocab, d.d_model, ws.h, ctx->lm_head, el))) return rc;
@@ -666,10 +653,9 @@ int hsd_create(const hsd_model_desc *desc, const hsd_weights *w, hsd_ctx **out) 
     return HSD_EHIP;
   }
   c->force_simple = false;
-  c->split_rows = split_row_limit(*desc);
-  // 256x256 8-wave tiles for the wide projections (gate/up, LM head), 64x128 tiles for QKV and O (more workgroups),
-  // 128x128 for the split-K down projection
-  const int defaults[5] = {5, 2, 8, 0, 8};
+  // 256x256 8-wave tiles for the wide projections (gate/up, LM head), 64x128 tiles for QKV, O and down (more
+  // workgroups)
+  const int defaults[5] = {5, 2, 8, 2, 8};
   for (int i = 0; i < 5; ++i) c->gemm_cfg[i] = defaults[i];
   *out = c;
   return HSD_OK;
@@ -680,15 +666,6 @@ int hsd_debug_set(hsd_ctx *c, int knob, int64_t value) {
   switch (knob) {
     case HSD_DEBUG_SYNC_LAYERS: c->sync_layers = value != 0; return HSD_OK;
     case HSD_DEBUG_FORCE_SIMPLE: c->force_simple = value != 0; return HSD_OK;
-    case HSD_DEBUG_SPLIT_ROWS:
-      if (value < 0) return HSD_EINVAL;
-      c->split_rows = value < split_row_limit(c->desc) ? value : split_row_limit(c->desc);
-      return HSD_OK;
-    case HSD_DEBUG_KCHUNKS_O:
-    case HSD_DEBUG_KCHUNKS_DOWN:
-      if (value < 0 || value > kMaxChunks) return HSD_EINVAL;
-      c->k_chunks[knob - HSD_DEBUG_KCHUNKS_O] = static_cast<int>(value);
-      return HSD_OK;
     case HSD_DEBUG_GEMM_CFG_QKV:
     case HSD_DEBUG_GEMM_CFG_O:
     case HSD_DEBUG_GEMM_CFG_GATE_UP:

@@ -141,7 +141,6 @@ __global__ void k_embed(int d, int vocab, const int32_t *__restrict__ tokens, co
 // RMSNorm: h[r,:] = x[r,:] * rsqrt(mean(x^2) + eps) * gain, fp32 math, output in the GEMM operand type.
 // One wave per row, 4 rows per 256-thread block; d is a multiple of 128 so every lane reads float4s.  The
 // first kNormCache float4 of a lane (rows up to 2048 wide) stay in registers between the two passes.
-// Both norm kernels share the helpers below, so they round identically.
 // ------------------------------------------------------------------------------------------------
 constexpr int kNormCache = 8;
 
@@ -190,44 +189,6 @@ __global__ void k_rmsnorm(int n_rows, int d, float eps, const float *__restrict_
     }
   }
   for (int c = lane + kWave * kNormCache; c < n4; c += kWave) ss += sumsq4(xr[c]);
-  norm_write_row<T>(xr, cache, n4, lane, ss, d, eps, gain, h + static_cast<size_t>(r) * d);
-}
-
-// ------------------------------------------------------------------------------------------------
-// Split-K reduction fused with the residual add and the following RMSNorm:
-//   x[r,:] = ((x[r,:] + part[0][r,:]) + part[1][r,:]) + ...   (the order in which a workgroup that walks the
-//                                                              chunks itself adds them to x)
-//   h[r,:]  = rmsnorm(x[r,:]) * gain                  (skipped when gain == nullptr)
-// One wave per row, 4 rows per block.
-// ------------------------------------------------------------------------------------------------
-template <typename T>
-__global__ void k_reduce_rmsnorm(int n_rows, int d, float eps, float *__restrict__ x, const float *__restrict__ part,
-                                 int n_splits, const float *__restrict__ gain, T *__restrict__ h) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int r = blockIdx.x * 4 + wave;
-  if (r >= n_rows) return;
-  floatx4 *xr = reinterpret_cast<floatx4 *>(x + static_cast<size_t>(r) * d);
-  const size_t split_stride = static_cast<size_t>(n_rows) * d / 4;
-  const floatx4 *pr = reinterpret_cast<const floatx4 *>(part) + static_cast<size_t>(r) * d / 4;
-  const int n4 = d >> 2;
-  auto reduce_at = [&](int c) {
-    floatx4 v = xr[c];
-    for (int k = 0; k < n_splits; ++k) v += pr[k * split_stride + c];
-    xr[c] = v;
-    return v;
-  };
-  floatx4 cache[kNormCache];
-  float ss = 0.f;
-#pragma unroll
-  for (int i = 0; i < kNormCache; ++i) {
-    const int c = lane + kWave * i;
-    if (c < n4) {
-      cache[i] = reduce_at(c);
-      ss += sumsq4(cache[i]);
-    }
-  }
-  for (int c = lane + kWave * kNormCache; c < n4; c += kWave) ss += sumsq4(reduce_at(c));
-  if (gain == nullptr) return;
   norm_write_row<T>(xr, cache, n4, lane, ss, d, eps, gain, h + static_cast<size_t>(r) * d);
 }
 

@@ -87,8 +87,8 @@ class Engine:
     def __init__(self, desc, weights: dict, n_blocks: int, n_slots: int, max_blocks_per_seq: int,
                  max_total_q: int, max_dump: int = 0, device: str = "cuda:0", attn_key_chunk: int = 0,
                  debug: Optional[dict] = None):
-        """debug: {"sync_layers" | "force_simple" | "split_rows" | "kchunks_o" | "kchunks_down": int,
-        "gemm_cfg": (qkv, o, gate_up, down, lm_head)} -> hsd_debug_set (experiments and cross-checks only)."""
+        """debug: {"sync_layers" | "force_simple": int, "gemm_cfg": (qkv, o, gate_up, down, lm_head)} ->
+        hsd_debug_set (experiments and cross-checks only)."""
         if not torch.cuda.is_available():
             raise RuntimeError("the HSD verification path needs a GPU (MI355X); there is no CPU fallback")
         self.dev = torch.device(device)
