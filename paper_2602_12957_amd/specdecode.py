@@ -77,7 +77,8 @@ class SpecDecoder:
         out: List[List[int]] = [[] for _ in range(n)]
         pend = [int(p) for p in pending]
         done = [False] * n
-        stats = dict(rounds=0, rows=0, accepted=0, plain_steps=0, seq_rounds=0)
+        stats = dict(rounds=0, rows=0, accepted=0, plain_steps=0, seq_rounds=0,
+                     per_seq=[[] for _ in range(n)])      # per sequence: (tree rows, accepted) of each of its rounds
         while not all(done):
             active = [i for i in range(n) if not done[i]]
             blocks, trees = [], []
@@ -109,6 +110,7 @@ class SpecDecoder:
                 pend[i] = int(bonus[j])
                 stats["accepted"] += int(alpha[j])
                 stats["seq_rounds"] += 1
+                stats["per_seq"][i].append((len(blocks[j]), int(alpha[j])))
                 if len(out[i]) >= n_tokens[i] or (eos is not None and eos in path + [int(bonus[j])]):
                     done[i] = True
             stats["rounds"] += 1
