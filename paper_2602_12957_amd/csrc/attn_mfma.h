@@ -50,43 +50,128 @@ constexpr size_t attn_smem_bytes(int qs) {
   return stages > merge ? stages : merge;
 }
 
-// What a workgroup needs to know about its query tile, resolved once per pass instead of by every workgroup of
-// every layer (a binary search and four dependent reads before the first K/V request could go out).
+// What a workgroup needs to know about its task -- one (query tile, kv head group) -- resolved once per pass instead
+// of by every workgroup of every layer (a binary search and four dependent reads before the first K/V request
+// could go out).
 struct __attribute__((aligned(32))) AttnTile {
-  int32_t seq;          // batch index of the sequence, -1 past the last tile
+  int32_t seq;          // batch index of the sequence, -1: no task (padding of the launch)
   int32_t tile_in_seq;  // index of the tile among the sequence's tiles
   int32_t slot;         // state row (seq_len / block_table row)
   int32_t S, base, Lq;  // cached length, first row and number of rows of the sequence's block
-  int32_t pad[2];
+  int32_t y;            // kv head * (head groups per kv head) + head group
+  int32_t pad;
 };
 
-// tiles[t] for t < max_tiles (the grid's upper bound of query tiles), with q_tile rows per tile.  One block of 1024
-// threads; s_cnt is turned into the exclusive prefix of the tile counts.
+constexpr int kAttnMaxGroups = 1024;   // task groups placed by the balancing pass (more: plain order)
+// Workgroups in the launch for `max_tiles` query tiles (an upper bound known on the host), `n_y` head groups and
+// groups of `sub_tiles` tiles: 8 lists of equal length with room for the unevenness the placement can leave.
+__host__ __device__ inline int attn_grid_size(int max_tiles, int n_y, int sub_tiles) {
+  return 8 * ((max_tiles * n_y + 7) / 8 + sub_tiles);
+}
+
+// Task table of an attention launch: tasks[i] is the task of workgroup i, for i < n_wg = attn_grid_size(...).
+//
+// Placement.  Workgroup i runs on XCD i % 8 (workgroups go to the 8 XCDs round robin), and each XCD has its own L2.
+// The tiles of one sequence and kv head read the same K/V, so they should meet in one L2: tasks are grouped by
+// (sequence, head group, run of `sub_tiles` consecutive tiles), every group goes to ONE XCD as a whole, and the
+// groups are dealt to the XCDs heaviest first, each to the XCD with the least work so far (work = 128-key stages a
+// task walks) among those whose list still has room, which keeps the 8 lists level.  Inside a group the tile with
+// the most keys comes first, and heavy groups come first in every list, so the long tasks of a ragged batch start
+// early instead of forming the tail.  List x's j-th task becomes workgroup 8 j + x; workgroups past the end of a
+// list find seq = -1.  Batches with more than kAttnMaxGroups groups are even enough by sheer number: they keep the
+// plain order (sequence by sequence, heaviest tile first).
+// The placement moves work between compute units and changes no result.  One block of 1024 threads.
 __global__ void __launch_bounds__(1024) k_attn_tiles(int n_seq, const int32_t *__restrict__ cu_q,
                                                      const int32_t *__restrict__ seq_slot, int n_slots,
-                                                     const int32_t *__restrict__ seq_len, int q_tile, int max_tiles,
-                                                     AttnTile *__restrict__ tiles) {
-  __shared__ int s_cnt[HSD_MAX_SEQ];
+                                                     const int32_t *__restrict__ seq_len, int q_tile, int n_y,
+                                                     int sub_tiles, int n_wg, AttnTile *__restrict__ tasks) {
+  __shared__ int s_cnt[HSD_MAX_SEQ];      // per sequence: groups (or tiles) before it, after the scan
   __shared__ int s_part[1024];
-  for (int s = threadIdx.x; s < n_seq; s += blockDim.x) s_cnt[s] = (cu_q[s + 1] - cu_q[s] + q_tile - 1) / q_tile;
-  __syncthreads();
-  const int total = block_exclusive_scan_4096(s_cnt, n_seq, s_part);
-  for (int t = threadIdx.x; t < max_tiles; t += blockDim.x) {
-    AttnTile d{-1, 0, 0, 0, 0, 0, {0, 0}};
-    if (t < total) {
-      int lo = 0, hi = n_seq - 1;   // last sequence whose first tile is <= t (every sequence has at least one row)
-      while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (s_cnt[mid] <= t) lo = mid; else hi = mid - 1;
-      }
-      d.seq = lo;
-      d.tile_in_seq = t - s_cnt[lo];
-      d.slot = slot_of(seq_slot, lo, n_slots);
-      d.S = seq_len[d.slot];
-      d.base = cu_q[lo];
-      d.Lq = cu_q[lo + 1] - d.base;
+  __shared__ int g_work[kAttnMaxGroups], g_key[kAttnMaxGroups], g_n[kAttnMaxGroups], g_order[kAttnMaxGroups];
+  __shared__ int g_bin[kAttnMaxGroups], g_pos[kAttnMaxGroups];
+  const int t = threadIdx.x;
+  const AttnTile none{-1, 0, 0, 0, 0, 0, 0, 0};
+  for (int i = t; i < n_wg; i += blockDim.x) tasks[i] = none;
+  for (int s = t; s < n_seq; s += blockDim.x) {
+    const int tiles = (cu_q[s + 1] - cu_q[s] + q_tile - 1) / q_tile;
+    s_cnt[s] = n_y * ((tiles + sub_tiles - 1) / sub_tiles);
+  }
+  __syncthreads();   // also: the padding above is complete before any task is written
+  const int n_groups = block_exclusive_scan_4096(s_cnt, n_seq, s_part);
+  if (n_groups > kAttnMaxGroups) {
+    __syncthreads();
+    for (int s = t; s < n_seq; s += blockDim.x) s_cnt[s] = (cu_q[s + 1] - cu_q[s] + q_tile - 1) / q_tile;
+    __syncthreads();
+    block_exclusive_scan_4096(s_cnt, n_seq, s_part);
+    for (int s = t; s < n_seq; s += blockDim.x) {
+      const int slot = slot_of(seq_slot, s, n_slots), base = cu_q[s], Lq = cu_q[s + 1] - base;
+      const int tiles = (Lq + q_tile - 1) / q_tile, S = seq_len[slot];
+      for (int k = 0; k < tiles; ++k)
+        for (int y = 0; y < n_y; ++y) {
+          const int i = (s_cnt[s] + k) * n_y + y;
+          if (i < n_wg) tasks[i] = AttnTile{s, tiles - 1 - k, slot, S, base, Lq, y, 0};
+        }
     }
-    tiles[t] = d;
+    return;
+  }
+  // group t of the batch: sequence s, head group y = local % n_y, tiles [t0, t1) with t0 = (local / n_y) * sub_tiles
+  int gs = 0, gy = 0, t0 = 0, t1 = 0, slot = 0, S = 0, base = 0, Lq = 0;
+  auto stages_of = [&](int tile) { return (S + min((tile + 1) * q_tile, Lq) + kAttnKeys - 1) / kAttnKeys; };
+  if (t < n_groups) {
+    int lo = 0, hi = n_seq - 1;   // last sequence whose first group is <= t (every sequence has at least one)
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (s_cnt[mid] <= t) lo = mid; else hi = mid - 1;
+    }
+    gs = lo;
+    const int local = t - s_cnt[gs];
+    gy = local % n_y;
+    slot = slot_of(seq_slot, gs, n_slots);
+    S = seq_len[slot];
+    base = cu_q[gs];
+    Lq = cu_q[gs + 1] - base;
+    t0 = (local / n_y) * sub_tiles;
+    t1 = min(t0 + sub_tiles, (Lq + q_tile - 1) / q_tile);
+    int w = 0;
+    for (int tile = t0; tile < t1; ++tile) w += stages_of(tile);
+    g_work[t] = w;
+    g_n[t] = t1 - t0;
+    g_key[t] = stages_of(t1 - 1);   // its heaviest task
+  }
+  __syncthreads();
+  if (t < n_groups) {   // rank: heaviest task first, then more work first, then lower index
+    int rank = 0;
+    const int k = g_key[t], w = g_work[t];
+    for (int o = 0; o < n_groups; ++o) {
+      const int ko = g_key[o], wo = g_work[o];
+      rank += (ko > k) || (ko == k && (wo > w || (wo == w && o < t)));
+    }
+    g_order[rank] = t;
+  }
+  __syncthreads();
+  if (t == 0) {
+    // the lists hold n_wg / 8 tasks each; the tasks number at most 8 * (n_wg / 8 - sub_tiles), so some list always
+    // has room for one more group of at most sub_tiles tasks
+    const int cap = n_wg / 8;
+    int load[8] = {0, 0, 0, 0, 0, 0, 0, 0}, count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int r = 0; r < n_groups; ++r) {
+      const int g = g_order[r];
+      int best = -1;
+      for (int x = 0; x < 8; ++x)
+        if (count[x] + g_n[g] <= cap && (best < 0 || load[x] < load[best])) best = x;
+      if (best < 0) best = 0;   // cannot happen (see above); the bound check at the write keeps it harmless
+      g_bin[g] = best;
+      g_pos[g] = count[best];
+      load[best] += g_work[g];
+      count[best] += g_n[g];
+    }
+  }
+  __syncthreads();
+  if (t < n_groups) {
+    for (int k = 0; k < t1 - t0; ++k) {   // heaviest tile first
+      const int i = 8 * (g_pos[t] + k) + g_bin[t];
+      if (i < n_wg) tasks[i] = AttnTile{gs, t1 - 1 - k, slot, S, base, Lq, gy, 0};
+    }
   }
 }
 
@@ -117,8 +202,7 @@ union Frag8 {
 // O^T) are folded through LDS at the end, always in the same order, so results do not depend on timing.
 // TREE selects the tree-ancestry mask (row_end = packed index one past each row's subtree) instead of the causal one.
 // SPLIT: grid z = key chunk (see AttnSplit); results go to the partial buffers instead of `out`.
-// grid: (upper bound of query tiles, n_kv_heads * ceil(group / G4), chunks), block 128*QS, dynamic LDS
-// attn_smem_bytes(QS).
+// grid: (attn_grid_size(...) tasks, 1, chunks), block 128*QS, dynamic LDS attn_smem_bytes(QS).
 template <int G4, int QS, bool TREE, bool SPLIT>
 __global__ void __launch_bounds__(128 * QS) k_attn_mfma(int n_q_heads, const AttnTile *__restrict__ tiles, PagedKV kv,
                                                         const bf16 *__restrict__ q, bf16 *__restrict__ out,
@@ -136,10 +220,10 @@ __global__ void __launch_bounds__(128 * QS) k_attn_mfma(int n_q_heads, const Att
   const ConstI32 td = (ConstI32)(reinterpret_cast<const int32_t *>(tiles + blockIdx.x));
   const int s = td[0];
   if (s < 0) return;  // uniform for the whole workgroup
-  const int tile_in_seq = td[1], slot = td[2], S = td[3], base = td[4], Lq = td[5];
+  const int tile_in_seq = td[1], slot = td[2], S = td[3], base = td[4], Lq = td[5], ty = td[6];
 
   const int group = n_q_heads / kv.n_kv_heads, hb = (group + G4 - 1) / G4;
-  const int kvh = blockIdx.y / hb, hgrp = blockIdx.y % hb;
+  const int kvh = ty / hb, hgrp = ty % hb;
   const int t = threadIdx.x, lane = t & 63, half = lane >> 5, qj = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wq = wave % QS, par = wave / QS;                       // query-set index, parity of the wave

@@ -95,7 +95,8 @@ Workspace carve(const hsd_model_desc &d, int64_t T, int64_t n_seq, void *base) {
   w.want_logit = reinterpret_cast<float *>(take(T * sizeof(float)));
   w.row_max = reinterpret_cast<float *>(take(T * sizeof(float)));
   w.dump_slot = reinterpret_cast<int32_t *>(take(T * sizeof(int32_t)));
-  w.attn_tiles = reinterpret_cast<AttnTile *>(take((T / 32 + n_seq) * sizeof(AttnTile)));   // 32 = smallest query tile
+  // the largest task table any attention launch over T rows can need (32-row tiles, one head group per kv head)
+  w.attn_tiles = reinterpret_cast<AttnTile *>(take(static_cast<size_t>(attn_grid_size(static_cast<int>(T / 32 + n_seq), d.n_q_heads, 8)) * sizeof(AttnTile)));
   w.rope_cs = reinterpret_cast<float2 *>(take(T * 32 * sizeof(float2)));
   w.lm_part = reinterpret_cast<Top2 *>(take(T * (d.vocab / 64) * sizeof(Top2)));
   w.ss = reinterpret_cast<float *>(take(T * (d.d_model / 64) * sizeof(float)));
@@ -360,12 +361,15 @@ int launch_attention(const hsd_ctx *ctx, hipStream_t st, const hsd_batch *b, con
       const int g4 = group >= 4 ? 4 : group, qs = page_mode ? 8 : 4;
       const int q_tile = 32 * (qs / g4);
       const int max_tiles = b->total_q / q_tile + b->n_seq;
-      const dim3 grid(max_tiles, d.n_kv_heads * ((group + g4 - 1) / g4));
+      const int n_y = d.n_kv_heads * ((group + g4 - 1) / g4);
+      const int sub_tiles = 256 / q_tile;   // tiles of one sequence and head group that share an XCD: 256 rows
+      const int n_wg = attn_grid_size(max_tiles, n_y, sub_tiles);
+      const dim3 grid(n_wg, 1);
       const bf16 *q = static_cast<const bf16 *>(ws.q);
       bf16 *o = static_cast<bf16 *>(ws.a);
-      if (kv.layer == 0) {  // the tile map depends on the batch only: built once per pass
+      if (kv.layer == 0) {  // the task table depends on the batch only: built once per pass
         hipLaunchKernelGGL(k_attn_tiles, dim3(1), dim3(1024), 0, st, b->n_seq, b->cu_q, b->seq_slot, b->n_slots,
-                           b->seq_len, q_tile, max_tiles, ws.attn_tiles);
+                           b->seq_len, q_tile, n_y, sub_tiles, n_wg, ws.attn_tiles);
         HSD_LAUNCH_CHECK();
       }
       // Key split (desc.attn_key_chunk > 0): one workgroup per (query tile, chunk of keys); no sequence can hold
