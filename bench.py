@@ -118,7 +118,7 @@ def run_config(cfg_index, args, weights_cache):
     prefix_len = [sp.n_visual + max(sp.n_prompt - 1, 0) for sp in specs]
     # workspace rows: one verification block, or (configs[1]) all prefixes at once for the prefill figure
     ws_rows = max(total_q, sum(prefix_len) if cfg_index == 1 else 8192)
-    steps = args.steps if cfg_index == 1 else max(3, min(args.steps, args.other_steps))
+    steps = args.steps if cfg_index in (1, args.profile_config) else max(3, min(args.steps, args.other_steps))
     debug = None
     if args.debug_knobs:       # experiments only: "name=value,..." with gemm_cfg=q:o:g:d:l
         debug = {}
@@ -388,6 +388,9 @@ def main():
                          "the rule the headline metric is defined on")
     ap.add_argument("--attn-key-chunk", type=int, default=0,
                     help="attention key split (hsd_model_desc.attn_key_chunk): keys per chunk, 0 = unsplit")
+    ap.add_argument("--profile-config", type=int, default=0, choices=[0, 1, 2, 3, 4],
+                    help="profiling aid: run round 1 of this one configuration only (set-up, warm-up, timed steps, "
+                         "per-kernel extra steps) and print its result object instead of the headline line")
     ap.add_argument("--debug-knobs", type=str, default="",
                     help="experiments only: hsd_debug_set knobs, e.g. kchunks_down=1,gemm_cfg=7:9:8:9:8")
     ap.add_argument("--breakdown", action="store_true",
@@ -400,6 +403,13 @@ def main():
     import torch
     others = [int(c) for c in args.configs.split(",") if c.strip() and int(c) != 1]
     weights_cache = {}
+    if args.profile_config:
+        res, st = run_config(args.profile_config, args, weights_cache)
+        if args.calibration_copy_mb > 0:
+            headline_extras({}, dict(st, eng=st["eng"]), argparse.Namespace(**dict(vars(args), random_target=True)))
+        st["eng"].close()
+        print(json.dumps(res))
+        return
     res1, st = run_config(1, args, weights_cache)
     out = {
         "metric": "verified_draft_tokens_per_s", "value": res1["verified_tokens_per_s"], "unit": "tokens/s",

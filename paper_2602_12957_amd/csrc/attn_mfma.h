@@ -87,7 +87,8 @@ __global__ void __launch_bounds__(1024) k_attn_tiles(int n_seq, const int32_t *_
                                                      int sub_tiles, int n_wg, AttnTile *__restrict__ tasks) {
   __shared__ int s_cnt[HSD_MAX_SEQ];      // per sequence: groups (or tiles) before it, after the scan
   __shared__ int s_part[1024];
-  __shared__ int g_work[kAttnMaxGroups], g_key[kAttnMaxGroups], g_n[kAttnMaxGroups], g_order[kAttnMaxGroups];
+  __shared__ int g_work[kAttnMaxGroups], g_key[kAttnMaxGroups], g_n[kAttnMaxGroups];
+  __shared__ int o_group[kAttnMaxGroups], o_work[kAttnMaxGroups], o_n[kAttnMaxGroups];   // the groups in dealing order
   __shared__ int g_bin[kAttnMaxGroups], g_pos[kAttnMaxGroups];
   const int t = threadIdx.x;
   const AttnTile none{-1, 0, 0, 0, 0, 0, 0, 0};
@@ -146,24 +147,45 @@ __global__ void __launch_bounds__(1024) k_attn_tiles(int n_seq, const int32_t *_
       const int ko = g_key[o], wo = g_work[o];
       rank += (ko > k) || (ko == k && (wo > w || (wo == w && o < t)));
     }
-    g_order[rank] = t;
+    o_group[rank] = t;
+    o_work[rank] = w;
+    o_n[rank] = g_n[t];
   }
   __syncthreads();
-  if (t == 0) {
-    // the lists hold n_wg / 8 tasks each; the tasks number at most 8 * (n_wg / 8 - sub_tiles), so some list always
-    // has room for one more group of at most sub_tiles tasks
+  if (t < kWave) {
+    // One wave deals the groups; lane x < 8 keeps list x's work and length in registers.  The lists hold n_wg / 8
+    // tasks each and the tasks number at most 8 * (n_wg / 8 - sub_tiles), so some list always has room for one
+    // more group of at most sub_tiles tasks.
     const int cap = n_wg / 8;
-    int load[8] = {0, 0, 0, 0, 0, 0, 0, 0}, count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int r = 0; r < n_groups; ++r) {
-      const int g = g_order[r];
-      int best = -1;
-      for (int x = 0; x < 8; ++x)
-        if (count[x] + g_n[g] <= cap && (best < 0 || load[x] < load[best])) best = x;
-      if (best < 0) best = 0;   // cannot happen (see above); the bound check at the write keeps it harmless
-      g_bin[g] = best;
-      g_pos[g] = count[best];
-      load[best] += g_work[g];
-      count[best] += g_n[g];
+    int load = 0, count = 0;
+    for (int r0 = 0; r0 < n_groups; r0 += kWave) {
+      // 64 groups at a time: lane l fetches group r0 + l once, the dealing loop then runs out of registers
+      const bool valid = r0 + t < n_groups;
+      const int n_v = valid ? o_n[r0 + t] : 0, w_v = valid ? o_work[r0 + t] : 0, g_v = valid ? o_group[r0 + t] : 0;
+      int my_bin = 0, my_pos = 0;
+      const int m = min(kWave, n_groups - r0);
+      for (int j = 0; j < m; ++j) {
+        const int n = __builtin_amdgcn_readlane(n_v, j), w = __builtin_amdgcn_readlane(w_v, j);
+        // least work among the lists with room; equal work: the lower list (work stays far below 2^27)
+        int key = (t < 8 && count + n <= cap) ? ((load << 3) | t) : 0x7fffffff;
+        key = min(key, __builtin_amdgcn_update_dpp(0x7fffffff, key, 0xB1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+        key = min(key, __builtin_amdgcn_update_dpp(0x7fffffff, key, 0x4E, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+        key = min(key, __builtin_amdgcn_update_dpp(0x7fffffff, key, 0x141, 0xf, 0xf, false));   // row_half_mirror
+        const int best = __builtin_amdgcn_readfirstlane(key) & 7;
+        const int pos = __builtin_amdgcn_readlane(count, best);
+        if (t == j) {
+          my_bin = best;
+          my_pos = pos;
+        }
+        if (t == best) {
+          load += w;
+          count += n;
+        }
+      }
+      if (valid) {
+        g_bin[g_v] = my_bin;
+        g_pos[g_v] = my_pos;
+      }
     }
   }
   __syncthreads();
