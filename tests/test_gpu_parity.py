@@ -224,6 +224,36 @@ def test_random_shapes_against_oracle():
         run_rounds_parity(desc, weights, seed, specs, drafts, mode=mode, attn_key_chunk=chunk or None)
 
 
+def test_many_sequences_take_the_plain_task_order():
+    """More sequences than the attention task table places group by group (over 1024 task groups: here 300 sequences
+    x 4 kv heads) fall back to the plain task order; one pass of such a batch, ragged, against the oracle."""
+    desc = W.ModelDesc(n_layers=2, d_model=256, n_q_heads=8, n_kv_heads=4, head_dim=64, d_ffn=256, vocab=512, dtype="bf16")
+    seed = 90
+    weights = W.make_weights(desc, seed)
+    rng = np.random.default_rng(90)
+    specs = [SequenceSpec(i, int(rng.integers(0, 40)), int(rng.integers(1, 4)), int(rng.integers(1, 70)), 0.0)
+             for i in range(300)]
+    drafts = [rng.integers(0, desc.vocab, size=sp.draft_len).astype(np.int32) for sp in specs]
+    total_q = sum(len(d) + 1 for d in drafts)
+    eng = make_engine(desc, weights, specs, max_total_q=total_q, max_dump=total_q)
+    ora = _oracle_state(desc, weights, seed, specs)
+    pend = _gpu_prefill(eng, desc, seed, specs)
+    blocks = [np.concatenate([[p], d]).astype(np.int32) for p, d in zip(pend, drafts)]
+    out = eng.verify(list(range(300)), blocks, "region", dump_rows=np.arange(total_q))
+    g_alpha, g_bonus, status = eng.read_acceptance(300)
+    assert status == 0
+    g_logits = out.logits.cpu().numpy()
+    worst = 0.0
+    for i, sp in enumerate(specs):
+        alpha, bonus, u_hat, logits = O.verify_block(desc, weights, ora[i][0], ora[i][1], drafts[i])
+        lo, hi = out.cu_q[i], out.cu_q[i + 1]
+        worst = max(worst, float(np.abs(g_logits[lo:hi] - logits).max()))
+        if np.all(O.top2_margin(logits)[:alpha + 1] > MARGIN_GATE):
+            assert (g_alpha[i], g_bonus[i]) == (alpha, bonus), i
+    assert worst <= TOL["bf16"], worst
+    eng.close()
+
+
 def test_prefill_takes_device_resident_embeddings():
     """Visual embedding rows handed over as device tensors (what a vision encoder leaves behind) give the same cache
     as host arrays uploaded chunk by chunk, also when the prefill runs in several passes."""
