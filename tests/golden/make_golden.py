@@ -12,7 +12,7 @@ For every sequence of a configuration it stores, as JSON:
     small probe (the tests size their floating-point bars for deep bf16 models from its RMS);
     "noise_floor": the deviation between two rounded evaluations that differ only in summation precision;
   * for a few rows of rounds 1-3 and of every fourth round after them, the logits at a seeded sample of
-    vocabulary columns plus each row's top-8 (value, index) pairs, for the element-wise logit comparison.
+    vocabulary columns (256 of them in rounds 1-3, 32 later) plus each row's top-8 (value, index) pairs, for the element-wise logit comparison.
 
 Every stored value comes from the oracle in its plain form (act_dtype=None: fp64, nothing rounded).
 
@@ -111,10 +111,12 @@ def one_sequence(args):
         rec = {"offset": committed, "k": int(len(rest)), "alpha": int(alpha), "bonus": int(bonus),
                "u_hat": u_hat.tolist(), "margin": [float(f"{m:.6g}") for m in margin],
                "top4_idx": top4.tolist(),
-               "top4_val": [[float(f"{x:.7g}") for x in row] for row in np.take_along_axis(logits, top4, axis=1)]}
+               "top4_val": [[float(f"{x:.6g}") for x in row] for row in np.take_along_axis(logits, top4, axis=1)]}
         r = len(rounds)
         if r < 3 or r % 4 == 0:
             rows, cols = sample_positions(seed, cfg_index, sp.seq_id, logits.shape[0], desc.vocab, r)
+            if r >= 3:
+                cols = cols[::8]          # later rounds: every eighth of the drawn columns keeps the files small
             top_idx = np.argsort(-logits[rows], axis=1)[:, :8]
             rec["logit_samples"] = {
                 "rows": rows.tolist(), "cols": cols.tolist(),
