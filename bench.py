@@ -31,7 +31,7 @@ PEAK_HBM_GBPS = 8000.0
 # from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE) scaled by what the same counters read for a plain
 # 2 GiB device copy; the runs and the scaling are recorded in profiles/bench_cfg1_region_verify_hbm_traffic.md.
 # The counters cannot be read from inside this script; None for kernels not profiled that way.
-MEASURED_TRAFFIC_BYTES = {(1, "gate_up"): 62_541_824}
+MEASURED_TRAFFIC_BYTES = {(1, "gate_up"): 63_512_576}
 
 WORKLOAD_TEXT = {
     1: "configs[1] region-level verify, round 1: 16 regions x (1055 cached + pending + draft U[16,256]), "

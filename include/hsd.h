@@ -187,7 +187,7 @@ int hsd_verify_region_batch(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool,
  * hsd_verify_region_batch; the workspace is a fixed device array inside the library (hsd_noalloc_scratch_bytes(),
  * 16 MiB, held by every GPU the library runs on until the process ends).  Calls no allocating routine.
  * Returns HSD_ERANGE when hsd_workspace_bytes(desc, batch->total_q, batch->n_seq) exceeds that size (for the
- * 24-layer d1024 model: up to about 400 rows per call).  All calls on one GPU share the array (whatever context they
+ * 24-layer d1024 model: up to about 670 rows per call).  All calls on one GPU share the array (whatever context they
  * use): calls that overlap in time on one GPU race; calls on one stream, or ordered by events, are safe.  Nothing in
  * the array needs to start at zero and nothing is kept between calls. */
 int hsd_verify_region_batch_noalloc(hsd_ctx *ctx, void *stream, const hsd_kv_pool *pool, const hsd_batch *batch);
