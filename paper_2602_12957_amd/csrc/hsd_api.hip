@@ -18,6 +18,7 @@
 #include "gemm_mfma.h"
 #include "gemm_mfma8.h"
 #include "gemm_mfma_ws.h"
+#include "gemm_mfma_d.h"
 #include "gemm_simple.h"
 #include "misc_kernels.h"
 
@@ -212,6 +213,22 @@ int launch_gemm_mfma_ws(hipStream_t st, int M, int N, int K, const void *A, cons
   return HSD_OK;
 }
 
+template <typename Cfg, typename Epi>
+int launch_gemm_mfma_d(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi) {
+  constexpr int MODE = GemmModeOf<Epi>::value;
+  auto kern = k_gemm_mfma_d<Cfg, MODE, Epi>;
+  constexpr int smem = Cfg::kSmemBytes + kRowScaleBytes;
+  static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (attr_rc != hipSuccess) return HSD_EHIP;
+  int tiles_act, tiles_w;
+  gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
+  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(Cfg::kThreadsD), smem, st, M, N, K, static_cast<const bf16 *>(A),
+                     static_cast<const bf16 *>(W), epi);
+  HSD_LAUNCH_CHECK();
+  return HSD_OK;
+}
+
 // Tile configurations of the MFMA GEMM (hsd_debug_set selects one for experiments; default per call site).
 using GemmCfg0 = GemmCfg<128, 128, 64, 2, 2>;
 using GemmCfg1 = GemmCfg<256, 128, 64, 2, 2>;
@@ -221,7 +238,9 @@ using GemmCfg2 = GemmCfg<64, 128, 64, 2, 2>;    // small tiles for narrow projec
 using GemmCfg3 = GemmCfg<128, 64, 64, 2, 1>;
 using GemmCfg5 = GemmCfg<128, 128, 64, 4, 2>;   // 8 waves, wave tile 32x64
 // configurations 7 and 9 = k_gemm_mfma_ws (128x128 / 64x128 tile, four multiplying and four moving waves),
-// 8 = k_gemm_mfma8
+// 8 = k_gemm_mfma8, 10 and 11 = k_gemm_mfma_d (64x128 / 128x128 tile, a requesting wave and LDS-direct loads)
+using GemmCfgD64 = GemmCfgD<64, 128, 5>;
+using GemmCfgD128 = GemmCfgD<128, 128, 4>;
 
 
 // Tile configuration actually used at a call site for a given problem (the launch and everything sized from the
@@ -230,15 +249,23 @@ template <typename T>
 int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_chunks, bool split) {
   if (!std::is_same<T, bf16>::value || ctx->force_simple || K % 64 != 0) return -1;
   int cfg = ctx->gemm_cfg[site];
-  if (cfg < 0 || cfg > 9) cfg = 0;
+  if (cfg < 0 || cfg > 11) cfg = 0;
   // The tile shape never changes a result bit (every output element sums its K slices in the same order), so it
   // may follow the row count and the path stays batch-invariant.  A kernel's time is set by one workgroup's walk
   // over K plus fixed costs as long as the launch fits the chip in one round, so fewer rows take smaller tiles: more
   // workgroups, each with less arithmetic per K slice (measured per site on the 24-layer model at 16 to 1856 rows).
   if (!ctx->gemm_cfg_forced) {
-    // 9 / 7: 64x128 / 128x128 tiles with separate operand-moving waves
+    // 9 / 7: 64x128 / 128x128 tiles with four operand-moving waves; 10: the 64x128 tile fed by a requesting wave
+    // (k_gemm_mfma_d).  Measured with operands that come from HBM, as they do inside a pass (24 layers of weights
+    // do not stay in any cache): the requesting-wave kernel wins up to ~512 rows (16 rows, K = 4096: 19.5 us against
+    // 23.7; 512 rows: 20.7 against 25.4) and loses from ~1 k to ~2 k rows (1856 rows: 35.8 against 32.0), although
+    // it wins there too when the operands are cache resident (25.7 against 28.3).
+    // At ~4 k rows the 128x128 tile of the same kernel (11) yields one workgroup per compute unit on the square
+    // projections and wins there (4096 x 1024, K = 4096: 47.3 us against 56.5).
     if (site == kSiteLM) cfg = M <= 128 ? 0 : cfg;
-    else if (M <= 64) cfg = 9;                                         // token-by-token decoding: one row tile
+    else if (M <= 64) cfg = 10;                                        // token-by-token decoding: one row tile
+    else if (site != kSiteGateUp && M <= 512) cfg = 10;
+    else if ((site == kSiteO || site == kSiteDown) && M >= 3072) cfg = 11;
     else if (site == kSiteQKV) cfg = M <= 1024 ? 9 : 7;
     else if (site == kSiteO || site == kSiteDown) cfg = 9;   // down walks all of K in one workgroup: small tiles,
                                                              // so that a pass over ~2 k rows still fills the chip
@@ -255,6 +282,11 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_
   }
   // the two-role kernels: not for the swapped LM-head mode, K chunks only as split-K
   if ((cfg == 7 || cfg == 9) && (site == kSiteLM || (k_chunks > 1 && !split))) cfg = cfg == 7 ? 0 : 2;
+  // the LDS-direct kernels: no K chunks, not the swapped mode, 32-bit operand offsets
+  if ((cfg == 10 || cfg == 11) &&
+      (site == kSiteLM || k_chunks > 1 || static_cast<int64_t>(M) * K * 2 >= (int64_t{1} << 31) ||
+       (site == kSiteGateUp ? 2 : 1) * static_cast<int64_t>(N) * K * 2 >= (int64_t{1} << 31)))
+    cfg = cfg == 11 ? 0 : 2;
   // the 8-wave kernel walks its K chunks itself (no split-K form), each an even number (>= 4) of 64-wide slices
   const int k_len = K / k_chunks;
   if (cfg == 8 && (split || k_len % 128 != 0 || k_len < 256)) cfg = 0;
@@ -292,6 +324,14 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
           return launch_gemm_mfma_ws<GemmCfgWS64>(st, M, N, K, A, W, epi, k_chunks, split);
         break;
       case 8: return launch_gemm_mfma8(st, M, N, K, A, W, epi, k_chunks);
+      case 10:
+        if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
+          return launch_gemm_mfma_d<GemmCfgD64>(st, M, N, K, A, W, epi);
+        break;
+      case 11:
+        if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
+          return launch_gemm_mfma_d<GemmCfgD128>(st, M, N, K, A, W, epi);
+        break;
       default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi, k_chunks, split);
     }
   }
@@ -675,7 +715,7 @@ int hsd_debug_set(hsd_ctx *c, int knob, int64_t value) {
     case HSD_DEBUG_GEMM_CFG_GATE_UP:
     case HSD_DEBUG_GEMM_CFG_DOWN:
     case HSD_DEBUG_GEMM_CFG_LM_HEAD:
-      if (value < 0 || value > 9) return HSD_EINVAL;
+      if (value < 0 || value > 11) return HSD_EINVAL;
       c->gemm_cfg[knob - HSD_DEBUG_GEMM_CFG_QKV] = static_cast<int>(value);
       c->gemm_cfg_forced = true;
       return HSD_OK;
