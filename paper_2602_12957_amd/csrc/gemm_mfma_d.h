@@ -50,11 +50,13 @@ __device__ __forceinline__ void lds_load16(__amdgpu_buffer_rsrc_t rs, LdsBytePtr
 // s_waitcnt vmcnt(N) with the other counters left alone (N < 64)
 #define HSD_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
 
-// grid: 1-D, tiles_act * tiles_w workgroups of 320 threads, Cfg::kSmemBytes + kRowScaleBytes dynamic LDS.
+// grid: 1-D, tiles_act * tiles_w workgroups of 320 threads, Cfg::kSmemBytes + kRowScaleBytes dynamic LDS; the tiles
+// cover rows m_base .. M-1 (a caller that gave the rows before m_base to another kernel passes their count, a
+// multiple of the tile height; otherwise 0).
 // K must be a multiple of 64; both matrices below 2 GiB (32-bit buffer offsets).
 // Every wave executes exactly K/64 + 1 workgroup barriers, whichever role it has.
 template <typename Cfg, int MODE, typename Epi>
-__global__ void __launch_bounds__(320) k_gemm_mfma_d(int M, int N, int K, const bf16 *__restrict__ A,
+__global__ void __launch_bounds__(320) k_gemm_mfma_d(int M, int N, int K, int m_base, const bf16 *__restrict__ A,
                                                      const bf16 *__restrict__ W, Epi epi) {
   static_assert(MODE == kModeNormal || MODE == kModeDual, "normal or dual mode");
   constexpr int BP = Cfg::BP, BQ = Cfg::BQ, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN, S = Cfg::kStages;
@@ -64,9 +66,9 @@ __global__ void __launch_bounds__(320) k_gemm_mfma_d(int M, int N, int K, const 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   int tiles_act, tiles_w, ta, tw;
-  gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
-  gemm_tile_of(blockIdx.x, M, (MODE == kModeDual) ? 2 * N : N, tiles_act, tiles_w, ta, tw);
-  const int m0 = ta * BP, n0 = tw * ((MODE == kModeDual) ? BQ / 2 : BQ);
+  gemm_tiles<Cfg, MODE>(M - m_base, N, tiles_act, tiles_w);
+  gemm_tile_of(blockIdx.x, M - m_base, (MODE == kModeDual) ? 2 * N : N, tiles_act, tiles_w, ta, tw);
+  const int m0 = m_base + ta * BP, n0 = tw * ((MODE == kModeDual) ? BQ / 2 : BQ);
   const int nk = K / BK;
 
   if (wave == 4) {

@@ -214,7 +214,7 @@ int launch_gemm_mfma_ws(hipStream_t st, int M, int N, int K, const void *A, cons
 }
 
 template <typename Cfg, typename Epi>
-int launch_gemm_mfma_d(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi) {
+int launch_gemm_mfma_d(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int m_base = 0) {
   constexpr int MODE = GemmModeOf<Epi>::value;
   auto kern = k_gemm_mfma_d<Cfg, MODE, Epi>;
   constexpr int smem = Cfg::kSmemBytes + kRowScaleBytes;
@@ -222,9 +222,9 @@ int launch_gemm_mfma_d(hipStream_t st, int M, int N, int K, const void *A, const
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (attr_rc != hipSuccess) return HSD_EHIP;
   int tiles_act, tiles_w;
-  gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
-  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(Cfg::kThreadsD), smem, st, M, N, K, static_cast<const bf16 *>(A),
-                     static_cast<const bf16 *>(W), epi);
+  gemm_tiles<Cfg, MODE>(M - m_base, N, tiles_act, tiles_w);
+  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(Cfg::kThreadsD), smem, st, M, N, K, m_base,
+                     static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), epi);
   HSD_LAUNCH_CHECK();
   return HSD_OK;
 }
@@ -307,7 +307,29 @@ template <typename T, typename Epi>
 int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int K, const void *A, const void *W,
                 const Epi &epi, int k_chunks = 1, bool split = false) {
   if constexpr (std::is_same<T, bf16>::value) {
-    switch (effective_gemm_cfg<T>(ctx, site, M, N, K, k_chunks, split)) {
+    const int cfg = effective_gemm_cfg<T>(ctx, site, M, N, K, k_chunks, split);
+    if constexpr (GemmModeOf<Epi>::value != kModeSwapLM) {
+      // A last row tile of the 256-row kernels that holds only a few rows costs a whole tile, and when the tile count
+      // is just above a multiple of the number of compute units it costs a whole extra round over the chip (4 pages
+      // of 8193 rows: 129 x 4 tiles of the down projection = 2.02 rounds).  Then the few rows go to the small-tile
+      // kernel in a launch of their own (rows are independent in every epilogue).
+      const int rem = M % 256;
+      if ((cfg == 8 || cfg == 6) && !ctx->gemm_cfg_forced && k_chunks == 1 && rem > 0 && rem <= 64) {
+        const int64_t cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
+        const int64_t w_cols = site == kSiteGateUp ? 2 * static_cast<int64_t>(N) : N;
+        const int64_t tiles_w = cfg == 8 ? (w_cols + 255) / 256 : (w_cols + 127) / 128;
+        const int64_t full = M / 256;
+        if ((full * tiles_w + cu - 1) / cu < ((full + 1) * tiles_w + cu - 1) / cu &&
+            static_cast<int64_t>(M) * K * 2 < (int64_t{1} << 31) && w_cols * K * 2 < (int64_t{1} << 31)) {
+          const int m_main = M - rem;
+          const int rc = cfg == 8 ? launch_gemm_mfma8(st, m_main, N, K, A, W, epi, 1)
+                                  : launch_gemm_mfma<GemmCfg6>(st, m_main, N, K, A, W, epi, 1, false);
+          if (rc != HSD_OK) return rc;
+          return launch_gemm_mfma_d<GemmCfgD64>(st, M, N, K, A, W, epi, m_main);
+        }
+      }
+    }
+    switch (cfg) {
       case -1: break;
       case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi, k_chunks, split);
       case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi, k_chunks, split);
