@@ -364,6 +364,74 @@ def headline_extras(out, st, args):
     del dev_embs
 
 
+def hw_probe(yardstick: bool):
+    """What this chip sustains, measured with the library's probe kernels (hsd_probe_launch): the matrix pipes with
+    every compute unit busy and with a few, a compute unit's load path from L2, its LDS.  With `yardstick` also the
+    vendor library's plain bf16 GEMM (torch.matmul) on the projection shapes of configurations 1 and 3, operands
+    rotated through copies so that they come from HBM as they do inside a pass."""
+    import torch
+    from paper_2602_12957_amd import binding as B
+    dev = torch.device("cuda:0")
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    scratch = torch.zeros(16 << 20, dtype=torch.uint8, device=dev)      # 8 regions of 2 MiB: L2 resident
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def timed(kind, n_wg, iters, arg=0):
+        B.hsd_probe_launch(stream, kind, n_wg, max(1, iters // 50), arg, scratch.data_ptr(), scratch.numel())
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.hsd_probe_launch(stream, kind, n_wg, iters, arg, scratch.data_ptr(), scratch.numel())
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3
+
+    out = {"probe": "hardware", "compute_units": n_cu, "peak_bf16_tflops_datasheet": PEAK_BF16_TFLOPS}
+    mf = {}
+    for n_wg in (8, n_cu // 4, n_cu):
+        iters = 20000
+        dt = timed(B.HSD_PROBE_MFMA, n_wg, iters)
+        ns = dt * 1e9 / (iters * 16)                   # per MFMA and SIMD (one wave per SIMD)
+        mf[str(n_wg)] = {"tflops": round(n_wg * 4 * iters * 16 * 32768 / dt / 1e12, 1), "ns_per_mfma": round(ns, 2),
+                         "clock_ghz_at_32_cycles": round(32 / ns, 3)}
+    out["mfma_32x32x16_bf16_by_busy_units"] = mf
+    ld = {}
+    for name, kind in (("to_registers", B.HSD_PROBE_LOAD_REG), ("to_lds", B.HSD_PROBE_LOAD_LDS)):
+        iters = 2000
+        dt = timed(kind, n_cu, iters)
+        ld[name] = {"bytes_per_ns_per_cu": round(iters * 32768 / (dt * 1e9), 1),
+                    "tb_per_s_chip": round(n_cu * iters * 32768 / dt / 1e12, 2)}
+    out["load_path_from_l2"] = ld
+    lds = {}
+    for waves in (4, 8, 16):
+        iters = 4000
+        dt = timed(B.HSD_PROBE_LDS_READ, n_cu, iters, waves)
+        lds[str(waves)] = round(iters * 8192 * waves / (dt * 1e9), 1)
+    out["lds_read_b128_bytes_per_ns_per_cu_by_waves"] = lds
+    if yardstick:
+        ys = {}
+        shapes = [("cfg1 gate/up", 1856, 8192, 1024), ("cfg1 down", 1856, 1024, 4096), ("cfg1 qkv", 1856, 1536, 1024),
+                  ("cfg1 o", 1856, 1024, 1024), ("cfg1 lm_head", 1856, 32768, 1024), ("cfg3 gate/up", 32772, 8192, 1024),
+                  ("cfg3 down", 32772, 1024, 4096), ("cfg3 lm_head", 32772, 32768, 1024), ("square 8192", 8192, 8192, 8192)]
+        for name, M, N, K in shapes:
+            nb = max(1, min(16, int(600e6 // ((M * K + N * K) * 2))))
+            A = [torch.randn(M, K, device=dev, dtype=torch.bfloat16) for _ in range(nb)]
+            Wt = [torch.randn(N, K, device=dev, dtype=torch.bfloat16) for _ in range(nb)]
+            o = torch.empty(M, N, device=dev, dtype=torch.bfloat16)
+            for i in range(3):
+                torch.matmul(A[i % nb], Wt[i % nb].t(), out=o)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(20):
+                torch.matmul(A[i % nb], Wt[i % nb].t(), out=o)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 20
+            ys[name] = {"M": M, "N": N, "K": K, "us": round(us, 1), "tflops": round(2.0 * M * N * K / us * 1e-6, 0)}
+            del A, Wt, o
+        out["vendor_gemm_yardstick"] = ys
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -395,12 +463,20 @@ def main():
                     help="experiments only: hsd_debug_set knobs, e.g. kchunks_down=1,gemm_cfg=7:9:8:9:8")
     ap.add_argument("--breakdown", action="store_true",
                     help="after the timed region, time every kernel class in turn (extra steps) and report avg us per launch")
+    ap.add_argument("--hw-probe", action="store_true",
+                    help="instead of the benchmark: run the library's hardware probes (sustained MFMA rate, load path, "
+                         "LDS) and print their JSON line")
+    ap.add_argument("--yardstick", action="store_true",
+                    help="with --hw-probe: also time the vendor library's plain GEMM on the projection shapes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
+    if args.hw_probe:
+        hw_probe(args.yardstick)
+        return
     others = [int(c) for c in args.configs.split(",") if c.strip() and int(c) != 1]
     weights_cache = {}
     if args.profile_config:

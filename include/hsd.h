@@ -256,6 +256,24 @@ enum {
 };
 int hsd_debug_set(hsd_ctx *ctx, int knob, int64_t value);
 
+/* Hardware probes (measurement helpers, not a step of the method): launch one of four small kernels that exercise a
+ * single resource of the chip, so that a caller can time it and state what the chip sustains -- the yardsticks the
+ * GEMM and attention rooflines are read against.  The call only enqueues on `stream` (device pointer/handle as for
+ * the verify calls) and never waits; the caller brackets it with events.
+ *   HSD_PROBE_MFMA      `n_workgroups` x 4 waves issue 16 bf16 32x32x16 MFMAs per wave and iteration, no memory
+ *                       traffic: 16 * 32768 flop per wave and iteration
+ *   HSD_PROBE_LOAD_REG  `n_workgroups` x 256 threads stream an L2-resident region with 16-byte loads into registers:
+ *                       32768 bytes per workgroup and iteration
+ *   HSD_PROBE_LOAD_LDS  the same with loads that write LDS directly
+ *   HSD_PROBE_LDS_READ  `n_workgroups` x `arg` waves (1..16) read LDS with conflict-free 128-bit reads: 8192 bytes
+ *                       per wave and iteration
+ * `scratch` (device, `scratch_bytes`): at least 4 bytes; the two load probes read it as eight regions of
+ * scratch_bytes / 8 bytes (one per XCD), each a multiple of 32 KiB, at least 32 KiB and below 2 GiB; contents are
+ * irrelevant and unchanged except for its first 4 bytes, which a probe may overwrite.
+ * Returns HSD_EINVAL for an unknown kind, n_workgroups or iters < 1, or a scratch buffer that does not fit the kind. */
+enum { HSD_PROBE_MFMA = 0, HSD_PROBE_LOAD_REG = 1, HSD_PROBE_LOAD_LDS = 2, HSD_PROBE_LDS_READ = 3 };
+int hsd_probe_launch(void *stream, int kind, int n_workgroups, int iters, int arg, void *scratch, size_t scratch_bytes);
+
 #ifdef __cplusplus
 }
 #endif

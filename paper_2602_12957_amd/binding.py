@@ -77,7 +77,10 @@ HSD_DEBUG_SYNC_LAYERS, HSD_DEBUG_FORCE_SIMPLE = 1, 2
 (HSD_DEBUG_GEMM_CFG_QKV, HSD_DEBUG_GEMM_CFG_O, HSD_DEBUG_GEMM_CFG_GATE_UP, HSD_DEBUG_GEMM_CFG_DOWN,
  HSD_DEBUG_GEMM_CFG_LM_HEAD) = range(6, 11)
 
-EXPORTS = ["hsd_verify_region_batch_noalloc", "hsd_noalloc_scratch_bytes", "hsd_debug_set", "hsd_profile_enable", "hsd_profile_read", "hsd_status_string", "hsd_validate_model", "hsd_validate_batch", "hsd_create", "hsd_destroy",
+lib.hsd_probe_launch.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_size_t]
+HSD_PROBE_MFMA, HSD_PROBE_LOAD_REG, HSD_PROBE_LOAD_LDS, HSD_PROBE_LDS_READ = range(4)
+
+EXPORTS = ["hsd_probe_launch", "hsd_verify_region_batch_noalloc", "hsd_noalloc_scratch_bytes", "hsd_debug_set", "hsd_profile_enable", "hsd_profile_read", "hsd_status_string", "hsd_validate_model", "hsd_validate_batch", "hsd_create", "hsd_destroy",
            "hsd_workspace_bytes", "hsd_kv_pool_init", "hsd_verify_region_batch", "hsd_verify_page",
            "hsd_kv_commit_rollback", "hsd_prefill"]
 
@@ -125,3 +128,5 @@ def hsd_profile_read(ctx):
 
 def hsd_debug_set(ctx, knob, value):
     check("hsd_debug_set", lib.hsd_debug_set(ctx, knob, value))
+def hsd_probe_launch(stream, kind, n_workgroups, iters, arg, scratch, scratch_bytes):
+    check("hsd_probe_launch", lib.hsd_probe_launch(stream, kind, n_workgroups, iters, arg, scratch, scratch_bytes))

@@ -19,6 +19,7 @@
 #include "gemm_mfma8.h"
 #include "gemm_mfma_ws.h"
 #include "gemm_mfma_d.h"
+#include "probes.h"
 #include "gemm_simple.h"
 #include "misc_kernels.h"
 
@@ -743,6 +744,42 @@ int hsd_debug_set(hsd_ctx *c, int knob, int64_t value) {
       return HSD_OK;
     default: return HSD_EINVAL;
   }
+}
+
+int hsd_probe_launch(void *stream, int kind, int n_workgroups, int iters, int arg, void *scratch, size_t scratch_bytes) {
+  if (n_workgroups < 1 || n_workgroups > (1 << 20) || iters < 1 || scratch == nullptr || scratch_bytes < 4) return HSD_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float *sink = static_cast<float *>(scratch);
+  switch (kind) {
+    case HSD_PROBE_MFMA:
+      hipLaunchKernelGGL(k_probe_mfma, dim3(n_workgroups), dim3(256), 0, st, iters, sink);
+      break;
+    case HSD_PROBE_LOAD_REG:
+    case HSD_PROBE_LOAD_LDS: {
+      const size_t region = scratch_bytes / 8;
+      if (region < 32768 || region % 32768 != 0 || region >= (size_t{1} << 31)) return HSD_EINVAL;
+      if (kind == HSD_PROBE_LOAD_REG)
+        hipLaunchKernelGGL(k_probe_load<false>, dim3(n_workgroups), dim3(256), 32768, st,
+                           static_cast<const unsigned char *>(scratch), static_cast<int>(region), iters, sink);
+      else
+        hipLaunchKernelGGL(k_probe_load<true>, dim3(n_workgroups), dim3(256), 32768, st,
+                           static_cast<const unsigned char *>(scratch), static_cast<int>(region), iters, sink);
+      break;
+    }
+    case HSD_PROBE_LDS_READ: {
+      if (arg < 1 || arg > 16) return HSD_EINVAL;
+      // more than half of a compute unit's LDS: one workgroup per unit
+      constexpr int smem = 96 * 1024;
+      static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(k_probe_lds),
+                                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+      if (attr_rc != hipSuccess) return HSD_EHIP;
+      hipLaunchKernelGGL(k_probe_lds, dim3(n_workgroups), dim3(64 * arg), smem, st, iters, sink);
+      break;
+    }
+    default: return HSD_EINVAL;
+  }
+  HSD_LAUNCH_CHECK();
+  return HSD_OK;
 }
 
 void hsd_destroy(hsd_ctx *ctx) {

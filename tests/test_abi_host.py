@@ -124,3 +124,15 @@ def test_create_without_gpu_reports_no_device():
     out = C.c_void_p()
     assert B.lib.hsd_create(C.byref(d), C.byref(w), C.byref(out)) == B.HSD_ENODEV
     assert not out.value
+
+
+def test_probe_launch_rejects_bad_arguments_before_touching_a_device():
+    """hsd_probe_launch validates its arguments on the host: nothing is launched for any of these."""
+    fake = C.c_void_p(0x1000)   # never dereferenced: every call below fails validation first
+    for kind, n_wg, iters, arg, scratch, nbytes in (
+            (B.HSD_PROBE_MFMA, 0, 10, 0, fake, 64), (B.HSD_PROBE_MFMA, 8, 0, 0, fake, 64),
+            (B.HSD_PROBE_MFMA, 8, 10, 0, None, 64), (B.HSD_PROBE_MFMA, 8, 10, 0, fake, 0),
+            (7, 8, 10, 0, fake, 64), (B.HSD_PROBE_LOAD_REG, 8, 10, 0, fake, 8 * 32768 - 8),
+            (B.HSD_PROBE_LOAD_LDS, 8, 10, 0, fake, 8 * 40000), (B.HSD_PROBE_LDS_READ, 8, 10, 0, fake, 64),
+            (B.HSD_PROBE_LDS_READ, 8, 10, 17, fake, 64)):
+        assert B.lib.hsd_probe_launch(None, kind, n_wg, iters, arg, scratch, nbytes) == B.HSD_EINVAL
