@@ -125,8 +125,11 @@ def run_config(cfg_index, args, weights_cache):
         for item in args.debug_knobs.split(","):
             k, v = item.split("=")
             debug[k] = tuple(int(x) for x in v.split(":")) if k == "gemm_cfg" else int(v)
+    # one long draft of one sequence (configs[2]) gives the attention launch 132 workgroups for 256 compute units:
+    # that is the case the library's key split (hsd_model_desc.attn_key_chunk, fixed cut points) is there for
+    key_chunk = args.attn_key_chunk if args.attn_key_chunk >= 0 else (1024 if cfg_index == 2 else 0)
     eng = Engine(desc, weights, n_blocks, n, maxb, ws_rows, max_dump=total_q if cfg_index == 1 else 0,
-                 attn_key_chunk=args.attn_key_chunk, debug=debug)
+                 attn_key_chunk=key_chunk, debug=debug)
     slots = list(range(n))
     toks, embs, pend = [], [], []
     for sp in specs:
@@ -221,6 +224,7 @@ def run_config(cfg_index, args, weights_cache):
     all_flops_step = gemm_flops_step + desc.n_layers * att_flops
     res = {
         "workload": WORKLOAD_TEXT[cfg_index] + (" (random drafts)" if args.random_target else ""),
+        "attn_key_chunk": key_chunk,
         "entry_point": "hsd_verify_region_batch" if mode == "region" else "hsd_verify_page",
         "n_seq": n, "rows_per_step": total_q, "draft_tokens_per_step": verified, "steps": steps,
         "ms_per_step": round(ms_step, 4),
@@ -454,8 +458,9 @@ def main():
     ap.add_argument("--tau", type=float, default=1.0,
                     help="acceptance threshold of the relaxed rule (paper default 0.75); 1.0 = exact greedy match, "
                          "the rule the headline metric is defined on")
-    ap.add_argument("--attn-key-chunk", type=int, default=0,
-                    help="attention key split (hsd_model_desc.attn_key_chunk): keys per chunk, 0 = unsplit")
+    ap.add_argument("--attn-key-chunk", type=int, default=-1,
+                    help="attention key split (hsd_model_desc.attn_key_chunk): keys per chunk, 0 = unsplit; "
+                         "default: 1024 for configs[2] (one long draft of one sequence), unsplit elsewhere")
     ap.add_argument("--profile-config", type=int, default=0, choices=[0, 1, 2, 3, 4],
                     help="profiling aid: run round 1 of this one configuration only (set-up, warm-up, timed steps, "
                          "per-kernel extra steps) and print its result object instead of the headline line")

@@ -50,7 +50,7 @@ def _load(cfg):
         return json.load(f)
 
 
-def _run_config(cfg, mode, max_rounds=None):
+def _run_config(cfg, mode, max_rounds=None, attn_key_chunk=None):
     gold = _load(cfg)
     seed = gold["seed"]
     desc = W.CONFIGS[cfg].model
@@ -60,7 +60,8 @@ def _run_config(cfg, mode, max_rounds=None):
     weights = W.make_weights(desc, seed)
     n = len(seqs)
     total_q = sum(sp.draft_len + 1 for sp in specs)
-    eng = make_engine(desc, weights, specs, max_total_q=max(total_q, 4096), max_dump=8 * n)
+    eng = make_engine(desc, weights, specs, max_total_q=max(total_q, 4096), max_dump=8 * n,
+                      attn_key_chunk=attn_key_chunk)
     toks, embs, pend = [], [], []
     for s, sp in zip(seqs, specs):
         _, _, tok, emb, pending = prefix_rows(desc, seed, sp)
@@ -209,9 +210,12 @@ def test_config1_through_page_entry_point_round1():
     print("cfg1/page", stats)
 
 
-def test_config2_page_level_all_rounds():
-    stats = _run_config(2, "page")
-    print("cfg2", stats)
+@pytest.mark.parametrize("key_chunk", [0, 1024])
+def test_config2_page_level_all_rounds(key_chunk):
+    """configs[2]: one page, one long draft; unsplit and with the attention key split the benchmark times it with
+    (keys cut at multiples of 1024: other grouping of the fp32 sums, same bars against the plain oracle)."""
+    stats = _run_config(2, "page", attn_key_chunk=key_chunk)
+    print("cfg2", key_chunk, stats)
 
 
 def test_config3_long_document_first_and_later_round():
