@@ -17,6 +17,7 @@
 #include "epilogues.h"
 #include "gemm_mfma.h"
 #include "gemm_mfma8.h"
+#include "gemm_mfma8p.h"
 #include "gemm_mfma_ws.h"
 #include "gemm_mfma_d.h"
 #include "probes.h"
@@ -169,7 +170,8 @@ int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const v
 }
 
 template <typename Epi, bool WALK>
-int launch_gemm_mfma8_impl(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks) {
+int launch_gemm_mfma8_impl(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks,
+                           int n_cu) {
   constexpr int MODE = GemmModeOf<Epi>::value;
   using Cfg = GemmCfg8;
   auto kern = k_gemm_mfma8<MODE, Epi, WALK>;
@@ -180,6 +182,23 @@ int launch_gemm_mfma8_impl(hipStream_t st, int M, int N, int K, const void *A, c
   if constexpr (MODE == kModeSwapLM) epi.n_tiles = (N / Cfg::BP) * Cfg::WM;
   int tiles_act, tiles_w;
   gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
+  // A launch of several rounds of tiles goes to the persistent form: one workgroup per compute unit (a multiple of
+  // 8, so that tiles stay on the XCD the tile order gives them) walks its tiles and requests the next tile's first
+  // K slices while the epilogue of the current one runs.  Not for the LM head: with the arg-max epilogue's state the
+  // slices in flight no longer fit the registers (67 spilled, 153 -> 184 us at 1856 rows).
+  if constexpr (!WALK && MODE != kModeSwapLM) {
+    const int grid_p = n_cu / 8 * 8;
+    if (grid_p >= 8 && tiles_act * tiles_w > grid_p) {
+      auto kern_p = k_gemm_mfma8p<MODE, Epi>;
+      static const hipError_t attr_rc_p = hipFuncSetAttribute(reinterpret_cast<const void *>(kern_p),
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+      if (attr_rc_p != hipSuccess) return HSD_EHIP;
+      hipLaunchKernelGGL(kern_p, dim3(grid_p), dim3(512), smem, st, M, N, K, static_cast<const bf16 *>(A),
+                         static_cast<const bf16 *>(W), epi);
+      HSD_LAUNCH_CHECK();
+      return HSD_OK;
+    }
+  }
   hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(512), smem, st, M, N, K, k_chunks,
                      static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), epi);
   HSD_LAUNCH_CHECK();
@@ -188,12 +207,13 @@ int launch_gemm_mfma8_impl(hipStream_t st, int M, int N, int K, const void *A, c
 
 // k_chunks > 1: the workgroup walks the chunks itself (read-modify-write epilogues only)
 template <typename Epi>
-int launch_gemm_mfma8(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks) {
+int launch_gemm_mfma8(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks,
+                      int n_cu) {
   if constexpr (Epi::kChunked) {
-    if (k_chunks > 1) return launch_gemm_mfma8_impl<Epi, true>(st, M, N, K, A, W, epi, k_chunks);
+    if (k_chunks > 1) return launch_gemm_mfma8_impl<Epi, true>(st, M, N, K, A, W, epi, k_chunks, n_cu);
   }
   if (k_chunks > 1) return HSD_EINVAL;
-  return launch_gemm_mfma8_impl<Epi, false>(st, M, N, K, A, W, epi, 1);
+  return launch_gemm_mfma8_impl<Epi, false>(st, M, N, K, A, W, epi, 1, n_cu);
 }
 
 template <typename Cfg, typename Epi>
@@ -323,7 +343,7 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
         if ((full * tiles_w + cu - 1) / cu < ((full + 1) * tiles_w + cu - 1) / cu &&
             static_cast<int64_t>(M) * K * 2 < (int64_t{1} << 31) && w_cols * K * 2 < (int64_t{1} << 31)) {
           const int m_main = M - rem;
-          const int rc = cfg == 8 ? launch_gemm_mfma8(st, m_main, N, K, A, W, epi, 1)
+          const int rc = cfg == 8 ? launch_gemm_mfma8(st, m_main, N, K, A, W, epi, 1, ctx->n_cu)
                                   : launch_gemm_mfma<GemmCfg6>(st, m_main, N, K, A, W, epi, 1, false);
           if (rc != HSD_OK) return rc;
           return launch_gemm_mfma_d<GemmCfgD64>(st, M, N, K, A, W, epi, m_main);
@@ -346,7 +366,7 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
         if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
           return launch_gemm_mfma_ws<GemmCfgWS64>(st, M, N, K, A, W, epi, k_chunks, split);
         break;
-      case 8: return launch_gemm_mfma8(st, M, N, K, A, W, epi, k_chunks);
+      case 8: return launch_gemm_mfma8(st, M, N, K, A, W, epi, k_chunks, ctx->n_cu);
       case 10:
         if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
           return launch_gemm_mfma_d<GemmCfgD64>(st, M, N, K, A, W, epi);
