@@ -465,7 +465,7 @@ def main():
                     help="profiling aid: run round 1 of this one configuration only (set-up, warm-up, timed steps, "
                          "per-kernel extra steps) and print its result object instead of the headline line")
     ap.add_argument("--debug-knobs", type=str, default="",
-                    help="experiments only: hsd_debug_set knobs, e.g. kchunks_down=1,gemm_cfg=7:9:8:9:8")
+                    help="experiments only: hsd_debug_set knobs, e.g. sync_layers=1,gemm_cfg=7:9:8:9:8")
     ap.add_argument("--breakdown", action="store_true",
                     help="after the timed region, time every kernel class in turn (extra steps) and report avg us per launch")
     ap.add_argument("--hw-probe", action="store_true",

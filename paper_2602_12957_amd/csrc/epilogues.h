@@ -34,9 +34,7 @@ struct RowScale {
 template <typename T>
 struct EpiQKV {
   static constexpr bool kDual = false;
-  static constexpr bool kChunked = false;
   static constexpr bool kRowScale = true;
-  __device__ __forceinline__ const EpiQKV &for_split(int, int) const { return *this; }
   int n_q_heads, n_kv_heads;
   RowMeta meta;
   PagedKV kv;
@@ -122,9 +120,7 @@ struct EpiQKV {
 // kernels use EpiResidualNorm.
 struct EpiResidual {
   static constexpr bool kDual = false;
-  static constexpr bool kChunked = false;
   static constexpr bool kRowScale = false;
-  __device__ __forceinline__ const EpiResidual &for_split(int, int) const { return *this; }
   float *x;
   int ld;
   static constexpr int kPiece = 4;
@@ -155,14 +151,12 @@ __device__ __forceinline__ float sum8_lanes(float v) {
   return v;
 }
 
-// x += A W^T as EpiResidual (never split), and everything the RMSNorm after it needs (see RowScale): h = x * gain
+// x += A W^T as EpiResidual, and everything the RMSNorm after it needs (see RowScale): h = x * gain
 // in the GEMM operand type and the sum of squares of each 64-column piece of the row.  With gain == nullptr (no
 // norm follows: last layer of a prefill) only x is updated.  MFMA kernels only.
 struct EpiResidualNorm {
   static constexpr bool kDual = false;
-  static constexpr bool kChunked = false;
   static constexpr bool kRowScale = false;
-  __device__ __forceinline__ const EpiResidualNorm &for_split(int, int) const { return *this; }
   float *x;
   int ld;
   const float *gain;  // [ld] gain of the norm that follows, or nullptr
@@ -204,9 +198,7 @@ struct EpiResidualNorm {
 template <typename T>
 struct EpiSwiGLU {
   static constexpr bool kDual = true;
-  static constexpr bool kChunked = false;
   static constexpr bool kRowScale = true;
-  __device__ __forceinline__ const EpiSwiGLU &for_split(int, int) const { return *this; }
   T *u;
   int ld;
   RowScale rs;
@@ -241,9 +233,7 @@ struct EpiSwiGLU {
 // kernel reduces the records of one row within the column tile and stores one record per (row, tile).
 struct EpiLMHead {
   static constexpr bool kDual = false;
-  static constexpr bool kChunked = false;
   static constexpr bool kRowScale = true;
-  __device__ __forceinline__ const EpiLMHead &for_split(int, int) const { return *this; }
   Top2 *part;  // [T][n_tiles]
   int n_tiles;
   int vocab;

@@ -212,16 +212,8 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[Cfg::TM][Cfg::TN],
 
 // grid: 1-D, tiles_act * tiles_w workgroups of Cfg::kThreads threads, Cfg::kSmemBytes dynamic LDS.
 // N is the number of output columns (for dual mode the weight matrix has 2N rows: gate | up).
-//
-// K may be reduced in `k_chunks` equal chunks whose sums are added to the destination one after the other, chunk 0
-// first: out = ((out + P0) + P1) + ...  With gridDim.y == k_chunks each workgroup handles one chunk and hands its
-// partial sum to the epilogue (split-K; the caller adds the partials in that order); with gridDim.y == 1 the
-// workgroup walks all chunks itself, running the (read-modify-write) epilogue and restarting its accumulators at
-// every chunk boundary.  Both forms round identically, so the choice between them (made from the number of tiles)
-// never changes a result bit.  WALK_CHUNKS selects the second form at compile time.
-template <typename Cfg, int MODE, typename Epi, bool WALK_CHUNKS = false>
-__global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K, int k_chunks,
-                                                             const bf16 *__restrict__ A,
+template <typename Cfg, int MODE, typename Epi>
+__global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K, const bf16 *__restrict__ A,
                                                              const bf16 *__restrict__ W, Epi epi) {
   constexpr int BP = Cfg::BP, BQ = Cfg::BQ, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN, LS = Cfg::kStride;
   constexpr int NT = Cfg::kThreads, CH = Cfg::kChunks;
@@ -280,9 +272,7 @@ __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K
   // groups of the four k-steps so that neither blocks a long MFMA run.
   u32x4 regP[2][Cfg::kLoadsP], regQ[2][Cfg::kLoadsQ];
   static_assert(BK == 64 && Cfg::kLoadsP % 2 == 0 && Cfg::kLoadsQ % 2 == 0, "pipeline is written for 4 k-steps");
-  const int k_len = K / k_chunks, nk = k_len / BK;
-  const bool split = gridDim.y > 1;
-  const int c_begin = split ? blockIdx.y : 0, c_end = split ? blockIdx.y + 1 : k_chunks;
+  const int nk = K / BK;
 
 #define HSD_GEMM_LOAD(set, k0, h)                                                                   \
   _Pragma("unroll") for (int i = (h) * (Cfg::kLoadsP / 2); i < ((h) + 1) * (Cfg::kLoadsP / 2); ++i) \
@@ -317,7 +307,7 @@ __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K
 #define HSD_GEMM_ITER(kt, ld, st, REQ, PUT)                                                         \
   {                                                                                                 \
     const uint16_t *sp = smem + ((kt) & 1) * Cfg::kStage;                                           \
-    const int knext = kc0 + ((kt) + 2) * BK;                                                        \
+    const int knext = ((kt) + 2) * BK;                                                              \
     if (REQ) { HSD_GEMM_LOAD(ld, knext, 0) }                                                        \
     HSD_GEMM_KSTEP(0)                                                                               \
     __builtin_amdgcn_sched_barrier(0);                                                              \
@@ -332,50 +322,32 @@ __global__ void __launch_bounds__(Cfg::kThreads) k_gemm_mfma(int M, int N, int K
     __syncthreads();                                                                                \
   }
 
-  for (int chunk = c_begin; chunk < c_end; ++chunk) {
-    const int kc0 = chunk * k_len;
-    HSD_GEMM_LOAD(0, kc0, 0) HSD_GEMM_LOAD(0, kc0, 1)
-    if (nk > 1) { HSD_GEMM_LOAD(1, kc0 + BK, 0) HSD_GEMM_LOAD(1, kc0 + BK, 1) }
-    HSD_GEMM_STORE(0, 0, 0) HSD_GEMM_STORE(0, 0, 1)
-    __syncthreads();
-    // slice kt is in LDS stage kt & 1 and came through register set kt & 1; iteration kt requests slice kt+2
-    // into set kt & 1 and stores set (kt+1) & 1.  Full iterations run while kt + 2 < nk.
-    int kt = 0;
-    for (; kt + 3 < nk; kt += 2) {
-      HSD_GEMM_ITER(kt, 0, 1, true, true)
-      HSD_GEMM_ITER(kt + 1, 1, 0, true, true)
-    }
-    if (kt + 2 < nk) {  // one more full iteration, then the two-iteration tail on swapped sets
-      HSD_GEMM_ITER(kt, 0, 1, true, true)
-      HSD_GEMM_ITER(kt + 1, 1, 0, false, true)
-      HSD_GEMM_ITER(kt + 2, 0, 1, false, false)
-    } else if (kt + 1 < nk) {
-      HSD_GEMM_ITER(kt, 0, 1, false, true)
-      HSD_GEMM_ITER(kt + 1, 1, 0, false, false)
-    } else {
-      HSD_GEMM_ITER(kt, 0, 1, false, false)
-    }
-    if constexpr (WALK_CHUNKS) {
-      // the chunk's sum goes to the destination now; the LDS stages double as the epilogue's staging area, so
-      // every wave must be through with it before the next chunk's first slice is written
-      gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(-1, M),
-                               reinterpret_cast<float *>(smem_raw));
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-      __syncthreads();
-    }
-  }  // chunk loop
+  HSD_GEMM_LOAD(0, 0, 0) HSD_GEMM_LOAD(0, 0, 1)
+  if (nk > 1) { HSD_GEMM_LOAD(1, BK, 0) HSD_GEMM_LOAD(1, BK, 1) }
+  HSD_GEMM_STORE(0, 0, 0) HSD_GEMM_STORE(0, 0, 1)
+  __syncthreads();
+  // slice kt is in LDS stage kt & 1 and came through register set kt & 1; iteration kt requests slice kt+2
+  // into set kt & 1 and stores set (kt+1) & 1.  Full iterations run while kt + 2 < nk.
+  int kt = 0;
+  for (; kt + 3 < nk; kt += 2) {
+    HSD_GEMM_ITER(kt, 0, 1, true, true)
+    HSD_GEMM_ITER(kt + 1, 1, 0, true, true)
+  }
+  if (kt + 2 < nk) {  // one more full iteration, then the two-iteration tail on swapped sets
+    HSD_GEMM_ITER(kt, 0, 1, true, true)
+    HSD_GEMM_ITER(kt + 1, 1, 0, false, true)
+    HSD_GEMM_ITER(kt + 2, 0, 1, false, false)
+  } else if (kt + 1 < nk) {
+    HSD_GEMM_ITER(kt, 0, 1, false, true)
+    HSD_GEMM_ITER(kt + 1, 1, 0, false, false)
+  } else {
+    HSD_GEMM_ITER(kt, 0, 1, false, false)
+  }
 #undef HSD_GEMM_LOAD
 #undef HSD_GEMM_STORE
 #undef HSD_GEMM_KSTEP
 #undef HSD_GEMM_ITER
-  if constexpr (!WALK_CHUNKS)
-    gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(split ? blockIdx.y : -1, M),
-                             reinterpret_cast<float *>(smem_raw));
+  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi, reinterpret_cast<float *>(smem_raw));
 }
 
 }  // namespace hsd

@@ -11,9 +11,7 @@
 // two register sets; the other set, holding slice k+1, is written to the free LDS stage after the last k-step.
 // Loads are raw buffer loads: rows past the end of a matrix read as zero in hardware, no clamping needed.
 //
-// Operand roles (P = MFMA i side, Q = j side), modes and the epilogue are those of gemm_mfma.h.  K may be walked in
-// `k_chunks` equal chunks (read-modify-write epilogues only): the epilogue runs and the accumulators restart at every
-// chunk boundary, which rounds exactly like the split-K form of the generic kernel.
+// Operand roles (P = MFMA i side, Q = j side), modes and the epilogue are those of gemm_mfma.h.
 #pragma once
 
 #include "gemm_mfma.h"
@@ -29,8 +27,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, si
 }
 
 // grid: 1-D, tiles_act * tiles_w workgroups of 512 threads, GemmCfg8::kSmemBytes dynamic LDS.
-template <int MODE, typename Epi, bool WALK_CHUNKS = false>
-__global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, int k_chunks, const bf16 *__restrict__ A,
+// K a multiple of 128 and at least 256 (an even number, >= 4, of K slices); both matrices below 2 GiB.
+template <int MODE, typename Epi>
+__global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, const bf16 *__restrict__ A,
                                                     const bf16 *__restrict__ W, Epi epi) {
   using Cfg = GemmCfg8;
   constexpr int BP = Cfg::BP, BQ = Cfg::BQ, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN, LS = Cfg::kStride;
@@ -88,10 +87,7 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, int k_c
   // iteration, and the requests for slice kt+2 go out into set Y.  A request therefore has two full
   // iterations to come back.
   u32x4 regP[2][4], regQ[2][4];
-  // without WALK_CHUNKS the chunk loop below is a single pass over all of K, known at compile time (a run-time
-  // loop around the pipeline costs the registers that keep this kernel free of spills)
-  const int n_chunks = WALK_CHUNKS ? k_chunks : 1;
-  const int k_len = K / n_chunks, nk = k_len / BK;
+  const int nk = K / BK;
 
 #define HSD_G8_LOAD(set, i, kbyte)                                                                    \
   regP[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rs_p, voff_p + (i) * p_step, (kbyte), 0);      \
@@ -120,7 +116,7 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, int k_c
 #define HSD_G8_ITER(kt, ld, st, REQ, PUT)                                                             \
   {                                                                                                   \
     const uint16_t *sp = smem + ((kt) & 1) * Cfg::kStage;                                             \
-    const int kbyte = kb0 + ((kt) + 2) * BK * 2;                                                      \
+    const int kbyte = ((kt) + 2) * BK * 2;                                                            \
     bf16x8 fa[2][TM], fb[2][TN];                                                                      \
     HSD_G8_FRAG(0, 0)                                                                                 \
     if (REQ) { HSD_G8_LOAD(ld, 0, kbyte) HSD_G8_LOAD(ld, 1, kbyte) }                                  \
@@ -140,37 +136,21 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8(int M, int N, int K, int k_c
     __syncthreads();                                                                                  \
   }
 
-  for (int chunk = 0; chunk < n_chunks; ++chunk) {
-    const int kb0 = WALK_CHUNKS ? chunk * k_len * 2 : 0;   // byte offset of the chunk's first K slice within a row
-    if (WALK_CHUNKS && chunk > 0) {
-      // the previous chunk's epilogue staged through the LDS the first slice is about to be written to
-      __syncthreads();
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    }
-    HSD_G8_LOAD(0, 0, kb0) HSD_G8_LOAD(0, 1, kb0) HSD_G8_LOAD(0, 2, kb0) HSD_G8_LOAD(0, 3, kb0)
-    HSD_G8_LOAD(1, 0, kb0 + BK * 2) HSD_G8_LOAD(1, 1, kb0 + BK * 2) HSD_G8_LOAD(1, 2, kb0 + BK * 2)
-    HSD_G8_LOAD(1, 3, kb0 + BK * 2)
-    HSD_G8_STORE(0, 0, 0, 4)
-    __syncthreads();
-    // slice kt+1 lives in set (kt+1) & 1; requests for slice kt+2 reuse set kt & 1 (stored one iteration ago)
-    // the host only launches this kernel with an even number (>= 4) of K slices per chunk: full iterations in
-    // pairs, then the fixed two-iteration tail (keeping the control flow this simple keeps the kernel free of
-    // register spills)
-    int kt = 0;
-    for (; kt + 3 < nk; kt += 2) {
-      HSD_G8_ITER(kt, 0, 1, true, true)
-      HSD_G8_ITER(kt + 1, 1, 0, true, true)
-    }
-    HSD_G8_ITER(kt, 0, 1, false, true)
-    HSD_G8_ITER(kt + 1, 1, 0, false, false)
-    gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(-1, M),
-                             reinterpret_cast<float *>(smem_raw));
+  HSD_G8_LOAD(0, 0, 0) HSD_G8_LOAD(0, 1, 0) HSD_G8_LOAD(0, 2, 0) HSD_G8_LOAD(0, 3, 0)
+  HSD_G8_LOAD(1, 0, BK * 2) HSD_G8_LOAD(1, 1, BK * 2) HSD_G8_LOAD(1, 2, BK * 2) HSD_G8_LOAD(1, 3, BK * 2)
+  HSD_G8_STORE(0, 0, 0, 4)
+  __syncthreads();
+  // slice kt+1 lives in set (kt+1) & 1; requests for slice kt+2 reuse set kt & 1 (stored one iteration ago).
+  // The host only launches this kernel with an even number (>= 4) of K slices: full iterations in pairs, then the
+  // fixed two-iteration tail (keeping the control flow this simple keeps the kernel free of register spills)
+  int kt = 0;
+  for (; kt + 3 < nk; kt += 2) {
+    HSD_G8_ITER(kt, 0, 1, true, true)
+    HSD_G8_ITER(kt + 1, 1, 0, true, true)
   }
+  HSD_G8_ITER(kt, 0, 1, false, true)
+  HSD_G8_ITER(kt + 1, 1, 0, false, false)
+  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi, reinterpret_cast<float *>(smem_raw));
 #undef HSD_G8_LOAD
 #undef HSD_G8_STORE
 #undef HSD_G8_FRAG

@@ -128,7 +128,7 @@ __global__ void __launch_bounds__(512) k_gemm_mfma8p(int M, int N, int K, const 
     }
     HSD_G8P_ITER(kt, 0, 1, vpn, vqn, 0, true)
     HSD_G8P_ITER(kt + 1, 1, 0, vpn, vqn, BK * 2, false)
-    gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(-1, M),
+    gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi,
                              reinterpret_cast<float *>(smem_raw));
     if (!has_next) break;
     pid = next;

@@ -194,7 +194,7 @@ __global__ void __launch_bounds__(320) k_gemm_mfma_d(int M, int N, int K, int m_
 #undef HSD_GD_FRAG
 #undef HSD_GD_MMA
   __builtin_amdgcn_s_barrier();   // the epilogue stages through the operand stages
-  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(-1, M),
+  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi,
                            reinterpret_cast<float *>(smem_raw));
 }
 

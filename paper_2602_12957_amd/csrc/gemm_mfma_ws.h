@@ -11,7 +11,7 @@
 // Same pipeline as the generic kernel (two LDS stages, two register sets, a slice requested two iterations before
 // it is stored), same tile order, same epilogue (multiplying waves only), same K order in every accumulator, so
 // results are bit-identical to every other tile configuration.  Modes: normal and dual (the swapped LM-head mode
-// has its own kernel); K chunks only as split-K.
+// has its own kernel).
 // Every wave executes exactly 1 + K/64 workgroup barriers, whichever role it has.
 #pragma once
 
@@ -23,9 +23,9 @@ using GemmCfgWS = GemmCfg<128, 128, 64, 2, 2>;
 using GemmCfgWS64 = GemmCfg<64, 128, 64, 2, 2>;
 
 // Cfg: a configuration with four (multiplying) waves.
-// grid: (tiles_act * tiles_w, k_chunks or 1), 512 threads, Cfg::kSmemBytes dynamic LDS.
+// grid: 1-D, tiles_act * tiles_w workgroups of 512 threads, Cfg::kSmemBytes + kRowScaleBytes dynamic LDS.
 template <typename Cfg, int MODE, typename Epi>
-__global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, int k_chunks, const bf16 *__restrict__ A,
+__global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, const bf16 *__restrict__ A,
                                                       const bf16 *__restrict__ W, Epi epi) {
   static_assert(Cfg::kThreads == 256 && Cfg::BK == 64, "four multiplying waves, 64-wide K slices");
   static_assert(MODE == kModeNormal || MODE == kModeDual, "normal or dual mode");
@@ -40,9 +40,7 @@ __global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, int k
   gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
   gemm_tile_of(blockIdx.x, M, (MODE == kModeDual) ? 2 * N : N, tiles_act, tiles_w, ta, tw);
   const int m0 = ta * BP, n0 = tw * ((MODE == kModeDual) ? BQ / 2 : BQ);
-  const bool split = gridDim.y > 1;
-  const int k_len = K / k_chunks, nk = k_len / BK;
-  const int kc0 = split ? static_cast<int>(blockIdx.y) * k_len : 0;
+  const int nk = K / BK;
 
   if (mover) {
     const int tp = t - NT;
@@ -51,7 +49,7 @@ __global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, int k
 #pragma unroll
     for (int i = 0; i < LP; ++i) {
       const int c = tp + NT * i, r = c / CH, kc = c % CH;
-      srcP[i] = A + static_cast<size_t>(min(m0 + r, M - 1)) * K + kc0 + kc * 8;
+      srcP[i] = A + static_cast<size_t>(min(m0 + r, M - 1)) * K + kc * 8;
     }
 #pragma unroll
     for (int i = 0; i < LQ; ++i) {
@@ -65,7 +63,7 @@ __global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, int k
       } else {
         row = min(n0 + r, N - 1);
       }
-      srcQ[i] = W + static_cast<size_t>(row) * K + kc0 + kc * 8;
+      srcQ[i] = W + static_cast<size_t>(row) * K + kc * 8;
     }
     u32x4 regP[2][LP], regQ[2][LQ];
     // requests are unconditional (past the last slice they re-read the last one; the LDS store that follows fills a
@@ -153,7 +151,7 @@ __global__ void __launch_bounds__(512) k_gemm_mfma_ws(int M, int N, int K, int k
   }
   // the moving waves have left; their last LDS stores came before the last barrier, so the stages are free for
   // the epilogue's staging
-  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi.for_split(split ? blockIdx.y : -1, M),
+  gemm_epilogue<Cfg, MODE>(acc, M, N, m0, n0, tw, wi, wj, lane, epi,
                                   reinterpret_cast<float *>(smem_raw));
 }
 

@@ -140,11 +140,10 @@ struct GemmModeOf {
   static constexpr int value = Epi::kDual ? kModeDual : (std::is_same<Epi, EpiLMHead>::value ? kModeSwapLM : kModeNormal);
 };
 
-template <typename Cfg, typename Epi, bool WALK>
-int launch_gemm_mfma_impl(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks,
-                          bool split) {
+template <typename Cfg, typename Epi>
+int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi) {
   constexpr int MODE = GemmModeOf<Epi>::value;
-  auto kern = k_gemm_mfma<Cfg, MODE, Epi, WALK>;
+  auto kern = k_gemm_mfma<Cfg, MODE, Epi>;
   constexpr int smem = Cfg::kSmemBytes + kRowScaleBytes;
   // set once per instantiation (initialisation of a function-local static is thread safe)
   static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -153,28 +152,17 @@ int launch_gemm_mfma_impl(hipStream_t st, int M, int N, int K, const void *A, co
   if constexpr (MODE == kModeSwapLM) epi.n_tiles = (N / Cfg::BP) * Cfg::WM;
   int tiles_act, tiles_w;
   gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
-  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w, split ? k_chunks : 1), dim3(Cfg::kThreads), smem, st, M, N, K,
-                     k_chunks, static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), epi);
+  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(Cfg::kThreads), smem, st, M, N, K,
+                     static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), epi);
   HSD_LAUNCH_CHECK();
   return HSD_OK;
 }
 
-// k_chunks > 1 without split: the workgroup walks the chunks itself (kernel variant with an epilogue per chunk)
-template <typename Cfg, typename Epi>
-int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks = 1,
-                     bool split = false) {
-  if constexpr (Epi::kChunked) {
-    if (k_chunks > 1 && !split) return launch_gemm_mfma_impl<Cfg, Epi, true>(st, M, N, K, A, W, epi, k_chunks, false);
-  }
-  return launch_gemm_mfma_impl<Cfg, Epi, false>(st, M, N, K, A, W, epi, k_chunks, split);
-}
-
-template <typename Epi, bool WALK>
-int launch_gemm_mfma8_impl(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks,
-                           int n_cu) {
+template <typename Epi>
+int launch_gemm_mfma8(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int n_cu) {
   constexpr int MODE = GemmModeOf<Epi>::value;
   using Cfg = GemmCfg8;
-  auto kern = k_gemm_mfma8<MODE, Epi, WALK>;
+  auto kern = k_gemm_mfma8<MODE, Epi>;
   constexpr int smem = Cfg::kSmemBytes + kRowScaleBytes;
   static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -186,7 +174,7 @@ int launch_gemm_mfma8_impl(hipStream_t st, int M, int N, int K, const void *A, c
   // 8, so that tiles stay on the XCD the tile order gives them) walks its tiles and requests the next tile's first
   // K slices while the epilogue of the current one runs.  Not for the LM head: with the arg-max epilogue's state the
   // slices in flight no longer fit the registers (67 spilled, 153 -> 184 us at 1856 rows).
-  if constexpr (!WALK && MODE != kModeSwapLM) {
+  if constexpr (MODE != kModeSwapLM) {
     const int grid_p = n_cu / 8 * 8;
     if (grid_p >= 8 && tiles_act * tiles_w > grid_p) {
       auto kern_p = k_gemm_mfma8p<MODE, Epi>;
@@ -199,37 +187,24 @@ int launch_gemm_mfma8_impl(hipStream_t st, int M, int N, int K, const void *A, c
       return HSD_OK;
     }
   }
-  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(512), smem, st, M, N, K, k_chunks,
-                     static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), epi);
+  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(512), smem, st, M, N, K, static_cast<const bf16 *>(A),
+                     static_cast<const bf16 *>(W), epi);
   HSD_LAUNCH_CHECK();
   return HSD_OK;
 }
 
-// k_chunks > 1: the workgroup walks the chunks itself (read-modify-write epilogues only)
-template <typename Epi>
-int launch_gemm_mfma8(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks,
-                      int n_cu) {
-  if constexpr (Epi::kChunked) {
-    if (k_chunks > 1) return launch_gemm_mfma8_impl<Epi, true>(st, M, N, K, A, W, epi, k_chunks, n_cu);
-  }
-  if (k_chunks > 1) return HSD_EINVAL;
-  return launch_gemm_mfma8_impl<Epi, false>(st, M, N, K, A, W, epi, 1, n_cu);
-}
-
 template <typename Cfg, typename Epi>
-int launch_gemm_mfma_ws(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi, int k_chunks,
-                        bool split) {
+int launch_gemm_mfma_ws(hipStream_t st, int M, int N, int K, const void *A, const void *W, Epi epi) {
   constexpr int MODE = GemmModeOf<Epi>::value;
   auto kern = k_gemm_mfma_ws<Cfg, MODE, Epi>;
   constexpr int smem = Cfg::kSmemBytes + kRowScaleBytes;
   static const hipError_t attr_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (attr_rc != hipSuccess) return HSD_EHIP;
-  if (k_chunks > 1 && !split) return HSD_EINVAL;   // K chunks only as split-K
   int tiles_act, tiles_w;
   gemm_tiles<Cfg, MODE>(M, N, tiles_act, tiles_w);
-  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w, split ? k_chunks : 1), dim3(512), smem, st, M, N, K, k_chunks,
-                     static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), epi);
+  hipLaunchKernelGGL(kern, dim3(tiles_act * tiles_w), dim3(512), smem, st, M, N, K, static_cast<const bf16 *>(A),
+                     static_cast<const bf16 *>(W), epi);
   HSD_LAUNCH_CHECK();
   return HSD_OK;
 }
@@ -267,7 +242,7 @@ using GemmCfgD128 = GemmCfgD<128, 128, 4>;
 // Tile configuration actually used at a call site for a given problem (the launch and everything sized from the
 // tile shape, like the LM-head partial records, must agree on it).  -1 = plain kernels.
 template <typename T>
-int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_chunks, bool split) {
+int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K) {
   if (!std::is_same<T, bf16>::value || ctx->force_simple || K % 64 != 0) return -1;
   int cfg = ctx->gemm_cfg[site];
   if (cfg < 0 || cfg > 11) cfg = 0;
@@ -294,23 +269,22 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_
   }
   // ... and a pass over many rows (prefill chunks, long-document blocks) has enough row tiles to fill the chip with
   // the 256x256 tile also on the narrower projections (measured crossover: about 6 k rows at N = 1536)
-  if ((site == kSiteQKV || site == kSiteO || (site == kSiteDown && !split)) && M >= 6144 && !ctx->gemm_cfg_forced) {
+  if ((site == kSiteQKV || site == kSiteO || site == kSiteDown) && M >= 6144 && !ctx->gemm_cfg_forced) {
     // 256x256 tiles, unless their count leaves the last round over the CUs nearly empty and 256x128 tiles (8 waves,
     // one workgroup per CU as well, 0.575 of the time per tile) fill the rounds better
     const int64_t rt = (M + 255) / 256, cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
     const int64_t t8 = rt * ((N + 255) / 256), t6 = rt * ((N + 127) / 128);
     cfg = ((t6 + cu - 1) / cu) * 575 < ((t8 + cu - 1) / cu) * 900 ? 6 : 8;   // only on a clear (10 %) advantage
   }
-  // the two-role kernels: not for the swapped LM-head mode, K chunks only as split-K
-  if ((cfg == 7 || cfg == 9) && (site == kSiteLM || (k_chunks > 1 && !split))) cfg = cfg == 7 ? 0 : 2;
-  // the LDS-direct kernels: no K chunks, not the swapped mode, 32-bit operand offsets
+  // the two-role kernels: not for the swapped LM-head mode
+  if ((cfg == 7 || cfg == 9) && site == kSiteLM) cfg = cfg == 7 ? 0 : 2;
+  // the LDS-direct kernels: not the swapped mode, 32-bit operand offsets
   if ((cfg == 10 || cfg == 11) &&
-      (site == kSiteLM || k_chunks > 1 || static_cast<int64_t>(M) * K * 2 >= (int64_t{1} << 31) ||
+      (site == kSiteLM || static_cast<int64_t>(M) * K * 2 >= (int64_t{1} << 31) ||
        (site == kSiteGateUp ? 2 : 1) * static_cast<int64_t>(N) * K * 2 >= (int64_t{1} << 31)))
     cfg = cfg == 11 ? 0 : 2;
-  // the 8-wave kernel walks its K chunks itself (no split-K form), each an even number (>= 4) of 64-wide slices
-  const int k_len = K / k_chunks;
-  if (cfg == 8 && (split || k_len % 128 != 0 || k_len < 256)) cfg = 0;
+  // the 8-wave kernel needs an even number (>= 4) of 64-wide K slices
+  if (cfg == 8 && (K % 128 != 0 || K < 256)) cfg = 0;
   // ... and addresses its operands with 32-bit byte offsets (buffer loads): both matrices must stay below 2 GiB
   // (in dual mode the weight matrix has 2N rows)
   const int64_t w_rows = site == kSiteGateUp ? 2 * static_cast<int64_t>(N) : N;
@@ -326,16 +300,16 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K, int k_
 
 template <typename T, typename Epi>
 int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int K, const void *A, const void *W,
-                const Epi &epi, int k_chunks = 1, bool split = false) {
+                const Epi &epi) {
   if constexpr (std::is_same<T, bf16>::value) {
-    const int cfg = effective_gemm_cfg<T>(ctx, site, M, N, K, k_chunks, split);
+    const int cfg = effective_gemm_cfg<T>(ctx, site, M, N, K);
     if constexpr (GemmModeOf<Epi>::value != kModeSwapLM) {
       // A last row tile of the 256-row kernels that holds only a few rows costs a whole tile, and when the tile count
       // is just above a multiple of the number of compute units it costs a whole extra round over the chip (4 pages
       // of 8193 rows: 129 x 4 tiles of the down projection = 2.02 rounds).  Then the few rows go to the small-tile
       // kernel in a launch of their own (rows are independent in every epilogue).
       const int rem = M % 256;
-      if ((cfg == 8 || cfg == 6) && !ctx->gemm_cfg_forced && k_chunks == 1 && rem > 0 && rem <= 64) {
+      if ((cfg == 8 || cfg == 6) && !ctx->gemm_cfg_forced && rem > 0 && rem <= 64) {
         const int64_t cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
         const int64_t w_cols = site == kSiteGateUp ? 2 * static_cast<int64_t>(N) : N;
         const int64_t tiles_w = cfg == 8 ? (w_cols + 255) / 256 : (w_cols + 127) / 128;
@@ -343,8 +317,8 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
         if ((full * tiles_w + cu - 1) / cu < ((full + 1) * tiles_w + cu - 1) / cu &&
             static_cast<int64_t>(M) * K * 2 < (int64_t{1} << 31) && w_cols * K * 2 < (int64_t{1} << 31)) {
           const int m_main = M - rem;
-          const int rc = cfg == 8 ? launch_gemm_mfma8(st, m_main, N, K, A, W, epi, 1, ctx->n_cu)
-                                  : launch_gemm_mfma<GemmCfg6>(st, m_main, N, K, A, W, epi, 1, false);
+          const int rc = cfg == 8 ? launch_gemm_mfma8(st, m_main, N, K, A, W, epi, ctx->n_cu)
+                                  : launch_gemm_mfma<GemmCfg6>(st, m_main, N, K, A, W, epi);
           if (rc != HSD_OK) return rc;
           return launch_gemm_mfma_d<GemmCfgD64>(st, M, N, K, A, W, epi, m_main);
         }
@@ -352,21 +326,21 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
     }
     switch (cfg) {
       case -1: break;
-      case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi, k_chunks, split);
-      case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi, k_chunks, split);
-      case 3: return launch_gemm_mfma<GemmCfg3>(st, M, N, K, A, W, epi, k_chunks, split);
-      case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi, k_chunks, split);
-      case 5: return launch_gemm_mfma<GemmCfg5>(st, M, N, K, A, W, epi, k_chunks, split);
-      case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi, k_chunks, split);
+      case 1: return launch_gemm_mfma<GemmCfg1>(st, M, N, K, A, W, epi);
+      case 2: return launch_gemm_mfma<GemmCfg2>(st, M, N, K, A, W, epi);
+      case 3: return launch_gemm_mfma<GemmCfg3>(st, M, N, K, A, W, epi);
+      case 4: return launch_gemm_mfma<GemmCfg4>(st, M, N, K, A, W, epi);
+      case 5: return launch_gemm_mfma<GemmCfg5>(st, M, N, K, A, W, epi);
+      case 6: return launch_gemm_mfma<GemmCfg6>(st, M, N, K, A, W, epi);
       case 7:
         if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
-          return launch_gemm_mfma_ws<GemmCfgWS>(st, M, N, K, A, W, epi, k_chunks, split);
+          return launch_gemm_mfma_ws<GemmCfgWS>(st, M, N, K, A, W, epi);
         break;
       case 9:
         if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
-          return launch_gemm_mfma_ws<GemmCfgWS64>(st, M, N, K, A, W, epi, k_chunks, split);
+          return launch_gemm_mfma_ws<GemmCfgWS64>(st, M, N, K, A, W, epi);
         break;
-      case 8: return launch_gemm_mfma8(st, M, N, K, A, W, epi, k_chunks, ctx->n_cu);
+      case 8: return launch_gemm_mfma8(st, M, N, K, A, W, epi, ctx->n_cu);
       case 10:
         if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
           return launch_gemm_mfma_d<GemmCfgD64>(st, M, N, K, A, W, epi);
@@ -375,7 +349,7 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
         if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
           return launch_gemm_mfma_d<GemmCfgD128>(st, M, N, K, A, W, epi);
         break;
-      default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi, k_chunks, split);
+      default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi);
     }
   }
   if constexpr (std::is_same<Epi, EpiResidualNorm>::value) {
@@ -393,7 +367,7 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
 template <typename T>
 int lm_head_tiles(const hsd_ctx *ctx, int M) {
   const int V = ctx->desc.vocab;
-  switch (effective_gemm_cfg<T>(ctx, kSiteLM, M, V, ctx->desc.d_model, 1, false)) {
+  switch (effective_gemm_cfg<T>(ctx, kSiteLM, M, V, ctx->desc.d_model)) {
     case -1: return V / 64;
     case 1: return V / GemmCfg1::BP * GemmCfg1::WM;
     case 4: return V / GemmCfg4::BP * GemmCfg4::WM;
