@@ -304,23 +304,31 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
   if constexpr (std::is_same<T, bf16>::value) {
     const int cfg = effective_gemm_cfg<T>(ctx, site, M, N, K);
     if constexpr (GemmModeOf<Epi>::value != kModeSwapLM) {
-      // A last row tile of the 256-row kernels that holds only a few rows costs a whole tile, and when the tile count
-      // is just above a multiple of the number of compute units it costs a whole extra round over the chip (4 pages
-      // of 8193 rows: 129 x 4 tiles of the down projection = 2.02 rounds).  Then the few rows go to the small-tile
-      // kernel in a launch of their own (rows are independent in every epilogue).
-      const int rem = M % 256;
-      if ((cfg == 8 || cfg == 6) && !ctx->gemm_cfg_forced && rem > 0 && rem <= 64) {
+      // Rounds over the chip.  The 256x256 kernel runs one tile per compute unit at a time, so a tile count just
+      // above a multiple of the number of units costs a whole extra round (4 pages of 8193 rows: 129 x 4 tiles of
+      // the down projection = 2.02 rounds; a prefill of 16,880 rows: 66 x 4 = 1.03 rounds).  When leaving out at most
+      // 512 rows saves that round, those rows go to the small-tile kernel in a launch of their own (rows are
+      // independent in every epilogue).  Costs in us from the measured per-tile times: a 256x256 tile 6 + 1.9 per K
+      // slice, a round of 64x128 tiles 6 + 0.3 per slice, a 256x128 tile 0.64 of a 256x256 one.
+      if ((cfg == 8 || cfg == 6) && !ctx->gemm_cfg_forced && K % 128 == 0 && K >= 256) {
         const int64_t cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
         const int64_t w_cols = site == kSiteGateUp ? 2 * static_cast<int64_t>(N) : N;
-        const int64_t tiles_w = cfg == 8 ? (w_cols + 255) / 256 : (w_cols + 127) / 128;
-        const int64_t full = M / 256;
-        if ((full * tiles_w + cu - 1) / cu < ((full + 1) * tiles_w + cu - 1) / cu &&
+        const int64_t tw8 = (w_cols + 255) / 256, tw_small = (w_cols + 127) / 128;
+        const int64_t r_all = (M + 255) / 256, rounds_all = (r_all * tw8 + cu - 1) / cu;
+        const int64_t r_main = std::min<int64_t>(M / 256, (rounds_all - 1) * cu / tw8);
+        const int64_t rem = M - 256 * r_main;
+        if (rounds_all >= 2 && r_main >= 1 && rem > 0 && rem <= 512 &&
             static_cast<int64_t>(M) * K * 2 < (int64_t{1} << 31) && w_cols * K * 2 < (int64_t{1} << 31)) {
-          const int m_main = M - rem;
-          const int rc = cfg == 8 ? launch_gemm_mfma8(st, m_main, N, K, A, W, epi, ctx->n_cu)
-                                  : launch_gemm_mfma<GemmCfg6>(st, m_main, N, K, A, W, epi);
-          if (rc != HSD_OK) return rc;
-          return launch_gemm_mfma_d<GemmCfgD64>(st, M, N, K, A, W, epi, m_main);
+          const double t8 = 6.0 + 1.9 * (K / 64), t_small = 6.0 + 0.3 * (K / 64);
+          const double cost_all = cfg == 8 ? rounds_all * t8 : ((r_all * tw_small + cu - 1) / cu) * 0.64 * t8;
+          const double cost_split = ((r_main * tw8 + cu - 1) / cu) * t8 +
+                                    ((((rem + 63) / 64) * tw_small + cu - 1) / cu) * t_small;
+          if (cost_split < 0.9 * cost_all) {
+            const int m_main = static_cast<int>(256 * r_main);
+            const int rc = launch_gemm_mfma8(st, m_main, N, K, A, W, epi, ctx->n_cu);
+            if (rc != HSD_OK) return rc;
+            return launch_gemm_mfma_d<GemmCfgD64>(st, M, N, K, A, W, epi, m_main);
+          }
         }
       }
     }
