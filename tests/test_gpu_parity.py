@@ -224,6 +224,34 @@ def test_random_shapes_against_oracle():
         run_rounds_parity(desc, weights, seed, specs, drafts, mode=mode, attn_key_chunk=chunk or None)
 
 
+def test_large_pass_dispatch_agrees_bitwise_with_plain_tiles():
+    """A pass of 16,880 rows (the shape of the prefix prefill) takes the dispatch paths that small batches never reach:
+    the persistent form of the 256x256 GEMM (gate/up: 528 tiles for 256 compute units) and the rounds-aware row split
+    (O and down: 66 x 4 tiles would be 1.03 rounds; 64 rows of tiles go to the large kernel, 496 rows to the small
+    one).  None of it may change a bit: arg-max rows and sampled logit rows equal those of the same pass forced onto
+    128x128 tiles everywhere."""
+    desc = W.ModelDesc(n_layers=2, d_model=1024, n_q_heads=16, n_kv_heads=4, head_dim=64, d_ffn=1024, vocab=1024, dtype="bf16")
+    seed = 21
+    weights = W.make_weights(desc, seed)
+    specs = [SequenceSpec(i, 3, 2, 4219, 0.0) for i in range(4)]
+    rng = np.random.default_rng(8)
+    drafts = [rng.integers(0, desc.vocab, size=sp.draft_len).astype(np.int32) for sp in specs]
+    total_q = sum(len(d) + 1 for d in drafts)
+    assert total_q == 16880
+    rows = np.unique(np.concatenate([np.arange(0, total_q, 97), np.arange(total_q - 600, total_q)])).astype(np.int32)
+    results = []
+    for debug in (None, {"gemm_cfg": (0, 0, 0, 0, 0)}):
+        eng = make_engine(desc, weights, specs, max_total_q=total_q, max_dump=len(rows), debug=debug)
+        pend = _gpu_prefill(eng, desc, seed, specs)
+        blocks = [np.concatenate([[p], d]).astype(np.int32) for p, d in zip(pend, drafts)]
+        out = eng.verify([0, 1, 2, 3], blocks, "page", dump_rows=rows)
+        results.append((out.argmax.cpu().numpy().copy(), out.logits.cpu().numpy().copy()))
+        eng.close()
+    np.testing.assert_array_equal(results[0][0], results[1][0])
+    np.testing.assert_array_equal(results[0][1], results[1][1])
+    assert np.isfinite(results[0][1]).all()
+
+
 def test_many_sequences_take_the_plain_task_order():
     """More sequences than the attention task table places group by group (over 1024 task groups: here 300 sequences
     x 4 kv heads) fall back to the plain task order; one pass of such a batch, ragged, against the oracle."""
