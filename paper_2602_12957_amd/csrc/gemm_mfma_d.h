@@ -26,16 +26,19 @@
 
 namespace hsd {
 
-template <int BP_, int BQ_, int STAGES_>
-struct GemmCfgD : GemmCfg<BP_, BQ_, 64, 2, 2> {
+template <int BP_, int BQ_, int STAGES_, int LW_ = 1, int WM_ = 2, int WN_ = 2>
+struct GemmCfgD : GemmCfg<BP_, BQ_, 64, WM_, WN_> {
   static constexpr int kStages = STAGES_;
+  static constexpr int kLoaderWaves = LW_;                         // requesting waves: 1, 2 or 4
   static constexpr int kStageBytes = (BP_ + BQ_) * 64 * 2;         // P rows, then Q rows, 128 bytes each
   static constexpr int kSmemBytes = STAGES_ * kStageBytes;         // operand stages; kRowScaleBytes more follow them
   static constexpr int kLoads = (BP_ + BQ_) / 8;                   // load instructions per slice (8 rows each)
-  static constexpr int kThreadsD = 320;                            // four multiplying waves and the requesting one
-  static_assert(BP_ % 64 == 0 && BQ_ % 128 == 0, "two wave rows of 32-row groups, two wave columns of 64-column groups");
+  static constexpr int kMulWaves = WM_ * WN_;                      // multiplying waves: 2 x 2, or 1 x 1 for tiny row counts
+  static constexpr int kThreadsD = 64 * (WM_ * WN_ + LW_);         // the multiplying waves and the requesting ones
+  static_assert((LW_ == 1 || LW_ == 2 || LW_ == 4) && ((BP_ + BQ_) / 8) % LW_ == 0, "requests divide evenly over the waves");
+  static_assert((BP_ / 8) % LW_ == 0, "every request slot of a wave is all P or all Q");
   static_assert(STAGES_ >= 3 && STAGES_ <= 6, "a slice being multiplied, one complete behind it, one to three in flight");
-  static_assert(4 * 32 * GemmCfg<BP_, BQ_, 64, 2, 2>::kEpiStride * 4 <= kSmemBytes, "epilogue staging must fit in the stages");
+  static_assert(WM_ * WN_ * 32 * GemmCfg<BP_, BQ_, 64, WM_, WN_>::kEpiStride * 4 <= kSmemBytes, "epilogue staging must fit in the stages");
 };
 
 typedef __attribute__((address_space(3))) unsigned char *LdsBytePtr;
@@ -50,17 +53,17 @@ __device__ __forceinline__ void lds_load16(__amdgpu_buffer_rsrc_t rs, LdsBytePtr
 // s_waitcnt vmcnt(N) with the other counters left alone (N < 64)
 #define HSD_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
 
-// grid: 1-D, tiles_act * tiles_w workgroups of 320 threads, Cfg::kSmemBytes + kRowScaleBytes dynamic LDS; the tiles
+// grid: 1-D, tiles_act * tiles_w workgroups of Cfg::kThreadsD threads, Cfg::kSmemBytes + kRowScaleBytes dynamic LDS; the tiles
 // cover rows m_base .. M-1 (a caller that gave the rows before m_base to another kernel passes their count, a
 // multiple of the tile height; otherwise 0).
 // K must be a multiple of 64; both matrices below 2 GiB (32-bit buffer offsets).
 // Every wave executes exactly K/64 + 1 workgroup barriers, whichever role it has.
 template <typename Cfg, int MODE, typename Epi>
-__global__ void __launch_bounds__(320) k_gemm_mfma_d(int M, int N, int K, int m_base, const bf16 *__restrict__ A,
+__global__ void __launch_bounds__(Cfg::kThreadsD) k_gemm_mfma_d(int M, int N, int K, int m_base, const bf16 *__restrict__ A,
                                                      const bf16 *__restrict__ W, Epi epi) {
   static_assert(MODE == kModeNormal || MODE == kModeDual, "normal or dual mode");
   constexpr int BP = Cfg::BP, BQ = Cfg::BQ, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN, S = Cfg::kStages;
-  constexpr int ROWB = BK * 2, NL = Cfg::kLoads;
+  constexpr int ROWB = BK * 2, LW = Cfg::kLoaderWaves, NL = Cfg::kLoads / LW;   // NL: requests per wave and slice
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
   const int t = threadIdx.x, lane = t & 63;
@@ -71,17 +74,20 @@ __global__ void __launch_bounds__(320) k_gemm_mfma_d(int M, int N, int K, int m_
   const int m0 = m_base + ta * BP, n0 = tw * ((MODE == kModeDual) ? BQ / 2 : BQ);
   const int nk = K / BK;
 
-  if (wave == 4) {
-    // ---- the requesting wave.  Instruction i of a slice covers tile rows 8 i .. 8 i + 7 (P rows, then Q rows); lane l
+  if (wave >= Cfg::kMulWaves) {
+    // ---- a requesting wave.  Instruction i of a slice covers tile rows 8 i .. 8 i + 7 (P rows, then Q rows); lane l
     // fetches, for row 8 i + l / 8, the piece that belongs at position l & 7.  Rows past the end of a matrix re-read
-    // its last row (their products are never stored).
+    // its last row (their products are never stored).  With LW requesting waves, wave w takes the instructions
+    // i = w, w + LW, ...: each wave's loads return in order, so several waves are several independent streams.
+    const int lw = wave - Cfg::kMulWaves;
     const LdsBytePtr lds = (LdsBytePtr)smem_raw;
     const int w_rows = (MODE == kModeDual) ? 2 * N : N;
     const __amdgpu_buffer_rsrc_t rs_p = make_rsrc(A, static_cast<size_t>(M) * K * 2);
     const __amdgpu_buffer_rsrc_t rs_q = make_rsrc(W, static_cast<size_t>(w_rows) * K * 2);
     int voff[NL];
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
+    for (int j = 0; j < NL; ++j) {
+      const int i = j * LW + lw;
       const int r = (i < BP / 8 ? 8 * i : 8 * i - BP) + (lane >> 3);   // row of the P or of the Q tile
       const int kc = (lane & 7) ^ ((r >> 1) & 7);
       int row;
@@ -95,14 +101,14 @@ __global__ void __launch_bounds__(320) k_gemm_mfma_d(int M, int N, int K, int m_
       } else {
         row = min(n0 + r, N - 1);
       }
-      voff[i] = (row * K + kc * 8) * 2;
+      voff[j] = (row * K + kc * 8) * 2;
     }
 #define HSD_GD_ISSUE(stage, slice)                                                                   \
   {                                                                                                  \
     const int kbyte = (slice) * BK * 2;                                                              \
     const LdsBytePtr dst = lds + (stage) * Cfg::kStageBytes;                                         \
-    _Pragma("unroll") for (int i = 0; i < NL; ++i)                                                   \
-        lds_load16(i < BP / 8 ? rs_p : rs_q, dst + i * 1024, voff[i], kbyte);                        \
+    _Pragma("unroll") for (int j = 0; j < NL; ++j)                                                   \
+        lds_load16(j < BP / 8 / LW ? rs_p : rs_q, dst + (j * LW + lw) * 1024, voff[j], kbyte);      \
   }
     // Wait until all but the `n_ahead` most recent slices have landed (the counter holds 63 loads at most: asking
     // for more to stay in flight than it can count only waits for a few loads more than necessary)
@@ -135,7 +141,7 @@ __global__ void __launch_bounds__(320) k_gemm_mfma_d(int M, int N, int K, int m_
 
   // ---- the multiplying waves
   const int wi = wave / Cfg::WN, wj = wave % Cfg::WN;
-  gemm_row_scales<Cfg, MODE>(epi, M, m0, t, 256, smem_raw);
+  gemm_row_scales<Cfg, MODE>(epi, M, m0, t, 64 * Cfg::kMulWaves, smem_raw);
   floatx16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)

@@ -440,7 +440,8 @@ def test_tile_configurations_agree_bitwise():
     drafts = [rng.integers(0, desc.vocab, size=sp.draft_len).astype(np.int32) for sp in specs]
     results = []
     for debug in (None, {"gemm_cfg": (5, 2, 8, 8, 8)}, {"gemm_cfg": (7, 9, 7, 9, 0)}, {"gemm_cfg": (0, 0, 0, 6, 1)},
-                  {"gemm_cfg": (10, 10, 10, 10, 0)}, {"gemm_cfg": (11, 11, 11, 11, 0)}):
+                  {"gemm_cfg": (10, 10, 10, 10, 0)}, {"gemm_cfg": (11, 11, 11, 11, 0)},
+                  {"gemm_cfg": (12, 12, 12, 12, 0)}):
         eng = make_engine(desc, weights, specs, max_total_q=256, max_dump=256, debug=debug)
         pend = _gpu_prefill(eng, desc, seed, specs)
         blocks = [np.concatenate([[p], d]).astype(np.int32) for p, d in zip(pend, drafts)]
