@@ -37,7 +37,7 @@ struct GemmCfgD : GemmCfg<BP_, BQ_, 64, WM_, WN_> {
   static constexpr int kThreadsD = 64 * (WM_ * WN_ + LW_);         // the multiplying waves and the requesting ones
   static_assert((LW_ == 1 || LW_ == 2 || LW_ == 4) && ((BP_ + BQ_) / 8) % LW_ == 0, "requests divide evenly over the waves");
   static_assert((BP_ / 8) % LW_ == 0, "every request slot of a wave is all P or all Q");
-  static_assert(STAGES_ >= 3 && STAGES_ <= 6, "a slice being multiplied, one complete behind it, one to three in flight");
+  static_assert(STAGES_ >= 3 && STAGES_ <= 12, "a slice being multiplied, one complete behind it, one to nine in flight");
   static_assert(WM_ * WN_ * 32 * GemmCfg<BP_, BQ_, 64, WM_, WN_>::kEpiStride * 4 <= kSmemBytes, "epilogue staging must fit in the stages");
 };
 
@@ -112,12 +112,12 @@ __global__ void __launch_bounds__(Cfg::kThreadsD) k_gemm_mfma_d(int M, int N, in
   }
     // Wait until all but the `n_ahead` most recent slices have landed (the counter holds 63 loads at most: asking
     // for more to stay in flight than it can count only waits for a few loads more than necessary)
-#define HSD_GD_WAIT(n_ahead)                                                   \
-  switch (n_ahead) {                                                           \
-    case 0: HSD_VMCNT(0); break;                                               \
-    case 1: HSD_VMCNT(NL < 63 ? NL : 63); break;                               \
-    case 2: HSD_VMCNT(2 * NL < 63 ? 2 * NL : 63); break;                       \
-    default: HSD_VMCNT(3 * NL < 63 ? 3 * NL : 63); break;                      \
+#define HSD_GD_WAIT_CASE(n) case n: HSD_VMCNT((n) * NL < 63 ? (n) * NL : 63); break;
+#define HSD_GD_WAIT(n_ahead)                                                                         \
+  switch (n_ahead) {                                                                                 \
+    HSD_GD_WAIT_CASE(0) HSD_GD_WAIT_CASE(1) HSD_GD_WAIT_CASE(2) HSD_GD_WAIT_CASE(3) HSD_GD_WAIT_CASE(4)  \
+    HSD_GD_WAIT_CASE(5) HSD_GD_WAIT_CASE(6) HSD_GD_WAIT_CASE(7) HSD_GD_WAIT_CASE(8)                  \
+    default: HSD_VMCNT(9 * NL < 63 ? 9 * NL : 63); break;                                            \
   }
 #pragma unroll
     for (int s = 0; s < S - 1; ++s)
@@ -136,6 +136,7 @@ __global__ void __launch_bounds__(Cfg::kThreadsD) k_gemm_mfma_d(int M, int N, in
     __builtin_amdgcn_s_barrier();   // every load has landed (the last wait was for all of them)
 #undef HSD_GD_ISSUE
 #undef HSD_GD_WAIT
+#undef HSD_GD_WAIT_CASE
     return;
   }
 
