@@ -243,7 +243,7 @@ int hsd_profile_read(hsd_ctx *ctx, int32_t *n_launches, float *total_ms);
  *   HSD_DEBUG_SYNC_LAYERS   value != 0: the verify/prefill calls WAIT for the stream after every layer (an
  *                           exception to "never synchronises"; bounds the launches in flight for counter tools)
  *   HSD_DEBUG_FORCE_SIMPLE  value != 0: bf16 models run the plain fp32-FMA kernels (cross-check of the MFMA path)
- *   HSD_DEBUG_GEMM_CFG_*    tile configuration (0..12) of one GEMM call site, used for every row count
+ *   HSD_DEBUG_GEMM_CFG_*    tile configuration (0..13) of one GEMM call site, used for every row count
  * Returns HSD_EINVAL for an unknown knob or a value out of range. */
 enum {
   HSD_DEBUG_SYNC_LAYERS = 1,

@@ -239,6 +239,7 @@ using GemmCfgD64 = GemmCfgD<64, 128, 5, 2>;    // two requesting waves: two inde
 using GemmCfgD128 = GemmCfgD<128, 128, 4, 4>;
 // 12 = the same kernel with ONE multiplying wave on a 32x64 tile (token-by-token decoding, see effective_gemm_cfg)
 using GemmCfgD32 = GemmCfgD<32, 64, 6, 2, 1, 1>;
+using GemmCfgD64n = GemmCfgD<64, 64, 6, 2, 2, 1>;   // 13: two multiplying waves on a 64x64 tile
 
 
 // Tile configuration actually used at a call site for a given problem (the launch and everything sized from the
@@ -247,7 +248,7 @@ template <typename T>
 int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K) {
   if (!std::is_same<T, bf16>::value || ctx->force_simple || K % 64 != 0) return -1;
   int cfg = ctx->gemm_cfg[site];
-  if (cfg < 0 || cfg > 12) cfg = 0;
+  if (cfg < 0 || cfg > 13) cfg = 0;
   // The tile shape never changes a result bit (every output element sums its K slices in the same order), so it
   // may follow the row count and the path stays batch-invariant.  A kernel's time is set by one workgroup's walk
   // over K plus fixed costs as long as the launch fits the chip in one round, so fewer rows take smaller tiles: more
@@ -260,12 +261,17 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K) {
     // it wins there too when the operands are cache resident (25.7 against 28.3).
     // At ~4 k rows the 128x128 tile of the same kernel (11) yields one workgroup per compute unit on the square
     // projections and wins there (4096 x 1024, K = 4096: 47.3 us against 56.5).
-    // Up to 32 rows (token-by-token decoding) the weights are all there is to read, from HBM, and a compute unit
-    // keeps only so many cache-line misses in flight (deeper rings and more requesting waves change nothing: the
-    // down projection's 8 workgroups of 64x128 tiles stream at 0.34 TB/s): what helps is more compute units, i.e.
-    // narrower tiles -- 32x64 with one multiplying wave (12).
+    // With few rows the weights are all there is to read, from HBM, and a compute unit streams them at a rate that
+    // neither deeper rings nor more requesting waves raise (the down projection's 8 workgroups of 64x128 tiles at 16
+    // rows: 0.34 TB/s): what helps is more compute units, i.e. narrower tiles, as long as the launch stays within one
+    // workgroup per unit -- 32x64 tiles with one multiplying wave (12), else 64x64 with two (13).  Measured with
+    // operands from HBM, K = 4096, N = 1024: 16 rows 15.6 us (64x128: 24.5), 512 rows 18.6 (31.0), 1024 rows 23.6 with
+    // 64x64 (32.4; two-role kernel 30.0); K = 1024, N = 1536: 256 rows 6.8 (8.3), 512 rows 9.9 with 64x64 (12.3).
+    const int64_t cu_n = ctx->n_cu > 0 ? ctx->n_cu : 256;
+    const int64_t cols64 = ((site == kSiteGateUp ? 2 * static_cast<int64_t>(N) : N) + 63) / 64;
     if (site == kSiteLM) cfg = M <= 128 ? 0 : cfg;
-    else if (M <= 32) cfg = 12;
+    else if (static_cast<int64_t>((M + 31) / 32) * cols64 <= cu_n) cfg = 12;
+    else if (static_cast<int64_t>((M + 63) / 64) * cols64 <= cu_n) cfg = 13;
     else if (M <= 64) cfg = 10;                                        // one row tile
     else if (site != kSiteGateUp && M <= 512) cfg = 10;
     else if ((site == kSiteO || site == kSiteDown) && M >= 3072) cfg = 11;
@@ -286,7 +292,7 @@ int effective_gemm_cfg(const hsd_ctx *ctx, int site, int M, int N, int K) {
   // the two-role kernels: not for the swapped LM-head mode
   if ((cfg == 7 || cfg == 9) && site == kSiteLM) cfg = cfg == 7 ? 0 : 2;
   // the LDS-direct kernels: not the swapped mode, 32-bit operand offsets
-  if ((cfg == 10 || cfg == 11 || cfg == 12) &&
+  if ((cfg == 10 || cfg == 11 || cfg == 12 || cfg == 13) &&
       (site == kSiteLM || static_cast<int64_t>(M) * K * 2 >= (int64_t{1} << 31) ||
        (site == kSiteGateUp ? 2 : 1) * static_cast<int64_t>(N) * K * 2 >= (int64_t{1} << 31)))
     cfg = cfg == 11 ? 0 : 2;
@@ -334,6 +340,10 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
             const int m_main = static_cast<int>(256 * r_main);
             const int rc = launch_gemm_mfma8(st, m_main, N, K, A, W, epi, ctx->n_cu);
             if (rc != HSD_OK) return rc;
+            // the narrowest tile that still gives at most one workgroup per compute unit (see effective_gemm_cfg)
+            const int64_t cols64 = (w_cols + 63) / 64;
+            if (((rem + 31) / 32) * cols64 <= cu) return launch_gemm_mfma_d<GemmCfgD32>(st, M, N, K, A, W, epi, m_main);
+            if (((rem + 63) / 64) * cols64 <= cu) return launch_gemm_mfma_d<GemmCfgD64n>(st, M, N, K, A, W, epi, m_main);
             return launch_gemm_mfma_d<GemmCfgD64>(st, M, N, K, A, W, epi, m_main);
           }
         }
@@ -367,6 +377,10 @@ int launch_gemm(const hsd_ctx *ctx, hipStream_t st, int site, int M, int N, int 
       case 12:
         if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
           return launch_gemm_mfma_d<GemmCfgD32>(st, M, N, K, A, W, epi);
+        break;
+      case 13:
+        if constexpr (GemmModeOf<Epi>::value != kModeSwapLM)
+          return launch_gemm_mfma_d<GemmCfgD64n>(st, M, N, K, A, W, epi);
         break;
       default: return launch_gemm_mfma<GemmCfg0>(st, M, N, K, A, W, epi);
     }
@@ -751,7 +765,7 @@ int hsd_debug_set(hsd_ctx *c, int knob, int64_t value) {
     case HSD_DEBUG_GEMM_CFG_GATE_UP:
     case HSD_DEBUG_GEMM_CFG_DOWN:
     case HSD_DEBUG_GEMM_CFG_LM_HEAD:
-      if (value < 0 || value > 12) return HSD_EINVAL;
+      if (value < 0 || value > 13) return HSD_EINVAL;
       c->gemm_cfg[knob - HSD_DEBUG_GEMM_CFG_QKV] = static_cast<int>(value);
       c->gemm_cfg_forced = true;
       return HSD_OK;

@@ -441,7 +441,7 @@ def test_tile_configurations_agree_bitwise():
     results = []
     for debug in (None, {"gemm_cfg": (5, 2, 8, 8, 8)}, {"gemm_cfg": (7, 9, 7, 9, 0)}, {"gemm_cfg": (0, 0, 0, 6, 1)},
                   {"gemm_cfg": (10, 10, 10, 10, 0)}, {"gemm_cfg": (11, 11, 11, 11, 0)},
-                  {"gemm_cfg": (12, 12, 12, 12, 0)}):
+                  {"gemm_cfg": (12, 12, 12, 12, 0)}, {"gemm_cfg": (13, 13, 13, 13, 0)}):
         eng = make_engine(desc, weights, specs, max_total_q=256, max_dump=256, debug=debug)
         pend = _gpu_prefill(eng, desc, seed, specs)
         blocks = [np.concatenate([[p], d]).astype(np.int32) for p, d in zip(pend, drafts)]
